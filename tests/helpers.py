@@ -1,0 +1,59 @@
+"""Test-side reference formulations that are independent of oracle/ (numpy, float64)."""
+from __future__ import annotations
+
+import numpy as np
+from scipy.special import expit, softmax
+
+from workloads import bf16_bits_to_f32
+
+
+def f64(bits):
+    return bf16_bits_to_f32(np.asarray(bits, dtype=np.uint16)).astype(np.float64)
+
+
+def split_expert(w_bits, i, M, H):
+    """(Wg [H,M], Wu [H,M], Wd [M,H]) of expert i as float64."""
+    sz = 3 * H * M
+    w = f64(np.asarray(w_bits).reshape(-1)[i * sz:(i + 1) * sz])
+    return (w[:H * M].reshape(H, M), w[H * M:2 * H * M].reshape(H, M),
+            w[2 * H * M:].reshape(M, H))
+
+
+def dense_ffn(X, Wg, Wu, Wd):
+    """Textbook SwiGLU feed-forward on all rows of X with library matmuls."""
+    g = X @ Wg.T
+    u = X @ Wu.T
+    return (g * expit(g) * u) @ Wd.T
+
+
+def topk_by_sort(logits_row, k):
+    """Explicit full sort: larger score first, equal scores -> lower index first."""
+    order = sorted(range(len(logits_row)), key=lambda e: (-float(logits_row[e]), e))
+    return order[:k]
+
+
+def brute_force_layer(tokens_bits, logits, routed_bits, shared_bits, *, M, H, E, e0, El,
+                      Ns, Hs, k):
+    """Dense-masked MoE layer: every local expert on every token, masked by the gate."""
+    X = f64(tokens_bits)
+    T = X.shape[0]
+    P = softmax(np.asarray(logits, dtype=np.float64), axis=1)
+    G = np.zeros((T, E))
+    for t in range(T):
+        sel = topk_by_sort(logits[t], k)
+        G[t, sel] = P[t, sel] / P[t, sel].sum()
+    out = np.zeros((T, M))
+    for e in range(El):
+        out += G[:, e0 + e, None] * dense_ffn(X, *split_expert(routed_bits, e, M, H))
+    for i in range(Ns):
+        out += dense_ffn(X, *split_expert(shared_bits, i, M, Hs))
+    return out, G
+
+
+def rel_err(got, ref):
+    """max_i |got - ref| / max(|ref_i|, rms(ref)): the parity figure used everywhere."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    rms = float(np.sqrt(np.mean(ref * ref))) if ref.size else 0.0
+    den = np.maximum(np.abs(ref), max(rms, 1e-30))
+    return float(np.max(np.abs(got - ref) / den)) if ref.size else 0.0
