@@ -1,0 +1,169 @@
+/*
+ * moe_ep.h -- C ABI of the expert-group side of one MoE layer on one MI355X.
+ *
+ * The library runs, for the experts one GPU of the expert group holds, the
+ * part of a mixture-of-experts layer that fine-grained disaggregated expert
+ * parallelism schedules: gate softmax + top-k (Sec. 2.1), partition of the
+ * tokens by expert (Sec. 2.1; Sec. 3.1 "The MoE Part"), the three projections
+ * of each routed expert (Sec. 3.1, Eq. moe_detail), the weighted aggregation
+ * of the selected experts' outputs (Sec. 2.1), the optional shared experts
+ * (Sec. 3.1, Eq. shared_detail), all cut along the token dimension into
+ * r_2 = r_chunks pieces (Sec. 2.3) whose transfers and compute overlap.
+ *
+ * Plain C: no C++ types, no exceptions, nothing from PyTorch crosses this
+ * boundary.  Every function returns a moe_ep_status (0 = OK, negative = error)
+ * unless stated otherwise, never aborts, and validates its arguments before
+ * the first HIP call.
+ *
+ * Notation (Table "Notations"): M hidden size, H expert intermediate size,
+ * E global experts, top_k experts per token, r_2 chunks.
+ */
+#ifndef MOE_EP_H
+#define MOE_EP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct moe_ep_ctx moe_ep_ctx; /* opaque, owned by the library */
+
+typedef enum {
+    MOE_EP_OK = 0,
+    MOE_EP_EINVAL = -1, /* bad argument; nothing was launched               */
+    MOE_EP_ENOMEM = -2, /* host or device allocation failed                 */
+    MOE_EP_EHIP = -3,   /* a HIP call failed (see moe_ep_last_error)        */
+    MOE_EP_ESTATE = -4  /* call not valid in the context's current state    */
+} moe_ep_status;
+
+/* Where the shared experts run relative to the routed chunks (Sec. 4.2,
+ * "Determine the order of Attention and Shared Expert", reduced to the one
+ * GPU this library drives).  The result does not depend on the order. */
+typedef enum {
+    MOE_EP_ORDER_SHARED_FIRST = 0, /* shared experts on all tokens, then the routed chunks:
+                                      the shared expert treated as part of what precedes the
+                                      transfer (Sec. 2.3, first limitation)                 */
+    MOE_EP_ORDER_INTERLEAVED = 1   /* shared experts of chunk j issued next to routed chunk j */
+} moe_ep_order;
+
+/* Where tokens / gate_logits / out live.  Weights are always in device memory. */
+typedef enum {
+    MOE_EP_IO_DEVICE = 0,     /* device pointers; no copies are made                        */
+    MOE_EP_IO_PINNED_HOST = 1 /* pinned host pointers; each chunk is copied in and out on
+                                 its own streams, standing in for the A2E / E2A transfers
+                                 (Sec. 2.2; Eq. a2e_detail)                                 */
+} moe_ep_io;
+
+typedef struct {
+    int32_t hidden;       /* M; multiple of 64                                              */
+    int32_t inter;        /* H of a routed expert; multiple of 64                           */
+    int32_t n_experts;    /* E, size of the gate's expert axis; 1..512                      */
+    int32_t local_begin;  /* first expert held here; experts [local_begin, +n_local)        */
+    int32_t n_local;      /* E/eg experts held here; >= 1                                   */
+    int32_t n_shared;     /* N_shared; 0 = no shared expert                                 */
+    int32_t shared_inter; /* H of each shared expert; multiple of 64 (ignored if none)      */
+    int32_t max_tokens;   /* largest n_tokens of a forward; sizes the workspaces            */
+    int32_t max_top_k;    /* largest top_k of a forward; 1..min(E, 64)                      */
+    int32_t max_chunks;   /* largest r_chunks of a forward; 1..64                           */
+    int32_t io_mode;      /* moe_ep_io                                                      */
+    int32_t device;       /* HIP device ordinal                                             */
+} moe_ep_config;
+
+/* Pure host checks, usable without a GPU.  Return MOE_EP_OK or MOE_EP_EINVAL; if
+ * `why` is not NULL it receives a static string naming the first violated rule. */
+int moe_ep_validate_config(const moe_ep_config *cfg, const char **why);
+int moe_ep_validate_forward(const moe_ep_config *cfg, const void *tokens,
+                            const float *gate_logits, const void *routed_w,
+                            const void *shared_w, int32_t top_k, int32_t r_chunks,
+                            int32_t order, int32_t n_tokens, const void *out,
+                            const char **why);
+
+/* Device bytes moe_ep_create will allocate for this configuration (0 if invalid). */
+size_t moe_ep_workspace_bytes(const moe_ep_config *cfg);
+
+/* Create a context: selects cfg->device, allocates all workspaces, streams and
+ * events once.  *out_ctx is set only on success.  Not thread-safe per context. */
+int moe_ep_create(const moe_ep_config *cfg, moe_ep_ctx **out_ctx);
+
+/*
+ * One pass of the layer over n_tokens tokens.
+ *
+ *   tokens      bf16 [n_tokens, M] row-major
+ *   gate_logits fp32 [n_tokens, E] row-major: routing scores over the GLOBAL expert axis.
+ *               Per token the top_k largest scores are selected (equal scores: lower
+ *               expert index first), their softmax weights renormalised to sum 1;
+ *               assignments to experts outside [local_begin, local_begin + n_local) are
+ *               dropped without renormalising (they belong to another GPU).
+ *               NaN / Inf scores are not supported.
+ *   routed_w    bf16, device: for each local expert, contiguous, W_gate [H, M],
+ *               W_up [H, M], W_down [M, H], all row-major (Sec. 3.1); experts contiguous.
+ *   shared_w    bf16, device: the same triple for each shared expert with H = shared_inter;
+ *               NULL exactly when n_shared == 0.
+ *   top_k       1..min(E, max_top_k);   r_chunks 1..max_chunks: the token range is cut
+ *               into r_chunks contiguous pieces of ceil(n_tokens / r_chunks) tokens (the
+ *               last ones may be short or empty);   order: moe_ep_order (ignored when
+ *               n_shared == 0).
+ *   out         bf16 [n_tokens, M]: sum over kept slots of weight * expert(token) plus the
+ *               sum of the shared experts; tokens with nothing kept and no shared expert
+ *               get zeros.  Accumulation is fp32; the activation between the up and down
+ *               projections and each expert's output are rounded to bf16 once.
+ *   stream      hipStream_t (NULL = the default stream).  The call only enqueues work:
+ *               it starts after everything already on `stream` and `stream` is made to
+ *               wait for its completion.  Buffers must stay valid until then.
+ *
+ * tokens / gate_logits / out are device pointers in MOE_EP_IO_DEVICE mode and pinned host
+ * pointers in MOE_EP_IO_PINNED_HOST mode.  The caller owns every buffer passed in; the
+ * library owns its workspaces.  n_tokens == 0 is a no-op.  Results are deterministic:
+ * the same inputs give the same bits, for every r_chunks and order.
+ */
+int moe_ep_forward(moe_ep_ctx *ctx, const void *tokens, const float *gate_logits,
+                   const void *routed_w, const void *shared_w, int32_t top_k,
+                   int32_t r_chunks, int32_t order, int32_t n_tokens, void *out,
+                   void *stream);
+
+/*
+ * Test / inspection surface: host copies of what the last forward computed for chunk
+ * `chunk` (synchronises the context's streams).  Any pointer may be NULL.  With
+ * Tc = ceil(n_tokens / r_chunks) and Tn the tokens of this chunk:
+ *   idx    int32 [Tn, top_k] selected global expert ids, best first
+ *   w      fp32  [Tn, top_k] routing weights
+ *   pos    int32 [Tn, top_k] row of the assignment in the grouped input, -1 if dropped
+ *   count  int32 [n_local]   rows per local expert
+ *   offset int32 [n_local+1] exclusive prefix sum of count
+ *   perm   int32 [offset[n_local]] row -> assignment id (chunk-local token * top_k + slot);
+ *          rows are grouped by expert and ascend by token inside an expert
+ * The caller sizes perm for Tn * top_k entries.  Returns MOE_EP_ESTATE before any forward.
+ */
+int moe_ep_get_routing(moe_ep_ctx *ctx, int32_t chunk, int32_t *idx, float *w, int32_t *pos,
+                       int32_t *count, int32_t *offset, int32_t *perm);
+
+/*
+ * Per-stage device time, in milliseconds, measured with HIP events on the streams the stages
+ * run on.  moe_ep_set_profiling(ctx, depth) makes the next `depth` forwards (0..256; 0 = off)
+ * record an event before and after every stage; this serialises nothing.
+ * moe_ep_get_stage_ms synchronises, returns the per-forward AVERAGE over the forwards recorded
+ * since the last call, and opens a new window of `depth` forwards:
+ *   ms[0] gate  ms[1] partition (scan + permute + row gather)  ms[2] routed gate/up GEMM
+ *   ms[3] routed down GEMM  ms[4] shared gate/up GEMM  ms[5] shared down GEMM
+ *   ms[6] aggregation  ms[7] whole forward (first enqueue to last completion)
+ * each summed over the chunks of a forward.  n = floats the caller provides (<= 8 written).
+ * Returns MOE_EP_ESTATE when nothing was recorded.
+ */
+int moe_ep_set_profiling(moe_ep_ctx *ctx, int32_t depth);
+int moe_ep_get_stage_ms(moe_ep_ctx *ctx, float *ms, int32_t n);
+
+/* Last error text of this context (never NULL; valid until the next call on it). */
+const char *moe_ep_last_error(const moe_ep_ctx *ctx);
+
+/* Release everything the context owns.  NULL is allowed. */
+int moe_ep_destroy(moe_ep_ctx *ctx);
+
+/* Library version, "major.minor". */
+const char *moe_ep_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOE_EP_H */

@@ -1,0 +1,13 @@
+"""MI355X-native expert-group side of one MoE layer (FinDEP hot path).
+
+The work is done by hand-written HIP kernels in ``libmoe_ep.so`` behind the C ABI of
+``include/moe_ep.h``; this package only marshals arguments.  There is no CPU fallback:
+if the library has not been built, importing the binding raises.
+"""
+from .binding import (IO_DEVICE, IO_PINNED_HOST, ORDER_INTERLEAVED, ORDER_SHARED_FIRST, STAGES,
+                      MoeEp, MoeEpConfig, MoeEpError, lib_path, load_library, validate_config,
+                      validate_forward, workspace_bytes)
+
+__all__ = ["MoeEp", "MoeEpConfig", "MoeEpError", "load_library", "lib_path", "validate_config",
+           "validate_forward", "workspace_bytes", "ORDER_SHARED_FIRST", "ORDER_INTERLEAVED",
+           "IO_DEVICE", "IO_PINNED_HOST", "STAGES"]

@@ -1,0 +1,193 @@
+"""ctypes binding of include/moe_ep.h -- same names, argument marshalling only."""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Dict, Optional, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libmoe_ep.so")
+_lib: Optional[ctypes.CDLL] = None
+
+ORDER_SHARED_FIRST = 0
+ORDER_INTERLEAVED = 1
+IO_DEVICE = 0
+IO_PINNED_HOST = 1
+STAGES = ("router", "partition", "routed_gate_up_gemm", "routed_down_gemm",
+          "shared_gate_up_gemm", "shared_down_gemm", "aggregation", "forward")
+
+_STATUS = {0: "OK", -1: "EINVAL", -2: "ENOMEM", -3: "EHIP", -4: "ESTATE"}
+
+
+class MoeEpError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"moe_ep: {_STATUS.get(code, code)}: {msg}")
+        self.code = code
+
+
+class MoeEpConfig(ctypes.Structure):
+    """Mirror of ``moe_ep_config``."""
+    _fields_ = [(n, ctypes.c_int32) for n in (
+        "hidden", "inter", "n_experts", "local_begin", "n_local", "n_shared", "shared_inter",
+        "max_tokens", "max_top_k", "max_chunks", "io_mode", "device")]
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def load_library() -> ctypes.CDLL:
+    """Load libmoe_ep.so; raises if it has not been built (there is no fallback path)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(f"{_LIB_PATH} is missing: run `python -m paper_2512_21487_amd.build` "
+                          "(hipcc, gfx950) first")
+    lib = ctypes.CDLL(_LIB_PATH)
+    vp, i32 = ctypes.c_void_p, ctypes.c_int32
+    cfgp = ctypes.POINTER(MoeEpConfig)
+    lib.moe_ep_version.restype = ctypes.c_char_p
+    lib.moe_ep_version.argtypes = []
+    lib.moe_ep_validate_config.restype = ctypes.c_int
+    lib.moe_ep_validate_config.argtypes = [cfgp, ctypes.POINTER(ctypes.c_char_p)]
+    lib.moe_ep_validate_forward.restype = ctypes.c_int
+    lib.moe_ep_validate_forward.argtypes = [cfgp, vp, vp, vp, vp, i32, i32, i32, i32, vp,
+                                            ctypes.POINTER(ctypes.c_char_p)]
+    lib.moe_ep_workspace_bytes.restype = ctypes.c_size_t
+    lib.moe_ep_workspace_bytes.argtypes = [cfgp]
+    lib.moe_ep_create.restype = ctypes.c_int
+    lib.moe_ep_create.argtypes = [cfgp, ctypes.POINTER(vp)]
+    lib.moe_ep_forward.restype = ctypes.c_int
+    lib.moe_ep_forward.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, vp, vp]
+    lib.moe_ep_get_routing.restype = ctypes.c_int
+    lib.moe_ep_get_routing.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp]
+    lib.moe_ep_set_profiling.restype = ctypes.c_int
+    lib.moe_ep_set_profiling.argtypes = [vp, i32]
+    lib.moe_ep_get_stage_ms.restype = ctypes.c_int
+    lib.moe_ep_get_stage_ms.argtypes = [vp, vp, i32]
+    lib.moe_ep_last_error.restype = ctypes.c_char_p
+    lib.moe_ep_last_error.argtypes = [vp]
+    lib.moe_ep_destroy.restype = ctypes.c_int
+    lib.moe_ep_destroy.argtypes = [vp]
+    _lib = lib
+    return lib
+
+
+def _ptr(x) -> Optional[int]:
+    """Raw address of a torch tensor / numpy array / int / None."""
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    if hasattr(x, "data_ptr"):
+        return x.data_ptr()
+    if isinstance(x, np.ndarray):
+        return x.ctypes.data
+    raise TypeError(f"cannot take the address of {type(x)}")
+
+
+def validate_config(cfg: MoeEpConfig) -> Tuple[int, str]:
+    why = ctypes.c_char_p()
+    rc = load_library().moe_ep_validate_config(ctypes.byref(cfg), ctypes.byref(why))
+    return rc, (why.value or b"").decode()
+
+
+def validate_forward(cfg: MoeEpConfig, tokens, gate_logits, routed_w, shared_w, top_k: int,
+                     r_chunks: int, order: int, n_tokens: int, out) -> Tuple[int, str]:
+    why = ctypes.c_char_p()
+    rc = load_library().moe_ep_validate_forward(
+        ctypes.byref(cfg), _ptr(tokens), _ptr(gate_logits), _ptr(routed_w), _ptr(shared_w),
+        top_k, r_chunks, order, n_tokens, _ptr(out), ctypes.byref(why))
+    return rc, (why.value or b"").decode()
+
+
+def workspace_bytes(cfg: MoeEpConfig) -> int:
+    return int(load_library().moe_ep_workspace_bytes(ctypes.byref(cfg)))
+
+
+class MoeEp:
+    """Owns one ``moe_ep_ctx``.  Tensors are torch tensors (or raw addresses) that the caller
+    allocated; nothing is computed on the Python side."""
+
+    def __init__(self, *, hidden: int, inter: int, n_experts: int, n_local: int, max_tokens: int,
+                 max_top_k: int, local_begin: int = 0, n_shared: int = 0, shared_inter: int = 0,
+                 max_chunks: int = 8, io_mode: int = IO_DEVICE, device: int = 0):
+        self._lib = load_library()
+        self.cfg = MoeEpConfig(hidden, inter, n_experts, local_begin, n_local, n_shared,
+                               shared_inter, max_tokens, max_top_k, max_chunks, io_mode, device)
+        self._ctx = ctypes.c_void_p()
+        rc, why = validate_config(self.cfg)
+        if rc != 0:
+            raise MoeEpError(rc, why)
+        rc = self._lib.moe_ep_create(ctypes.byref(self.cfg), ctypes.byref(self._ctx))
+        if rc != 0:
+            self._ctx = ctypes.c_void_p()
+            raise MoeEpError(rc, "moe_ep_create failed (no usable HIP device or out of memory)")
+        self._last = (0, 0, 0)
+
+    # -- moe_ep_forward -------------------------------------------------------------------
+    def forward(self, tokens, gate_logits, routed_w, shared_w, top_k: int, r_chunks: int = 1,
+                order: int = ORDER_SHARED_FIRST, n_tokens: Optional[int] = None, out=None,
+                stream: Optional[int] = None) -> int:
+        if n_tokens is None:
+            n_tokens = int(tokens.shape[0])
+        if stream is None:
+            import torch
+            stream = torch.cuda.current_stream().cuda_stream
+        rc = self._lib.moe_ep_forward(self._ctx, _ptr(tokens), _ptr(gate_logits), _ptr(routed_w),
+                                      _ptr(shared_w), top_k, r_chunks, order, n_tokens, _ptr(out),
+                                      stream)
+        if rc != 0:
+            raise MoeEpError(rc, self.last_error())
+        self._last = (n_tokens, top_k, r_chunks)
+        return rc
+
+    # -- moe_ep_get_routing ---------------------------------------------------------------
+    def get_routing(self, chunk: int = 0) -> Dict[str, np.ndarray]:
+        T, k, r = self._last
+        Tc = (T + r - 1) // r if r else 0
+        t0 = chunk * Tc
+        Tn = 0 if t0 >= T else min(Tc, T - t0)
+        El = self.cfg.n_local
+        idx = np.zeros((Tn, k), dtype=np.int32)
+        w = np.zeros((Tn, k), dtype=np.float32)
+        pos = np.full((Tn, k), -1, dtype=np.int32)
+        count = np.zeros(El, dtype=np.int32)
+        offset = np.zeros(El + 1, dtype=np.int32)
+        perm = np.full(max(Tn * k, 1), -1, dtype=np.int32)
+        rc = self._lib.moe_ep_get_routing(self._ctx, chunk, _ptr(idx), _ptr(w), _ptr(pos),
+                                          _ptr(count), _ptr(offset), _ptr(perm))
+        if rc != 0:
+            raise MoeEpError(rc, self.last_error())
+        return {"idx": idx, "w": w, "pos": pos, "count": count, "offset": offset,
+                "perm": perm[:offset[-1]].copy()}
+
+    # -- profiling ------------------------------------------------------------------------
+    def set_profiling(self, depth: int) -> None:
+        rc = self._lib.moe_ep_set_profiling(self._ctx, depth)
+        if rc != 0:
+            raise MoeEpError(rc, self.last_error())
+
+    def get_stage_ms(self) -> Dict[str, float]:
+        ms = (ctypes.c_float * 8)()
+        rc = self._lib.moe_ep_get_stage_ms(self._ctx, ctypes.cast(ms, ctypes.c_void_p), 8)
+        if rc != 0:
+            raise MoeEpError(rc, self.last_error())
+        return {name: float(ms[i]) for i, name in enumerate(STAGES)}
+
+    def last_error(self) -> str:
+        return (self._lib.moe_ep_last_error(self._ctx) or b"").decode()
+
+    def destroy(self) -> None:
+        if getattr(self, "_ctx", None) is not None and self._ctx.value:
+            self._lib.moe_ep_destroy(self._ctx)
+            self._ctx = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass

@@ -1,0 +1,52 @@
+// Weighted aggregation of the selected experts' outputs, plus the shared experts' output
+// (Sec. 2.1).  Token-major gather-reduce: a wavefront owns an output row, walks the row's
+// kept slots in slot order, and accumulates in fp32; every load and store is 16 bytes per
+// lane and contiguous over the wavefront.  No atomics, so the result is deterministic.
+#include "common.h"
+#include "kernels.h"
+
+namespace moe_ep {
+
+__device__ __forceinline__ void fma8(float* acc, float ws, const uint4& v) {
+    acc[0] = fmaf(ws, bf16_lo(v.x), acc[0]); acc[1] = fmaf(ws, bf16_hi(v.x), acc[1]);
+    acc[2] = fmaf(ws, bf16_lo(v.y), acc[2]); acc[3] = fmaf(ws, bf16_hi(v.y), acc[3]);
+    acc[4] = fmaf(ws, bf16_lo(v.z), acc[4]); acc[5] = fmaf(ws, bf16_hi(v.z), acc[5]);
+    acc[6] = fmaf(ws, bf16_lo(v.w), acc[6]); acc[7] = fmaf(ws, bf16_hi(v.w), acc[7]);
+}
+
+__global__ __launch_bounds__(256) void combine_kernel(
+    const uint4* __restrict__ y, const uint4* __restrict__ ysh, const int32_t* __restrict__ pos,
+    const float* __restrict__ w, int Tn, int k, int M8, uint4* __restrict__ out)
+{
+    const int lane = threadIdx.x & 63;
+    const int gw = (blockIdx.x * 256 + threadIdx.x) >> 6, nw = gridDim.x * 4;
+    for (int t = gw; t < Tn; t += nw) {
+        const int my_pos = (lane < k) ? pos[(size_t)t * k + lane] : -1;
+        const float my_w = (lane < k) ? w[(size_t)t * k + lane] : 0.f;
+        for (int c = lane; c < M8; c += 64) {
+            float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+            for (int s = 0; s < k; ++s) {
+                const int p = __shfl(my_pos, s, 64);  // uniform over the wavefront
+                const float ws = __shfl(my_w, s, 64);
+                if (p >= 0) fma8(acc, ws, y[(size_t)p * M8 + c]);
+            }
+            if (ysh != nullptr) fma8(acc, 1.0f, ysh[(size_t)t * M8 + c]);
+            uint4 o;
+            o.x = pack_bf16x2(acc[0], acc[1]); o.y = pack_bf16x2(acc[2], acc[3]);
+            o.z = pack_bf16x2(acc[4], acc[5]); o.w = pack_bf16x2(acc[6], acc[7]);
+            out[(size_t)t * M8 + c] = o;
+        }
+    }
+}
+
+hipError_t launch_combine(const void* y, const void* ysh, const int32_t* pos, const float* w, int Tn,
+                          int k, int M, void* out, int grid, hipStream_t s)
+{
+    if (Tn <= 0) return hipSuccess;
+    hipLaunchKernelGGL(combine_kernel, dim3(grid), dim3(256), 0, s, static_cast<const uint4*>(y),
+                       static_cast<const uint4*>(ysh), pos, w, Tn, k, M / 8,
+                       static_cast<uint4*>(out));
+    return hipGetLastError();
+}
+
+}  // namespace moe_ep

@@ -1,0 +1,53 @@
+// Host-side launchers of the HIP kernels (internal to the library; the public boundary is moe_ep.h).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace moe_ep {
+
+// tokens per router / permute workgroup: one bit each in a 64-bit mask per expert
+constexpr int kTokPerBlock = 64;
+
+// ---- gate: softmax + top-k (Sec. 2.1) and per-workgroup expert bit masks for the partition
+hipError_t launch_router(const float* logits, int Tn, int E, int k, int e0, int El, int32_t* idx,
+                         float* w, unsigned long long* blk_mask, hipStream_t s);
+
+// ---- partition by expert (Sec. 2.1; Sec. 3.1 "The MoE Part")
+hipError_t launch_dispatch_scan(const unsigned long long* blk_mask, int nblk, int El, int BM,
+                                int32_t* blk_off, int32_t* count, int32_t* offset,
+                                int32_t* mt_prefix, hipStream_t s);
+hipError_t launch_dispatch_permute(const int32_t* idx, const unsigned long long* blk_mask,
+                                   const int32_t* blk_off, const int32_t* offset, int Tn, int k,
+                                   int e0, int El, int32_t* pos, int32_t* perm, hipStream_t s);
+hipError_t launch_gather_rows(const void* tokens, const int32_t* perm, const int32_t* n_rows_ptr,
+                              int k, int M, void* xp, int grid, hipStream_t s);
+
+// ---- weighted aggregation (Sec. 2.1)
+hipError_t launch_combine(const void* y, const void* ysh, const int32_t* pos, const float* w, int Tn,
+                          int k, int M, void* out, int grid, hipStream_t s);
+
+// ---- expert projections as one grouped GEMM launch (Sec. 3.1, Eq. moe_detail / shared_detail)
+struct GemmArgs {
+    const uint16_t* A;         // activations, bf16 [rows, lda]
+    const uint16_t* W;         // first group's weight matrix, bf16 rows of length ldw
+    uint16_t* C;               // output, bf16 [rows, ldc]
+    const int32_t* offset;     // ragged mode: [G+1] first row of each group (device); NULL = dense
+    const int32_t* mt_prefix;  // ragged mode: [G+1] prefix sum of row tiles per group (device)
+    int G;                     // groups (experts)
+    int dense_rows;            // dense mode: every group multiplies rows [0, dense_rows) of A
+    int K;                     // reduction length, multiple of 64
+    int N;                     // output columns per group (SwiGLU: activation columns)
+    int lda, ldc, ldw;
+    long long w_group_stride;  // elements from one group's matrix to the next group's
+    long long w_up_offset;     // SwiGLU: elements from W_gate to W_up
+    int kseg_len;              // K is split into segments of this length ...
+    long long w_kseg_stride;   // ... whose weight blocks are this many elements apart
+    int c_group_col_stride;    // dense mode: group g writes columns starting at g * this
+};
+// variant: 0 = 128x256 tile (default), 1 = 128x128 tile
+hipError_t launch_grouped_gemm(const GemmArgs& a, bool swiglu, int variant, int n_cu,
+                               int max_row_tiles, hipStream_t s);
+hipError_t grouped_gemm_init();   // raises the dynamic-LDS limit of every instantiation once
+int grouped_gemm_row_tile();      // BM: rows per tile (all variants share it)
+
+}  // namespace moe_ep

@@ -1,0 +1,490 @@
+// C ABI of the expert-group MoE layer: argument checks, workspaces, and the chunk pipeline
+// that strings the kernels together (Sec. 2.3: the token range is cut into r_2 pieces whose
+// transfers and expert compute overlap; Sec. 3.2, Eq. limitation: each of the three
+// resources -- inbound transfer, expert compute, outbound transfer -- runs one task at a
+// time, and a chunk's compute waits for its inbound transfer, its outbound transfer for its
+// compute).  The resources are three HIP streams; the precedence rules are HIP events.
+#include <hip/hip_runtime.h>
+
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "kernels.h"
+#include "moe_ep.h"
+
+using namespace moe_ep;
+
+namespace {
+
+enum Stage { ST_ROUTER = 0, ST_PARTITION, ST_GEMM1, ST_GEMM2, ST_SGEMM1, ST_SGEMM2, ST_COMBINE, ST_TOTAL, ST_COUNT };
+
+struct ProfSpan { hipEvent_t a, b; int stage; };
+
+}  // namespace
+
+struct moe_ep_ctx {
+    moe_ep_config cfg;
+    int n_cu = 0;
+    int gemm_variant = 0;
+    int BM = 128;
+    // device workspaces
+    void* d_tokens = nullptr; float* d_logits = nullptr; void* d_out = nullptr;  // pinned-host mode staging
+    int32_t* idx = nullptr; float* w = nullptr; int32_t* pos = nullptr; int32_t* perm = nullptr;
+    unsigned long long* blk_mask = nullptr; int32_t* blk_off = nullptr;
+    int32_t* count = nullptr; int32_t* offset = nullptr; int32_t* mt_prefix = nullptr;
+    uint16_t* xp = nullptr; uint16_t* h = nullptr; uint16_t* y = nullptr;
+    uint16_t* hs = nullptr; uint16_t* ysh = nullptr;
+    // streams and events
+    hipStream_t s_in = nullptr, s_comp = nullptr, s_out = nullptr;
+    hipEvent_t ev_start = nullptr, ev_done = nullptr, ev_comp_done = nullptr;
+    std::vector<hipEvent_t> ev_in, ev_comp;
+    // last forward (for moe_ep_get_routing)
+    int last_T = -1, last_k = 0, last_r = 0;
+    // stage profiling
+    int prof_depth = 0, prof_recorded = 0;
+    std::vector<hipEvent_t> prof_pool; size_t prof_next = 0;
+    std::vector<ProfSpan> prof_spans;
+    char err[256] = {0};
+};
+
+namespace {
+
+const char* set_why(const char** why, const char* msg) { if (why) *why = msg; return msg; }
+
+size_t align256(size_t b) { return (b + 255) & ~(size_t)255; }
+
+struct WsLayout {
+    size_t tokens, logits, out, idx, w, pos, perm, blk_mask, blk_off, count, offset, mt_prefix, xp, h, y, hs, ysh, total;
+};
+
+WsLayout ws_layout(const moe_ep_config& c)
+{
+    WsLayout L{};
+    const size_t T = (size_t)c.max_tokens, k = (size_t)c.max_top_k, M = (size_t)c.hidden, H = (size_t)c.inter;
+    const size_t A = T * k, El = (size_t)c.n_local, R = (size_t)c.max_chunks;
+    const size_t nblk = (T + kTokPerBlock - 1) / kTokPerBlock + R;
+    const bool pinned = c.io_mode == MOE_EP_IO_PINNED_HOST;
+    size_t o = 0;
+    auto take = [&](size_t bytes) { size_t at = o; o += align256(bytes ? bytes : 1); return at; };
+    L.tokens = take(pinned ? T * M * 2 : 0);
+    L.logits = take(pinned ? T * (size_t)c.n_experts * 4 : 0);
+    L.out = take(pinned ? T * M * 2 : 0);
+    L.idx = take(A * 4); L.w = take(A * 4); L.pos = take(A * 4); L.perm = take(A * 4);
+    L.blk_mask = take(nblk * El * 8); L.blk_off = take(nblk * El * 4);
+    L.count = take(R * El * 4); L.offset = take(R * (El + 1) * 4); L.mt_prefix = take(R * (El + 1) * 4);
+    L.xp = take(A * M * 2); L.h = take(A * H * 2); L.y = take(A * M * 2);
+    L.hs = take(c.n_shared > 0 ? T * (size_t)c.n_shared * (size_t)c.shared_inter * 2 : 0);
+    L.ysh = take(c.n_shared > 0 ? T * M * 2 : 0);
+    L.total = o;
+    return L;
+}
+
+int fail(moe_ep_ctx* ctx, int code, const char* what, hipError_t e = hipSuccess)
+{
+    if (ctx) {
+        if (e != hipSuccess) snprintf(ctx->err, sizeof ctx->err, "%s: %s", what, hipGetErrorString(e));
+        else snprintf(ctx->err, sizeof ctx->err, "%s", what);
+    }
+    return code;
+}
+
+#define HIP_TRY(ctx, call)                                                      \
+    do {                                                                        \
+        hipError_t e__ = (call);                                                \
+        if (e__ != hipSuccess) return fail((ctx), MOE_EP_EHIP, #call, e__);     \
+    } while (0)
+
+hipEvent_t prof_event(moe_ep_ctx* ctx)
+{
+    if (ctx->prof_next >= ctx->prof_pool.size()) return nullptr;
+    return ctx->prof_pool[ctx->prof_next++];
+}
+
+// Marks the start of a timed stage on stream s; returns the span index or -1.
+int prof_begin(moe_ep_ctx* ctx, bool on, int stage, hipStream_t s)
+{
+    if (!on) return -1;
+    hipEvent_t a = prof_event(ctx), b = prof_event(ctx);
+    if (!a || !b) return -1;
+    if (hipEventRecord(a, s) != hipSuccess) return -1;
+    ctx->prof_spans.push_back({a, b, stage});
+    return (int)ctx->prof_spans.size() - 1;
+}
+void prof_end(moe_ep_ctx* ctx, int span, hipStream_t s)
+{
+    if (span >= 0) (void)hipEventRecord(ctx->prof_spans[span].b, s);
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* moe_ep_version(void) { return "0.1"; }
+
+int moe_ep_validate_config(const moe_ep_config* c, const char** why)
+{
+    set_why(why, "ok");
+    if (!c) { set_why(why, "cfg is NULL"); return MOE_EP_EINVAL; }
+    if (c->hidden < 64 || c->hidden % 64) { set_why(why, "hidden must be a positive multiple of 64"); return MOE_EP_EINVAL; }
+    if (c->inter < 64 || c->inter % 64) { set_why(why, "inter must be a positive multiple of 64"); return MOE_EP_EINVAL; }
+    if (c->n_experts < 1 || c->n_experts > 512) { set_why(why, "n_experts must be in 1..512"); return MOE_EP_EINVAL; }
+    if (c->n_local < 1 || c->local_begin < 0 || (long long)c->local_begin + c->n_local > c->n_experts) {
+        set_why(why, "local experts [local_begin, local_begin+n_local) must lie inside 0..n_experts"); return MOE_EP_EINVAL; }
+    if (c->n_shared < 0 || c->n_shared > 64) { set_why(why, "n_shared must be in 0..64"); return MOE_EP_EINVAL; }
+    if (c->n_shared > 0 && (c->shared_inter < 64 || c->shared_inter % 64)) {
+        set_why(why, "shared_inter must be a positive multiple of 64 when n_shared > 0"); return MOE_EP_EINVAL; }
+    if (c->max_tokens < 1 || c->max_tokens > (1 << 20)) { set_why(why, "max_tokens must be in 1..1048576"); return MOE_EP_EINVAL; }
+    if (c->max_top_k < 1 || c->max_top_k > 64 || c->max_top_k > c->n_experts) {
+        set_why(why, "max_top_k must be in 1..min(n_experts, 64)"); return MOE_EP_EINVAL; }
+    if (c->max_chunks < 1 || c->max_chunks > 64) { set_why(why, "max_chunks must be in 1..64"); return MOE_EP_EINVAL; }
+    if (c->io_mode != MOE_EP_IO_DEVICE && c->io_mode != MOE_EP_IO_PINNED_HOST) { set_why(why, "unknown io_mode"); return MOE_EP_EINVAL; }
+    if (c->device < 0) { set_why(why, "device must be >= 0"); return MOE_EP_EINVAL; }
+    if ((long long)c->max_tokens * c->max_top_k > (1ll << 30)) { set_why(why, "max_tokens * max_top_k too large"); return MOE_EP_EINVAL; }
+    return MOE_EP_OK;
+}
+
+int moe_ep_validate_forward(const moe_ep_config* c, const void* tokens, const float* gate_logits,
+                            const void* routed_w, const void* shared_w, int32_t top_k,
+                            int32_t r_chunks, int32_t order, int32_t n_tokens, const void* out,
+                            const char** why)
+{
+    int rc = moe_ep_validate_config(c, why);
+    if (rc != MOE_EP_OK) return rc;
+    if (n_tokens < 0 || n_tokens > c->max_tokens) { set_why(why, "n_tokens must be in 0..max_tokens"); return MOE_EP_EINVAL; }
+    if (top_k < 1 || top_k > c->max_top_k || top_k > c->n_experts) { set_why(why, "top_k must be in 1..min(n_experts, max_top_k)"); return MOE_EP_EINVAL; }
+    if (r_chunks < 1 || r_chunks > c->max_chunks) { set_why(why, "r_chunks must be in 1..max_chunks"); return MOE_EP_EINVAL; }
+    if (c->n_shared > 0 && order != MOE_EP_ORDER_SHARED_FIRST && order != MOE_EP_ORDER_INTERLEAVED) {
+        set_why(why, "unknown order"); return MOE_EP_EINVAL; }
+    if (!routed_w) { set_why(why, "routed_w is NULL"); return MOE_EP_EINVAL; }
+    if (c->n_shared > 0 && !shared_w) { set_why(why, "shared_w is NULL but n_shared > 0"); return MOE_EP_EINVAL; }
+    if (c->n_shared == 0 && shared_w) { set_why(why, "shared_w given but n_shared == 0"); return MOE_EP_EINVAL; }
+    if (n_tokens > 0 && (!tokens || !gate_logits || !out)) { set_why(why, "tokens, gate_logits and out must not be NULL"); return MOE_EP_EINVAL; }
+    return MOE_EP_OK;
+}
+
+size_t moe_ep_workspace_bytes(const moe_ep_config* cfg)
+{
+    if (moe_ep_validate_config(cfg, nullptr) != MOE_EP_OK) return 0;
+    return ws_layout(*cfg).total;
+}
+
+int moe_ep_destroy(moe_ep_ctx* ctx)
+{
+    if (!ctx) return MOE_EP_OK;
+    (void)hipSetDevice(ctx->cfg.device);
+    if (ctx->s_in) (void)hipStreamSynchronize(ctx->s_in);
+    if (ctx->s_comp) (void)hipStreamSynchronize(ctx->s_comp);
+    if (ctx->s_out) (void)hipStreamSynchronize(ctx->s_out);
+    for (hipEvent_t e : ctx->ev_in) (void)hipEventDestroy(e);
+    for (hipEvent_t e : ctx->ev_comp) (void)hipEventDestroy(e);
+    for (hipEvent_t e : ctx->prof_pool) (void)hipEventDestroy(e);
+    if (ctx->ev_start) (void)hipEventDestroy(ctx->ev_start);
+    if (ctx->ev_done) (void)hipEventDestroy(ctx->ev_done);
+    if (ctx->ev_comp_done) (void)hipEventDestroy(ctx->ev_comp_done);
+    if (ctx->s_in) (void)hipStreamDestroy(ctx->s_in);
+    if (ctx->s_comp) (void)hipStreamDestroy(ctx->s_comp);
+    if (ctx->s_out) (void)hipStreamDestroy(ctx->s_out);
+    if (ctx->d_tokens) (void)hipFree(ctx->d_tokens);  // one slab holds every workspace
+    delete ctx;
+    return MOE_EP_OK;
+}
+
+int moe_ep_create(const moe_ep_config* cfg, moe_ep_ctx** out_ctx)
+{
+    if (!out_ctx) return MOE_EP_EINVAL;
+    if (moe_ep_validate_config(cfg, nullptr) != MOE_EP_OK) return MOE_EP_EINVAL;
+    int n_dev = 0;
+    if (hipGetDeviceCount(&n_dev) != hipSuccess || cfg->device >= n_dev) return MOE_EP_EHIP;
+    if (hipSetDevice(cfg->device) != hipSuccess) return MOE_EP_EHIP;
+    moe_ep_ctx* ctx = new (std::nothrow) moe_ep_ctx();
+    if (!ctx) return MOE_EP_ENOMEM;
+    ctx->cfg = *cfg;
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, cfg->device) != hipSuccess) { delete ctx; return MOE_EP_EHIP; }
+    ctx->n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+    ctx->BM = grouped_gemm_row_tile();
+    if (const char* v = getenv("MOE_EP_GEMM_VARIANT")) ctx->gemm_variant = atoi(v);
+    if (grouped_gemm_init() != hipSuccess) { delete ctx; return MOE_EP_EHIP; }
+
+    const WsLayout L = ws_layout(*cfg);
+    char* slab = nullptr;
+    if (hipMalloc(reinterpret_cast<void**>(&slab), L.total) != hipSuccess) { delete ctx; return MOE_EP_ENOMEM; }
+    ctx->d_tokens = slab + L.tokens;  // L.tokens == 0: the slab base, freed in destroy
+    ctx->d_logits = reinterpret_cast<float*>(slab + L.logits);
+    ctx->d_out = slab + L.out;
+    ctx->idx = reinterpret_cast<int32_t*>(slab + L.idx);
+    ctx->w = reinterpret_cast<float*>(slab + L.w);
+    ctx->pos = reinterpret_cast<int32_t*>(slab + L.pos);
+    ctx->perm = reinterpret_cast<int32_t*>(slab + L.perm);
+    ctx->blk_mask = reinterpret_cast<unsigned long long*>(slab + L.blk_mask);
+    ctx->blk_off = reinterpret_cast<int32_t*>(slab + L.blk_off);
+    ctx->count = reinterpret_cast<int32_t*>(slab + L.count);
+    ctx->offset = reinterpret_cast<int32_t*>(slab + L.offset);
+    ctx->mt_prefix = reinterpret_cast<int32_t*>(slab + L.mt_prefix);
+    ctx->xp = reinterpret_cast<uint16_t*>(slab + L.xp);
+    ctx->h = reinterpret_cast<uint16_t*>(slab + L.h);
+    ctx->y = reinterpret_cast<uint16_t*>(slab + L.y);
+    ctx->hs = reinterpret_cast<uint16_t*>(slab + L.hs);
+    ctx->ysh = reinterpret_cast<uint16_t*>(slab + L.ysh);
+
+    bool ok = true;
+    ok = ok && hipStreamCreateWithFlags(&ctx->s_in, hipStreamNonBlocking) == hipSuccess;
+    ok = ok && hipStreamCreateWithFlags(&ctx->s_comp, hipStreamNonBlocking) == hipSuccess;
+    ok = ok && hipStreamCreateWithFlags(&ctx->s_out, hipStreamNonBlocking) == hipSuccess;
+    ok = ok && hipEventCreateWithFlags(&ctx->ev_start, hipEventDisableTiming) == hipSuccess;
+    ok = ok && hipEventCreateWithFlags(&ctx->ev_done, hipEventDisableTiming) == hipSuccess;
+    ok = ok && hipEventCreateWithFlags(&ctx->ev_comp_done, hipEventDisableTiming) == hipSuccess;
+    for (int i = 0; ok && i < cfg->max_chunks; ++i) {
+        hipEvent_t a = nullptr, b = nullptr;
+        ok = ok && hipEventCreateWithFlags(&a, hipEventDisableTiming) == hipSuccess;
+        if (a) ctx->ev_in.push_back(a);
+        ok = ok && hipEventCreateWithFlags(&b, hipEventDisableTiming) == hipSuccess;
+        if (b) ctx->ev_comp.push_back(b);
+    }
+    if (!ok) { moe_ep_destroy(ctx); return MOE_EP_EHIP; }
+    *out_ctx = ctx;
+    return MOE_EP_OK;
+}
+
+const char* moe_ep_last_error(const moe_ep_ctx* ctx) { return ctx ? ctx->err : "context is NULL"; }
+
+int moe_ep_set_profiling(moe_ep_ctx* ctx, int32_t depth)
+{
+    if (!ctx || depth < 0 || depth > 256) return MOE_EP_EINVAL;
+    HIP_TRY(ctx, hipSetDevice(ctx->cfg.device));
+    HIP_TRY(ctx, hipDeviceSynchronize());
+    const size_t per_forward = 2 * ((size_t)ctx->cfg.max_chunks * 8 + 4);
+    const size_t want = (size_t)depth * per_forward;
+    while (ctx->prof_pool.size() < want) {
+        hipEvent_t e = nullptr;
+        HIP_TRY(ctx, hipEventCreate(&e));
+        ctx->prof_pool.push_back(e);
+    }
+    ctx->prof_depth = depth;
+    ctx->prof_recorded = 0;
+    ctx->prof_next = 0;
+    ctx->prof_spans.clear();
+    return MOE_EP_OK;
+}
+
+int moe_ep_get_stage_ms(moe_ep_ctx* ctx, float* ms, int32_t n)
+{
+    if (!ctx || !ms || n < 1) return MOE_EP_EINVAL;
+    if (ctx->prof_recorded == 0) return fail(ctx, MOE_EP_ESTATE, "no profiled forward recorded");
+    HIP_TRY(ctx, hipSetDevice(ctx->cfg.device));
+    HIP_TRY(ctx, hipDeviceSynchronize());
+    double acc[ST_COUNT] = {0};
+    for (const ProfSpan& sp : ctx->prof_spans) {
+        float t = 0.f;
+        HIP_TRY(ctx, hipEventElapsedTime(&t, sp.a, sp.b));
+        acc[sp.stage] += t;
+    }
+    for (int i = 0; i < n && i < ST_COUNT; ++i) ms[i] = (float)(acc[i] / ctx->prof_recorded);
+    // start a fresh window
+    ctx->prof_recorded = 0;
+    ctx->prof_next = 0;
+    ctx->prof_spans.clear();
+    return MOE_EP_OK;
+}
+
+int moe_ep_forward(moe_ep_ctx* ctx, const void* tokens, const float* gate_logits,
+                   const void* routed_w, const void* shared_w, int32_t top_k, int32_t r_chunks,
+                   int32_t order, int32_t n_tokens, void* out, void* stream)
+{
+    if (!ctx) return MOE_EP_EINVAL;
+    const char* why = nullptr;
+    if (moe_ep_validate_forward(&ctx->cfg, tokens, gate_logits, routed_w, shared_w, top_k, r_chunks,
+                                order, n_tokens, out, &why) != MOE_EP_OK)
+        return fail(ctx, MOE_EP_EINVAL, why);
+    ctx->err[0] = 0;
+    const moe_ep_config& c = ctx->cfg;
+    const int T = n_tokens, k = top_k, r = r_chunks;
+    const int M = c.hidden, H = c.inter, E = c.n_experts, El = c.n_local, e0 = c.local_begin;
+    const int Ns = c.n_shared, Hs = c.shared_inter;
+    ctx->last_T = T; ctx->last_k = k; ctx->last_r = r;
+    if (T == 0) return MOE_EP_OK;
+    HIP_TRY(ctx, hipSetDevice(c.device));
+
+    hipStream_t user = static_cast<hipStream_t>(stream);
+    const bool pinned = c.io_mode == MOE_EP_IO_PINNED_HOST;
+    hipStream_t s_in = pinned ? ctx->s_in : user;
+    hipStream_t s_comp = pinned ? ctx->s_comp : user;
+    hipStream_t s_out = pinned ? ctx->s_out : user;
+    const bool prof = ctx->prof_depth > 0 && ctx->prof_recorded < ctx->prof_depth;
+
+    const uint16_t* tok_dev = static_cast<const uint16_t*>(pinned ? ctx->d_tokens : tokens);
+    const float* log_dev = pinned ? ctx->d_logits : gate_logits;
+    uint16_t* out_dev = static_cast<uint16_t*>(pinned ? ctx->d_out : out);
+    const uint16_t* rw = static_cast<const uint16_t*>(routed_w);
+    const uint16_t* sw = static_cast<const uint16_t*>(shared_w);
+
+    const int span_total = prof_begin(ctx, prof, ST_TOTAL, user);
+    if (pinned) {
+        HIP_TRY(ctx, hipEventRecord(ctx->ev_start, user));
+        HIP_TRY(ctx, hipStreamWaitEvent(s_in, ctx->ev_start, 0));
+        HIP_TRY(ctx, hipStreamWaitEvent(s_comp, ctx->ev_start, 0));
+        HIP_TRY(ctx, hipStreamWaitEvent(s_out, ctx->ev_start, 0));
+    }
+    const int Tc = (T + r - 1) / r;
+    const int bw_grid = ctx->n_cu * 8;  // bandwidth kernels: 8 workgroups of 4 wavefronts per CU
+
+    // shared experts of token range [t0, t0+Tn) -> ysh rows [t0, t0+Tn)
+    auto run_shared = [&](int t0, int Tn) -> int {
+        GemmArgs g1{};
+        g1.A = tok_dev + (size_t)t0 * M; g1.W = sw; g1.C = ctx->hs + (size_t)t0 * Ns * Hs;
+        g1.offset = nullptr; g1.mt_prefix = nullptr; g1.G = Ns; g1.dense_rows = Tn;
+        g1.K = M; g1.N = Hs; g1.lda = M; g1.ldc = Ns * Hs; g1.ldw = M;
+        g1.w_group_stride = (long long)3 * Hs * M; g1.w_up_offset = (long long)Hs * M;
+        g1.kseg_len = M; g1.w_kseg_stride = 0; g1.c_group_col_stride = Hs;
+        const int mt = (Tn + ctx->BM - 1) / ctx->BM;
+        int sp = prof_begin(ctx, prof, ST_SGEMM1, s_comp);
+        HIP_TRY(ctx, launch_grouped_gemm(g1, true, ctx->gemm_variant, ctx->n_cu, mt * Ns, s_comp));
+        prof_end(ctx, sp, s_comp);
+        GemmArgs g2{};
+        g2.A = ctx->hs + (size_t)t0 * Ns * Hs; g2.W = sw + (size_t)2 * Hs * M; g2.C = ctx->ysh + (size_t)t0 * M;
+        g2.offset = nullptr; g2.mt_prefix = nullptr; g2.G = 1; g2.dense_rows = Tn;
+        g2.K = Ns * Hs; g2.N = M; g2.lda = Ns * Hs; g2.ldc = M; g2.ldw = Hs;
+        g2.w_group_stride = 0; g2.w_up_offset = 0;
+        g2.kseg_len = Hs; g2.w_kseg_stride = (long long)3 * Hs * M; g2.c_group_col_stride = 0;
+        sp = prof_begin(ctx, prof, ST_SGEMM2, s_comp);
+        HIP_TRY(ctx, launch_grouped_gemm(g2, false, ctx->gemm_variant, ctx->n_cu, mt, s_comp));
+        prof_end(ctx, sp, s_comp);
+        return MOE_EP_OK;
+    };
+
+    // inbound transfers: all chunks are queued at once on their own stream
+    if (pinned) {
+        for (int cidx = 0; cidx < r; ++cidx) {
+            const int t0 = cidx * Tc;
+            const int Tn = t0 >= T ? 0 : (T - t0 < Tc ? T - t0 : Tc);
+            if (Tn > 0) {
+                HIP_TRY(ctx, hipMemcpyAsync(static_cast<char*>(ctx->d_tokens) + (size_t)t0 * M * 2,
+                                            static_cast<const char*>(tokens) + (size_t)t0 * M * 2,
+                                            (size_t)Tn * M * 2, hipMemcpyHostToDevice, s_in));
+                HIP_TRY(ctx, hipMemcpyAsync(ctx->d_logits + (size_t)t0 * E, gate_logits + (size_t)t0 * E,
+                                            (size_t)Tn * E * 4, hipMemcpyHostToDevice, s_in));
+            }
+            HIP_TRY(ctx, hipEventRecord(ctx->ev_in[cidx], s_in));
+        }
+    }
+    if (Ns > 0 && order == MOE_EP_ORDER_SHARED_FIRST) {
+        if (pinned) HIP_TRY(ctx, hipStreamWaitEvent(s_comp, ctx->ev_in[r - 1], 0));
+        int rc = run_shared(0, T);
+        if (rc != MOE_EP_OK) return rc;
+    }
+
+    for (int cidx = 0; cidx < r; ++cidx) {
+        const int t0 = cidx * Tc;
+        const int Tn = t0 >= T ? 0 : (T - t0 < Tc ? T - t0 : Tc);
+        int32_t* count = ctx->count + (size_t)cidx * El;
+        int32_t* offset = ctx->offset + (size_t)cidx * (El + 1);
+        int32_t* mt_prefix = ctx->mt_prefix + (size_t)cidx * (El + 1);
+        if (pinned) HIP_TRY(ctx, hipStreamWaitEvent(s_comp, ctx->ev_in[cidx], 0));
+        const int nblk = (Tn + kTokPerBlock - 1) / kTokPerBlock;
+        int32_t* idx = ctx->idx + (size_t)t0 * k;
+        float* w = ctx->w + (size_t)t0 * k;
+        int32_t* pos = ctx->pos + (size_t)t0 * k;
+        int32_t* perm = ctx->perm + (size_t)t0 * k;
+
+        int sp = prof_begin(ctx, prof, ST_ROUTER, s_comp);
+        HIP_TRY(ctx, launch_router(log_dev + (size_t)t0 * E, Tn, E, k, e0, El, idx, w, ctx->blk_mask, s_comp));
+        prof_end(ctx, sp, s_comp);
+
+        sp = prof_begin(ctx, prof, ST_PARTITION, s_comp);
+        HIP_TRY(ctx, launch_dispatch_scan(ctx->blk_mask, nblk, El, ctx->BM, ctx->blk_off, count, offset, mt_prefix, s_comp));
+        if (Tn > 0) {
+            HIP_TRY(ctx, launch_dispatch_permute(idx, ctx->blk_mask, ctx->blk_off, offset, Tn, k, e0, El, pos, perm, s_comp));
+            HIP_TRY(ctx, launch_gather_rows(tok_dev + (size_t)t0 * M, perm, offset + El, k, M, ctx->xp, bw_grid, s_comp));
+        }
+        prof_end(ctx, sp, s_comp);
+        if (Tn == 0) {
+            if (pinned) HIP_TRY(ctx, hipEventRecord(ctx->ev_comp[cidx], s_comp));
+            continue;
+        }
+
+        // an upper bound of the row tiles the device-side prefix sums can describe
+        const long long a_max = (long long)Tn * k;
+        const int max_row_tiles = (int)((a_max + ctx->BM - 1) / ctx->BM) + El;
+
+        GemmArgs g1{};
+        g1.A = ctx->xp; g1.W = rw; g1.C = ctx->h; g1.offset = offset; g1.mt_prefix = mt_prefix;
+        g1.G = El; g1.dense_rows = 0; g1.K = M; g1.N = H; g1.lda = M; g1.ldc = H; g1.ldw = M;
+        g1.w_group_stride = (long long)3 * H * M; g1.w_up_offset = (long long)H * M;
+        g1.kseg_len = M; g1.w_kseg_stride = 0; g1.c_group_col_stride = 0;
+        sp = prof_begin(ctx, prof, ST_GEMM1, s_comp);
+        HIP_TRY(ctx, launch_grouped_gemm(g1, true, ctx->gemm_variant, ctx->n_cu, max_row_tiles, s_comp));
+        prof_end(ctx, sp, s_comp);
+
+        GemmArgs g2{};
+        g2.A = ctx->h; g2.W = rw + (size_t)2 * H * M; g2.C = ctx->y; g2.offset = offset; g2.mt_prefix = mt_prefix;
+        g2.G = El; g2.dense_rows = 0; g2.K = H; g2.N = M; g2.lda = H; g2.ldc = M; g2.ldw = H;
+        g2.w_group_stride = (long long)3 * H * M; g2.w_up_offset = 0;
+        g2.kseg_len = H; g2.w_kseg_stride = 0; g2.c_group_col_stride = 0;
+        sp = prof_begin(ctx, prof, ST_GEMM2, s_comp);
+        HIP_TRY(ctx, launch_grouped_gemm(g2, false, ctx->gemm_variant, ctx->n_cu, max_row_tiles, s_comp));
+        prof_end(ctx, sp, s_comp);
+
+        if (Ns > 0 && order == MOE_EP_ORDER_INTERLEAVED) {
+            int rc = run_shared(t0, Tn);
+            if (rc != MOE_EP_OK) return rc;
+        }
+
+        sp = prof_begin(ctx, prof, ST_COMBINE, s_comp);
+        HIP_TRY(ctx, launch_combine(ctx->y, Ns > 0 ? ctx->ysh + (size_t)t0 * M : nullptr, pos, w, Tn, k, M,
+                                    out_dev + (size_t)t0 * M, bw_grid, s_comp));
+        prof_end(ctx, sp, s_comp);
+
+        if (pinned) {
+            HIP_TRY(ctx, hipEventRecord(ctx->ev_comp[cidx], s_comp));
+            HIP_TRY(ctx, hipStreamWaitEvent(s_out, ctx->ev_comp[cidx], 0));
+            HIP_TRY(ctx, hipMemcpyAsync(static_cast<char*>(out) + (size_t)t0 * M * 2,
+                                        reinterpret_cast<const char*>(out_dev) + (size_t)t0 * M * 2,
+                                        (size_t)Tn * M * 2, hipMemcpyDeviceToHost, s_out));
+        }
+    }
+    if (pinned) {
+        HIP_TRY(ctx, hipEventRecord(ctx->ev_comp_done, s_comp));
+        HIP_TRY(ctx, hipStreamWaitEvent(s_out, ctx->ev_comp_done, 0));
+        HIP_TRY(ctx, hipEventRecord(ctx->ev_done, s_out));
+        HIP_TRY(ctx, hipStreamWaitEvent(user, ctx->ev_done, 0));
+    }
+    prof_end(ctx, span_total, user);
+    if (prof) ctx->prof_recorded++;
+    return MOE_EP_OK;
+}
+
+int moe_ep_get_routing(moe_ep_ctx* ctx, int32_t chunk, int32_t* idx, float* w, int32_t* pos,
+                       int32_t* count, int32_t* offset, int32_t* perm)
+{
+    if (!ctx) return MOE_EP_EINVAL;
+    if (ctx->last_T < 0) return fail(ctx, MOE_EP_ESTATE, "no forward has run yet");
+    if (chunk < 0 || chunk >= ctx->last_r) return fail(ctx, MOE_EP_EINVAL, "chunk out of range");
+    const moe_ep_config& c = ctx->cfg;
+    const int T = ctx->last_T, k = ctx->last_k, r = ctx->last_r, El = c.n_local;
+    const int Tc = (T + r - 1) / r, t0 = chunk * Tc;
+    const int Tn = t0 >= T ? 0 : (T - t0 < Tc ? T - t0 : Tc);
+    HIP_TRY(ctx, hipSetDevice(c.device));
+    HIP_TRY(ctx, hipDeviceSynchronize());
+    if (T == 0) {
+        if (count) memset(count, 0, sizeof(int32_t) * El);
+        if (offset) memset(offset, 0, sizeof(int32_t) * (El + 1));
+        return MOE_EP_OK;
+    }
+    std::vector<int32_t> off(El + 1);
+    HIP_TRY(ctx, hipMemcpy(off.data(), ctx->offset + (size_t)chunk * (El + 1), sizeof(int32_t) * (El + 1), hipMemcpyDeviceToHost));
+    if (offset) memcpy(offset, off.data(), sizeof(int32_t) * (El + 1));
+    if (count) HIP_TRY(ctx, hipMemcpy(count, ctx->count + (size_t)chunk * El, sizeof(int32_t) * El, hipMemcpyDeviceToHost));
+    const size_t na = (size_t)Tn * k;
+    if (na > 0) {
+        if (idx) HIP_TRY(ctx, hipMemcpy(idx, ctx->idx + (size_t)t0 * k, na * 4, hipMemcpyDeviceToHost));
+        if (w) HIP_TRY(ctx, hipMemcpy(w, ctx->w + (size_t)t0 * k, na * 4, hipMemcpyDeviceToHost));
+        if (pos) HIP_TRY(ctx, hipMemcpy(pos, ctx->pos + (size_t)t0 * k, na * 4, hipMemcpyDeviceToHost));
+        if (perm && off[El] > 0) HIP_TRY(ctx, hipMemcpy(perm, ctx->perm + (size_t)t0 * k, (size_t)off[El] * 4, hipMemcpyDeviceToHost));
+    }
+    return MOE_EP_OK;
+}
+
+}  // extern "C"

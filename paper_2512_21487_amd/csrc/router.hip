@@ -1,0 +1,86 @@
+// Gate: per token, the top-k of E routing scores and their renormalised softmax weights
+// (Sec. 2.1).  One 64-lane wavefront owns a token: lane l holds scores l, l+64, ... in
+// registers, each of the k rounds is a lane-local scan plus a 6-step butterfly arg-max.
+// The same workgroup (64 tokens) also records, per local expert, a 64-bit mask of the
+// tokens that selected it; the partition kernels derive counts and stable ranks from it,
+// so no atomically allocated slot ever decides an order.
+#include "common.h"
+#include "kernels.h"
+
+namespace moe_ep {
+
+constexpr int kMaxEpl = 8;  // scores per lane: E <= 512
+
+__global__ __launch_bounds__(256) void router_topk_kernel(
+    const float* __restrict__ logits, int Tn, int E, int k, int e0, int El,
+    int32_t* __restrict__ idx, float* __restrict__ w, unsigned long long* __restrict__ blk_mask)
+{
+    extern __shared__ unsigned long long smask[];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    for (int i = tid; i < El; i += 256) smask[i] = 0ull;
+    __syncthreads();
+
+    const int epl = (E + 63) >> 6;
+    constexpr int kTokPerWave = kTokPerBlock / 4;
+    for (int j = 0; j < kTokPerWave; ++j) {
+        const int tl = wave * kTokPerWave + j;
+        const int t = blockIdx.x * kTokPerBlock + tl;
+        if (t >= Tn) break;  // uniform over the wavefront
+        const float* row = logits + (size_t)t * E;
+        float v[kMaxEpl];
+        unsigned taken = 0;
+#pragma unroll
+        for (int i = 0; i < kMaxEpl; ++i) {
+            const int e = lane + 64 * i;
+            const bool ok = (i < epl) && (e < E);
+            v[i] = ok ? row[e] : 0.f;
+            if (!ok) taken |= 1u << i;
+        }
+        int my_idx = 0;
+        float my_val = 0.f;
+        for (int s = 0; s < k; ++s) {
+            // lane-local best: larger score first, equal scores keep the lower index
+            float bv = -INFINITY;
+            int bi = INT_MAX;
+#pragma unroll
+            for (int i = 0; i < kMaxEpl; ++i) {
+                if (!((taken >> i) & 1u) && (bi == INT_MAX || v[i] > bv)) { bv = v[i]; bi = lane + 64 * i; }
+            }
+#pragma unroll
+            for (int d = 32; d >= 1; d >>= 1) {
+                const float ov = __shfl_xor(bv, d, 64);
+                const int oi = __shfl_xor(bi, d, 64);
+                if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+            }
+            if ((bi & 63) == lane) taken |= 1u << (bi >> 6);
+            if (lane == s) { my_idx = bi; my_val = bv; }
+        }
+        // softmax restricted to the selection = full softmax renormalised over it
+        const float v0 = __shfl(my_val, 0, 64);
+        const float ex = (lane < k) ? expf(my_val - v0) : 0.f;
+        float sum = ex;
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) sum += __shfl_xor(sum, d, 64);
+        if (lane < k) {
+            idx[(size_t)t * k + lane] = my_idx;
+            w[(size_t)t * k + lane] = ex / sum;
+            const int el = my_idx - e0;
+            if (el >= 0 && el < El) atomicOr(&smask[el], 1ull << tl);
+        }
+    }
+    __syncthreads();
+    unsigned long long* dst = blk_mask + (size_t)blockIdx.x * El;
+    for (int i = tid; i < El; i += 256) dst[i] = smask[i];
+}
+
+hipError_t launch_router(const float* logits, int Tn, int E, int k, int e0, int El, int32_t* idx,
+                         float* w, unsigned long long* blk_mask, hipStream_t s)
+{
+    if (Tn <= 0) return hipSuccess;
+    const int nblk = (Tn + kTokPerBlock - 1) / kTokPerBlock;
+    hipLaunchKernelGGL(router_topk_kernel, dim3(nblk), dim3(256), El * sizeof(unsigned long long), s,
+                       logits, Tn, E, k, e0, El, idx, w, blk_mask);
+    return hipGetLastError();
+}
+
+}  // namespace moe_ep

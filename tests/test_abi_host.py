@@ -1,0 +1,103 @@
+"""Host-only checks of the C-ABI library: it loads, exports every declared symbol, and rejects
+bad arguments before touching HIP (no compute call is made here)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2512_21487_amd as pkg
+from paper_2512_21487_amd import MoeEpConfig
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _good(**kw):
+    base = dict(hidden=256, inter=512, n_experts=8, local_begin=0, n_local=8, n_shared=1,
+                shared_inter=512, max_tokens=128, max_top_k=2, max_chunks=8, io_mode=0, device=0)
+    base.update(kw)
+    return MoeEpConfig(**base)
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "moe_ep.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    names = set(re.findall(r"\b(moe_ep_[a-z_]+)\s*\(", header))
+    assert {"moe_ep_create", "moe_ep_forward", "moe_ep_destroy"} <= names
+    lib = pkg.load_library()
+    for n in sorted(names):
+        assert hasattr(lib, n), f"{n} declared in moe_ep.h but not exported"
+    assert lib.moe_ep_version().decode().count(".") == 1
+
+
+def test_config_struct_matches_header():
+    header = open(os.path.join(ROOT, "include", "moe_ep.h")).read()
+    body = re.search(r"typedef struct \{(.*?)\} moe_ep_config;", header, flags=re.S).group(1)
+    body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+    fields = re.findall(r"int32_t\s+(\w+)\s*;", body)
+    assert fields == [f[0] for f in MoeEpConfig._fields_]
+    assert ctypes.sizeof(MoeEpConfig) == 4 * len(fields)
+
+
+def test_valid_config_and_workspace_size():
+    cfg = _good()
+    assert pkg.validate_config(cfg) == (0, "ok")
+    ws = pkg.workspace_bytes(cfg)
+    # grouped input + grouped output rows alone: A_max * M * 2 bytes each
+    assert ws >= 2 * 128 * 2 * 256 * 2
+    assert pkg.workspace_bytes(_good(hidden=100)) == 0
+
+
+@pytest.mark.parametrize("kw,word", [
+    (dict(hidden=100), "hidden"), (dict(hidden=0), "hidden"), (dict(inter=96), "inter"),
+    (dict(n_experts=0), "n_experts"), (dict(n_experts=513, n_local=8), "n_experts"),
+    (dict(n_local=0), "local"), (dict(local_begin=4, n_local=5), "local"),
+    (dict(local_begin=-1), "local"), (dict(n_shared=-1), "n_shared"),
+    (dict(n_shared=1, shared_inter=0), "shared_inter"), (dict(max_tokens=0), "max_tokens"),
+    (dict(max_top_k=0), "max_top_k"), (dict(max_top_k=9), "max_top_k"),
+    (dict(max_top_k=65, n_experts=128, n_local=8), "max_top_k"),
+    (dict(max_chunks=0), "max_chunks"), (dict(max_chunks=65), "max_chunks"),
+    (dict(io_mode=2), "io_mode"), (dict(device=-1), "device"),
+])
+def test_bad_config_is_rejected_with_a_reason(kw, word):
+    rc, why = pkg.validate_config(_good(**kw))
+    assert rc == -1 and word in why
+
+
+def test_create_rejects_bad_config_without_touching_hip():
+    lib = pkg.load_library()
+    ctx = ctypes.c_void_p()
+    cfg = _good(hidden=100)
+    assert lib.moe_ep_create(ctypes.byref(cfg), ctypes.byref(ctx)) == -1
+    assert not ctx.value
+    assert lib.moe_ep_create(ctypes.byref(_good()), None) == -1
+    assert lib.moe_ep_destroy(None) == 0
+    assert lib.moe_ep_forward(None, None, None, None, None, 1, 1, 0, 0, None, None) == -1
+
+
+@pytest.mark.parametrize("kw,word", [
+    (dict(top_k=0), "top_k"), (dict(top_k=3), "top_k"), (dict(r_chunks=0), "r_chunks"),
+    (dict(r_chunks=9), "r_chunks"), (dict(n_tokens=-1), "n_tokens"),
+    (dict(n_tokens=129), "n_tokens"), (dict(order=2), "order"), (dict(routed_w=None), "routed_w"),
+    (dict(shared_w=None), "shared_w"), (dict(tokens=None), "tokens"), (dict(out=None), "tokens"),
+    (dict(gate_logits=None), "tokens"),
+])
+def test_bad_forward_arguments_are_rejected(kw, word):
+    args = dict(tokens=0x1000, gate_logits=0x2000, routed_w=0x3000, shared_w=0x4000, top_k=2,
+                r_chunks=1, order=0, n_tokens=128, out=0x5000)
+    assert pkg.validate_forward(_good(), **args) == (0, "ok")
+    args.update(kw)
+    rc, why = pkg.validate_forward(_good(), **args)
+    assert rc == -1 and word in why
+
+
+def test_forward_edge_arguments_that_are_legal():
+    base = dict(tokens=0x1000, gate_logits=0x2000, routed_w=0x3000, shared_w=0x4000, top_k=2,
+                r_chunks=8, order=1, n_tokens=3, out=0x5000)
+    assert pkg.validate_forward(_good(), **base)[0] == 0          # r_chunks > n_tokens
+    base.update(n_tokens=0, tokens=None, gate_logits=None, out=None)
+    assert pkg.validate_forward(_good(), **base)[0] == 0          # empty call is a no-op
+    noshared = _good(n_shared=0, shared_inter=0)
+    args = dict(base, shared_w=None, order=77)                     # order ignored without shared
+    assert pkg.validate_forward(noshared, **args)[0] == 0
+    assert pkg.validate_forward(noshared, **dict(args, shared_w=0x4000))[0] == -1

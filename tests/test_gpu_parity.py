@@ -1,0 +1,261 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same
+seeded inputs.  Integer results (selected experts, counts, offsets, permutation) must be
+bit-exact; outputs must satisfy max_i |gpu_i - ref_i| / max(|ref_i|, rms(ref)) <= 2e-2
+(bf16 inputs, fp32 accumulation, activation and expert outputs rounded to bf16 once)."""
+import numpy as np
+import pytest
+
+import oracle
+from helpers import rel_err
+from workloads import CONFIGS, bf16_bits_to_f32, make_inputs, tiny_workload
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+TOL = 2e-2
+W_TOL = 2e-6  # routing weights: fp32 exp and division against the fp64 oracle
+
+
+def _gpu():
+    import gpu_util
+    return gpu_util
+
+
+def _oracle_full(inp, wl, r=1):
+    return oracle.forward(inp["tokens"], inp["gate_logits"], inp["routed_w"], inp["shared_w"],
+                          hidden=wl.hidden, inter=wl.inter, n_experts=wl.n_experts,
+                          local_begin=wl.local_begin, n_local=wl.n_local, n_shared=wl.n_shared,
+                          shared_inter=wl.shared_inter, top_k=wl.top_k, r_chunks=r)
+
+
+def _check_routing(ctx, ref, r, T, k):
+    """Every chunk's routing against the oracle run with the same r: bit-exact."""
+    Tc = (T + r - 1) // r
+    for c in range(r):
+        got = ctx.get_routing(c)
+        t0 = c * Tc
+        Tn = 0 if t0 >= T else min(Tc, T - t0)
+        assert np.array_equal(got["idx"], ref["idx"][t0:t0 + Tn]), f"idx differs in chunk {c}"
+        assert np.array_equal(got["count"], ref["count"][c]), f"count differs in chunk {c}"
+        assert np.array_equal(got["offset"], ref["offset"][c]), f"offset differs in chunk {c}"
+        A = int(ref["offset"][c][-1])
+        assert np.array_equal(got["perm"], ref["perm"][c][:A]), f"perm differs in chunk {c}"
+        assert np.array_equal(got["pos"], ref["pos"][t0:t0 + Tn]), f"pos differs in chunk {c}"
+        if Tn:
+            assert np.max(np.abs(got["w"].astype(np.float64) - ref["w"][t0:t0 + Tn])) <= W_TOL
+
+
+def _full_parity(wl, seed=0, r=1, order=0, mutate=None):
+    g = _gpu()
+    inp = make_inputs(wl, seed=seed)
+    if mutate:
+        mutate(inp)
+    print(f"[case] {wl.name} T={wl.n_tokens} M={wl.hidden} H={wl.inter} E={wl.n_experts} "
+          f"El={wl.n_local}@{wl.local_begin} k={wl.top_k} Ns={wl.n_shared} r={r} order={order} "
+          f"seed={seed}", flush=True)
+    ref = _oracle_full(inp, wl, r)
+    ctx = g.make_ctx(wl, max_chunks=max(r, 1))
+    d = g.DeviceInputs(wl, inp)
+    out = g.run_forward(ctx, wl, d, r=r, order=order)
+    _check_routing(ctx, ref, r, wl.n_tokens, wl.top_k)
+    err = rel_err(bf16_bits_to_f32(out), ref["out"])
+    print(f"       rel_err={err:.3e}", flush=True)
+    assert err <= TOL
+    ctx.destroy()
+    return out, ref
+
+
+# ------------------------------------------------------------------ element by element
+def test_tiny_config_matches_oracle():
+    _full_parity(CONFIGS["tiny"])
+
+
+@pytest.mark.parametrize("r,order", [(1, 0), (3, 1), (8, 0)])
+def test_ragged_multi_tile_local_share(r, order):
+    """Several row tiles per expert with ragged tails, a column tail, a local share that
+    starts at expert 2, E not a multiple of 64, two shared experts."""
+    wl = tiny_workload(name="ragged", n_tokens=777, hidden=192, inter=320, n_experts=10,
+                       local_begin=2, n_local=6, top_k=3, n_shared=2, shared_inter=192)
+    _full_parity(wl, seed=21, r=r, order=order)
+
+
+def test_skewed_load_with_empty_experts():
+    wl = tiny_workload(name="skew", n_tokens=600, hidden=128, inter=128, n_experts=70,
+                       n_local=70, top_k=4)
+
+    def mutate(inp):
+        inp["gate_logits"][:, 5] += 30.0      # one expert takes every token
+        inp["gate_logits"][:, 40:60] -= 30.0  # twenty experts get none
+
+    out, ref = _full_parity(wl, seed=22, mutate=mutate)
+    assert ref["count"][0][5] == 600 and np.all(ref["count"][0][40:60] == 0)
+
+
+def test_quantised_logits_ties_are_bit_exact():
+    wl = tiny_workload(name="ties", n_tokens=500, hidden=64, inter=64, n_experts=160,
+                       local_begin=0, n_local=160, top_k=6)
+
+    def mutate(inp):
+        inp["gate_logits"][:] = np.round(inp["gate_logits"] * 2.0) / 2.0
+        inp["gate_logits"][::7] = 0.0          # all-equal rows, signed zeros included
+        inp["gate_logits"][::14, ::2] = -0.0
+
+    _full_parity(wl, seed=23, mutate=mutate)
+
+
+@pytest.mark.parametrize("k,E", [(1, 8), (8, 8), (1, 1)])
+def test_top_k_extremes(k, E):
+    wl = tiny_workload(name=f"k{k}E{E}", n_tokens=130, hidden=64, inter=128, n_experts=E,
+                       n_local=E, top_k=k)
+    _full_parity(wl, seed=24)
+
+
+def test_no_token_selects_a_local_expert():
+    wl = tiny_workload(name="none_local", n_tokens=100, hidden=64, inter=64, n_experts=8,
+                       local_begin=6, n_local=2, top_k=2)
+
+    def mutate(inp):
+        inp["gate_logits"][:, 6:] = -40.0
+
+    out, ref = _full_parity(wl, seed=25, mutate=mutate)
+    assert ref["count"].sum() == 0 and not out.any()       # exact zeros
+
+
+def test_single_token_and_empty_call():
+    g = _gpu()
+    wl = tiny_workload(name="one", n_tokens=1, hidden=64, inter=64, n_experts=8, n_local=8,
+                       top_k=2, n_shared=1, shared_inter=64)
+    _full_parity(wl, seed=26)
+    ctx = g.make_ctx(wl)
+    d = g.DeviceInputs(wl, make_inputs(wl, seed=26))
+    ctx.forward(d.tokens, d.logits, d.routed, d.shared, 2, 1, 0, n_tokens=0, out=d.out)
+    torch.cuda.synchronize()
+    assert not d.out.cpu().numpy().any()
+    ctx.destroy()
+
+
+# ------------------------------------------------------------------ invariants on the GPU
+def test_chunking_and_order_do_not_change_a_bit():
+    g = _gpu()
+    wl = CONFIGS["tiny"]
+    inp = make_inputs(wl)
+    ctx = g.make_ctx(wl, max_chunks=64)
+    d = g.DeviceInputs(wl, inp)
+    base = g.run_forward(ctx, wl, d, r=1, order=0)
+    for r, order in [(1, 1), (2, 0), (4, 1), (7, 0), (64, 1)]:
+        print(f"[case] tiny r={r} order={order}", flush=True)
+        out = g.run_forward(ctx, wl, d, r=r, order=order)
+        assert np.array_equal(out, base), f"r={r} order={order} changed the output bits"
+    ctx.destroy()
+
+
+def test_context_reuse_with_fewer_tokens():
+    """A context sized for more tokens serves a smaller call; stale workspace rows do not leak."""
+    g = _gpu()
+    wl = CONFIGS["tiny"]
+    inp = make_inputs(wl)
+    ctx = g.make_ctx(wl)
+    d = g.DeviceInputs(wl, inp)
+    full = g.run_forward(ctx, wl, d)
+    part = g.run_forward(ctx, wl, d, n_tokens=50)
+    assert np.array_equal(part, full[:50])
+    ctx.destroy()
+
+
+def test_pinned_host_pipeline_matches_device_mode():
+    g = _gpu()
+    wl = tiny_workload(name="pinned", n_tokens=700, hidden=256, inter=192, n_experts=16,
+                       local_begin=4, n_local=8, top_k=4, n_shared=1, shared_inter=128)
+    inp = make_inputs(wl, seed=27)
+    ctx = g.make_ctx(wl)
+    base = g.run_forward(ctx, wl, g.DeviceInputs(wl, inp))
+    ctx.destroy()
+    pctx = g.make_ctx(wl, pinned=True)
+    pd = g.DeviceInputs(wl, inp, pinned=True)
+    for r, order in [(1, 0), (4, 1), (8, 0)]:
+        print(f"[case] pinned r={r} order={order}", flush=True)
+        out = g.run_forward(pctx, wl, pd, r=r, order=order)
+        assert np.array_equal(out, base)
+    pctx.destroy()
+
+
+def test_errors_surface_as_status_codes():
+    g = _gpu()
+    import paper_2512_21487_amd as pkg
+    wl = CONFIGS["tiny"]
+    ctx = g.make_ctx(wl)
+    d = g.DeviceInputs(wl, make_inputs(wl))
+    with pytest.raises(pkg.MoeEpError) as ei:
+        ctx.forward(d.tokens, d.logits, d.routed, d.shared, 3, 1, 0, out=d.out)
+    assert ei.value.code == -1 and "top_k" in str(ei.value)
+    with pytest.raises(pkg.MoeEpError):
+        ctx.forward(d.tokens, d.logits, d.routed, None, 2, 1, 0, out=d.out)
+    g.run_forward(ctx, wl, d)  # still usable afterwards
+    ctx.destroy()
+
+
+# ------------------------------------------------------------------ full-size configurations
+def _sampled_parity(name, variants, pinned=False, n_sample=24):
+    """At the benchmark's sizes: routing of every token bit-exact, outputs of sampled tokens
+    against the oracle, and every (r, order) variant bit-identical to the first."""
+    g = _gpu()
+    wl = CONFIGS[name]
+    inp = make_inputs(wl)
+    T, k = wl.n_tokens, wl.top_k
+    idx, w = oracle.router(inp["gate_logits"], k)
+    local = (idx >= wl.local_begin) & (idx < wl.local_begin + wl.n_local)
+    rng = np.random.default_rng(1234)
+    ids = np.unique(np.concatenate([[0, T - 1], rng.integers(0, T, n_sample)])).astype(np.int32)
+    ref_rows = oracle.forward_tokens(inp["tokens"], inp["gate_logits"], inp["routed_w"],
+                                     inp["shared_w"], ids, hidden=wl.hidden, inter=wl.inter,
+                                     n_experts=wl.n_experts, local_begin=wl.local_begin,
+                                     n_local=wl.n_local, n_shared=wl.n_shared,
+                                     shared_inter=wl.shared_inter, top_k=k)
+    ctx = g.make_ctx(wl, pinned=pinned)
+    d = g.DeviceInputs(wl, inp, pinned=pinned)
+    first = None
+    for r, order in variants:
+        print(f"[case] {name} r={r} order={order} pinned={pinned}", flush=True)
+        out = g.run_forward(ctx, wl, d, r=r, order=order)
+        Tc = (T + r - 1) // r
+        kept_total = 0
+        for c in range(r):
+            t0 = c * Tc
+            Tn = 0 if t0 >= T else min(Tc, T - t0)
+            got = ctx.get_routing(c)
+            ref = oracle.dispatch(idx[t0:t0 + Tn], wl.local_begin, wl.n_local)
+            assert np.array_equal(got["idx"], idx[t0:t0 + Tn])
+            for key in ("count", "offset", "perm", "pos"):
+                assert np.array_equal(got[key], ref[key]), f"{key} differs in chunk {c}"
+            assert np.max(np.abs(got["w"].astype(np.float64) - w[t0:t0 + Tn])) <= W_TOL
+            kept_total += int(ref["offset"][-1])
+        assert kept_total == int(local.sum())      # token conservation over the chunks
+        err = rel_err(bf16_bits_to_f32(out[ids]), ref_rows)
+        print(f"       sampled rel_err={err:.3e} over {ids.size} tokens, kept={kept_total}",
+              flush=True)
+        assert err <= TOL
+        if wl.n_shared == 0:                       # rows with nothing kept are exact zeros
+            assert not out[~local.any(axis=1)].any()
+        if first is None:
+            first = out
+        else:
+            assert np.array_equal(out, first), f"r={r} order={order} changed the output bits"
+    ctx.destroy()
+
+
+def test_dsv2_lite_full_size():
+    _sampled_parity("dsv2_lite", [(1, 0), (4, 1)])
+
+
+def test_qwen3_30b_full_size_skewed():
+    _sampled_parity("qwen3_30b", [(1, 0), (8, 0)])
+
+
+def test_dsv2_expert_group_share_full_size():
+    _sampled_parity("dsv2_eg", [(1, 0), (8, 1), (2, 0)])
+
+
+@pytest.mark.parametrize("name,r", [("qwen3_235b_eg_256", 8), ("qwen3_235b_eg_1024", 2),
+                                    ("qwen3_235b_eg_4096", 4)])
+def test_qwen3_235b_expert_group_share_decode_pinned(name, r):
+    _sampled_parity(name, [(1, 0), (r, 0)], pinned=True)
