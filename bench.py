@@ -1,0 +1,181 @@
+#!/usr/bin/env python3
+"""Benchmark of the expert-group MoE layer on one MI355X.
+
+A step is one moe_ep_forward (gate, partition, routed gate/up + down grouped GEMM, shared
+experts, aggregation, all r chunks) over one batch of synthetic input that is already
+resident where the context expects it.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--r R] [--order O]
+                    [--variant V] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 matrix peak
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E peak
+
+
+def cpu_baseline(wl, inp, budget_s=15.0):
+    """The CPU oracle, as it stands, on a bounded sample of the same workload's tokens."""
+    import numpy as np
+    import oracle
+    kw = dict(hidden=wl.hidden, inter=wl.inter, n_experts=wl.n_experts, local_begin=wl.local_begin,
+              n_local=wl.n_local, n_shared=wl.n_shared, shared_inter=wl.shared_inter,
+              top_k=wl.top_k)
+    cores = oracle.threads()
+    n = min(wl.n_tokens, 2 * cores)
+    ids = np.arange(n, dtype=np.int32)
+    t0 = time.perf_counter()
+    oracle.forward_tokens(inp["tokens"], inp["gate_logits"], inp["routed_w"], inp["shared_w"], ids, **kw)
+    dt = time.perf_counter() - t0
+    total_n, total_t = n, dt
+    n2 = int(min(wl.n_tokens - n, max(0, (budget_s - dt) / max(dt / n, 1e-9))))
+    n2 = (n2 // cores) * cores
+    if n2 > 0:
+        ids = np.arange(n, n + n2, dtype=np.int32)
+        t0 = time.perf_counter()
+        oracle.forward_tokens(inp["tokens"], inp["gate_logits"], inp["routed_w"], inp["shared_w"], ids, **kw)
+        total_t += time.perf_counter() - t0
+        total_n += n2
+    return {"value": total_n / total_t, "unit": "tokens/s", "cores": cores, "kind": "oracle",
+            "sample": f"first {total_n} tokens of the workload through oracle.forward_tokens "
+                      f"(fp64, plain C) in {total_t:.1f} s"}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="dsv2_eg")
+    ap.add_argument("--r", type=int, default=1, help="r_chunks")
+    ap.add_argument("--order", type=int, default=0, help="0 shared first, 1 interleaved")
+    ap.add_argument("--variant", type=int, default=None, help="GEMM tile variant (tuning)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build drives one GPU only (no collectives, no sharding); "
+              "run with --gpus 1", file=sys.stderr)
+        return 2
+    if args.variant is not None:
+        os.environ["MOE_EP_GEMM_VARIANT"] = str(args.variant)
+
+    import numpy as np
+    import torch
+
+    import paper_2512_21487_amd as pkg
+    from workloads import CONFIGS, make_inputs
+
+    wl = CONFIGS[args.workload]
+    torch.cuda.set_device(0)
+    inp = make_inputs(wl)
+    T, M, H, k = wl.n_tokens, wl.hidden, wl.inter, wl.top_k
+    pinned = wl.pinned_io
+
+    def put(a, host=False):
+        a = a.view(np.int16) if a.dtype == np.uint16 else a
+        t = torch.from_numpy(np.ascontiguousarray(a))
+        if host:
+            p = torch.empty(t.shape, dtype=t.dtype, pin_memory=True)
+            p.copy_(t)
+            return p
+        return t.cuda()
+
+    tokens, logits = put(inp["tokens"], pinned), put(inp["gate_logits"], pinned)
+    routed = put(inp["routed_w"])
+    shared = put(inp["shared_w"]) if inp["shared_w"] is not None else None
+    if pinned:
+        out = torch.zeros((T, M), dtype=torch.int16, pin_memory=True)
+    else:
+        out = torch.zeros((T, M), dtype=torch.int16, device="cuda")
+    ctx = pkg.MoeEp(hidden=M, inter=H, n_experts=wl.n_experts, local_begin=wl.local_begin,
+                    n_local=wl.n_local, n_shared=wl.n_shared, shared_inter=wl.shared_inter,
+                    max_tokens=T, max_top_k=k, max_chunks=max(args.r, 1),
+                    io_mode=pkg.IO_PINNED_HOST if pinned else pkg.IO_DEVICE)
+    stream = torch.cuda.current_stream().cuda_stream
+
+    def step():
+        ctx.forward(tokens, logits, routed, shared, k, args.r, args.order, n_tokens=T, out=out,
+                    stream=stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ctx.set_profiling(args.steps)          # HIP events around every stage, on the stage's stream
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    stages = ctx.get_stage_ms()
+    ctx.set_profiling(0)
+
+    kept = sum(int(ctx.get_routing(c)["offset"][-1]) for c in range(args.r))
+    ms_per_step = dt / args.steps * 1e3
+    value = T * args.steps / dt
+
+    def gemm_line(flop, ms):
+        if ms <= 0:
+            return None
+        ach = flop / (ms * 1e-3) / 1e12
+        return {"bound": "mfma", "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                "frac": ach / PEAK_BF16_TFLOPS, "ms_per_step": ms}
+
+    def hbm_line(nbytes, ms):
+        if ms <= 0:
+            return None
+        ach = nbytes / (ms * 1e-3) / 1e9
+        return {"bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                "frac": ach / PEAK_HBM_GBS, "ms_per_step": ms}
+
+    Ns, Hs = wl.n_shared, wl.shared_inter
+    kernels = {
+        "routed_gate_up_gemm": gemm_line(4.0 * kept * M * H, stages["routed_gate_up_gemm"]),
+        "routed_down_gemm": gemm_line(2.0 * kept * M * H, stages["routed_down_gemm"]),
+        "shared_gate_up_gemm": gemm_line(4.0 * T * Ns * M * Hs, stages["shared_gate_up_gemm"]),
+        "shared_down_gemm": gemm_line(2.0 * T * Ns * M * Hs, stages["shared_down_gemm"]),
+        # partition: per kept row 2M bytes read + 2M written, plus the routing arrays
+        "partition": hbm_line(kept * 4.0 * M + T * k * 16.0, stages["partition"]),
+        # aggregation: per kept row 2M bytes read, per token 2M written (+2M shared read)
+        "aggregation": hbm_line(kept * 2.0 * M + T * 2.0 * M * (2 if Ns else 1), stages["aggregation"]),
+        "router": hbm_line(T * (4.0 * wl.n_experts + 8.0 * k), stages["router"]),
+    }
+    routed_ms = stages["routed_gate_up_gemm"] + stages["routed_down_gemm"]
+    routed = gemm_line(6.0 * kept * M * H, routed_ms)
+    roof = dict(kernels["routed_gate_up_gemm"] or {})
+    roof.pop("ms_per_step", None)
+    roof["traffic"] = None
+    roof["kernel"] = "grouped_gemm_kernel<128,256,2,2,swiglu,ragged> (routed gate/up projection)"
+
+    line = {
+        "metric": "expert-layer tokens/sec at 1 GPU; grouped-GEMM % of bf16 MFMA peak",
+        "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{wl.name}: T={T} M={M} H={H} E={wl.n_experts} local={wl.n_local} "
+                               f"top_k={k} shared={Ns}x{Hs} io={'pinned_host' if pinned else 'device'}",
+                   "r_chunks": args.r, "order": args.order, "kept_assignments": kept},
+        "grouped_gemm_pct_of_bf16_mfma_peak": None if routed is None else 100.0 * routed["frac"],
+        "roofline": roof,
+        "kernels": kernels,
+        "stage_ms": stages,
+    }
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(wl, inp)
+    ctx.destroy()
+    print(json.dumps(line))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

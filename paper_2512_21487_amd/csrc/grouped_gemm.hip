@@ -46,7 +46,7 @@ struct GemmCfg {
 
 __device__ __forceinline__ float silu_f(float g) { return g / (1.0f + __expf(-g)); }
 
-template <int BM, int BN, int WGM, int WGN, bool SWIGLU>
+template <int BM, int BN, int WGM, int WGN, bool SWIGLU, bool RAGGED>
 __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_kernel(GemmArgs a)
 {
     using Cfg = GemmCfg<BM, BN, WGM, WGN, SWIGLU>;
@@ -58,7 +58,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_kernel(GemmArgs a)
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WGN, wn = wave % WGN;
-    const bool ragged = (a.offset != nullptr);
+    constexpr bool ragged = RAGGED;  // routed experts: ragged groups from device prefix sums; shared: dense
     const int NT = (a.N + BN_OUT - 1) / BN_OUT;
     int mt_total, mt_per = 0;
     if (ragged) {
@@ -231,7 +231,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_kernel(GemmArgs a)
     }
 }
 
-template <int BM, int BN, int WGM, int WGN, bool SWIGLU>
+template <int BM, int BN, int WGM, int WGN, bool SWIGLU, bool RAGGED>
 static hipError_t launch_variant(const GemmArgs& a, int n_cu, int max_row_tiles, hipStream_t s)
 {
     using Cfg = GemmCfg<BM, BN, WGM, WGN, SWIGLU>;
@@ -242,40 +242,53 @@ static hipError_t launch_variant(const GemmArgs& a, int n_cu, int max_row_tiles,
     long long grid = (long long)n_cu * occ;
     if (grid > max_tiles) grid = max_tiles;
     grid = (grid + 7) / 8 * 8;
-    hipLaunchKernelGGL((grouped_gemm_kernel<BM, BN, WGM, WGN, SWIGLU>), dim3((unsigned)grid),
+    hipLaunchKernelGGL((grouped_gemm_kernel<BM, BN, WGM, WGN, SWIGLU, RAGGED>), dim3((unsigned)grid),
                        dim3(Cfg::THREADS), Cfg::LDS_BYTES, s, a);
     return hipGetLastError();
 }
 
-template <int BM, int BN, int WGM, int WGN, bool SWIGLU>
+template <int BM, int BN, int WGM, int WGN, bool SWIGLU, bool RAGGED>
 static hipError_t raise_lds_limit()
 {
     using Cfg = GemmCfg<BM, BN, WGM, WGN, SWIGLU>;
     return hipFuncSetAttribute(
-        reinterpret_cast<const void*>(&grouped_gemm_kernel<BM, BN, WGM, WGN, SWIGLU>),
+        reinterpret_cast<const void*>(&grouped_gemm_kernel<BM, BN, WGM, WGN, SWIGLU, RAGGED>),
         hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::LDS_BYTES);
+}
+
+template <int BN>
+static hipError_t raise_all()
+{
+    hipError_t e;
+    if ((e = raise_lds_limit<kBM, BN, 2, 2, true, true>()) != hipSuccess) return e;
+    if ((e = raise_lds_limit<kBM, BN, 2, 2, true, false>()) != hipSuccess) return e;
+    if ((e = raise_lds_limit<kBM, BN, 2, 2, false, true>()) != hipSuccess) return e;
+    return raise_lds_limit<kBM, BN, 2, 2, false, false>();
 }
 
 hipError_t grouped_gemm_init()
 {
-    hipError_t e;
-    if ((e = raise_lds_limit<kBM, 256, 2, 2, true>()) != hipSuccess) return e;
-    if ((e = raise_lds_limit<kBM, 256, 2, 2, false>()) != hipSuccess) return e;
-    if ((e = raise_lds_limit<kBM, 128, 2, 2, true>()) != hipSuccess) return e;
-    if ((e = raise_lds_limit<kBM, 128, 2, 2, false>()) != hipSuccess) return e;
-    return hipSuccess;
+    hipError_t e = raise_all<256>();
+    return e != hipSuccess ? e : raise_all<128>();
 }
 
 int grouped_gemm_row_tile() { return kBM; }
 
+template <int BN>
+static hipError_t launch_bn(const GemmArgs& a, bool swiglu, int n_cu, int max_row_tiles, hipStream_t s)
+{
+    const bool ragged = a.offset != nullptr;
+    if (swiglu) return ragged ? launch_variant<kBM, BN, 2, 2, true, true>(a, n_cu, max_row_tiles, s)
+                              : launch_variant<kBM, BN, 2, 2, true, false>(a, n_cu, max_row_tiles, s);
+    return ragged ? launch_variant<kBM, BN, 2, 2, false, true>(a, n_cu, max_row_tiles, s)
+                  : launch_variant<kBM, BN, 2, 2, false, false>(a, n_cu, max_row_tiles, s);
+}
+
 hipError_t launch_grouped_gemm(const GemmArgs& a, bool swiglu, int variant, int n_cu,
                                int max_row_tiles, hipStream_t s)
 {
-    if (variant == 1)
-        return swiglu ? launch_variant<kBM, 128, 2, 2, true>(a, n_cu, max_row_tiles, s)
-                      : launch_variant<kBM, 128, 2, 2, false>(a, n_cu, max_row_tiles, s);
-    return swiglu ? launch_variant<kBM, 256, 2, 2, true>(a, n_cu, max_row_tiles, s)
-                  : launch_variant<kBM, 256, 2, 2, false>(a, n_cu, max_row_tiles, s);
+    if (variant == 1) return launch_bn<128>(a, swiglu, n_cu, max_row_tiles, s);
+    return launch_bn<256>(a, swiglu, n_cu, max_row_tiles, s);
 }
 
 }  // namespace moe_ep
