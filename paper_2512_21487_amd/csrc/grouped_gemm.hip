@@ -13,10 +13,14 @@
 // share a weight panel through that XCD's L2.  The id -> workgroup map hands each XCD
 // contiguous runs of tile ids (workgroup b runs on XCD b mod 8).
 //
-// LDS tiles are [rows][64] bf16 (128 B per row, eight 16-byte chunks) with the chunk index
-// XOR-ed by bits 1..3 of the row, which makes both the 16-byte staging stores and the
-// MFMA fragment loads conflict-free.  Two stages: global -> registers for step kt+1 is in
-// flight while step kt is multiplied out of LDS; one barrier per step.
+// Data movement: global_load_lds_dwordx4 moves 16 bytes per lane from global memory straight
+// into LDS (no staging registers, no ds_write), into a ring of STAGES K-steps: while step kt
+// is multiplied, the loads of the next STAGES-1 steps are in flight.  One wave instruction
+// fills 1 KB of LDS in lane order; LDS rows are BK bf16 wide and their 16-byte chunks are
+// XOR-swizzled by the row so that MFMA fragment reads are bank-conflict free.  The swizzle
+// is applied on the global side: lane l fetches the chunk that belongs at physical slot l.
+// The loads are asynchronous: each wavefront counts its own with s_waitcnt vmcnt(n), then a
+// raw s_barrier publishes every wavefront's rows (one barrier per K step).
 //
 // SwiGLU: the weight tile holds BN/2 rows of W_gate and the matching BN/2 rows of W_up; a
 // wavefront's accumulator blocks pair a gate block with the up block of the same columns,
@@ -26,65 +30,74 @@
 
 namespace moe_ep {
 
-constexpr int kBM = 128;  // rows per tile, shared by all variants (the scan kernel counts row tiles with it)
-
-template <int BM, int BN, int WGM, int WGN, bool SWIGLU>
+template <int BM, int BN, int BK_, int STAGES_, int WGM, int WGN, int KG_, bool SWIGLU>
 struct GemmCfg {
-    static constexpr int BK = 64;
-    static constexpr int THREADS = WGM * WGN * 64;
+    static constexpr int BK = BK_, STAGES = STAGES_;
+    static constexpr int CPR = BK / 8;             // 16-byte chunks per LDS row
+    static constexpr int RP = 16 / CPR;            // LDS rows per 256 bytes (one sweep over all banks)
+    static constexpr int RPR = 64 / CPR;           // LDS rows per 1 KB region (one wave load instruction)
+    static constexpr int KG = KG_;                 // wavefront groups that split every K step between them
+    static constexpr int KKW = BK / 16 / KG;       // MFMA k16 steps per K step and wavefront
+    static constexpr int NW = WGM * WGN * KG, THREADS = NW * 64;
     static constexpr int WTM = BM / WGM, WTN = BN / WGN;
     static constexpr int MB = WTM / 32, NB = WTN / 32;
-    static constexpr int XL = BM * 8 / THREADS, WL = BN * 8 / THREADS;
-    static constexpr int ROWS_PER_PASS = THREADS / 8;
-    static constexpr int STAGE_CHUNKS = (BM + BN) * 8;
-    static constexpr int LDS_BYTES = 2 * STAGE_CHUNKS * 16;
+    static constexpr int REGIONS = (BM + BN) / RPR;
+    static constexpr int RPW = REGIONS / NW;       // regions each wavefront loads per stage
+    static constexpr int XRPW = (BM / RPR) / NW;   // of which activation regions
+    static constexpr int STAGE_CHUNKS = (BM + BN) * CPR;
+    static constexpr int LDS_BYTES = STAGES * STAGE_CHUNKS * 16;
     static constexpr int BN_OUT = SWIGLU ? BN / 2 : BN;
+    static_assert(BK == 32 || BK == 64, "LDS rows are 64 or 128 bytes");
     static_assert(BM % (WGM * 32) == 0 && BN % (WGN * 32) == 0, "wave tiles are 32x32 blocks");
     static_assert(!SWIGLU || NB % 2 == 0, "gate/up blocks pair up inside a wavefront");
-    static_assert((BM * 8) % THREADS == 0 && (BN * 8) % THREADS == 0, "whole staging passes");
+    static_assert((BM / RPR) % NW == 0 && (BN / RPR) % NW == 0, "regions split evenly over wavefronts");
+    static_assert(STAGES >= 2 && STAGES <= 5 && (STAGES - 2) * RPW <= 63, "ring depth and vmcnt budget");
+    static_assert(KG == 1 || (KG == 2 && MB % 2 == 0 && KKW >= 1), "K split over two wavefront groups");
+    static_assert(KG == 1 || LDS_BYTES >= NW * (MB / 2) * NB * 1024, "partial sums are exchanged through the ring's LDS");
 };
 
 __device__ __forceinline__ float silu_f(float g) { return g / (1.0f + __expf(-g)); }
 
-template <int BM, int BN, int WGM, int WGN, bool SWIGLU, bool RAGGED>
-__global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_kernel(GemmArgs a)
+// s_waitcnt with only vmcnt constrained (gfx9 encoding: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[5:4] << 14)
+#define MOE_EP_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | (((n) >> 4) << 14) | 0x0F70)
+
+template <int BM, int BN, int BK, int STAGES, int WGM, int WGN, int KG, bool SWIGLU, bool RAGGED>
+__global__ __launch_bounds__(WGM* WGN* KG * 64) void grouped_gemm_kernel(GemmArgs a)
 {
-    using Cfg = GemmCfg<BM, BN, WGM, WGN, SWIGLU>;
-    constexpr int MB = Cfg::MB, NB = Cfg::NB, XL = Cfg::XL, WL = Cfg::WL;
-    constexpr int THREADS = Cfg::THREADS, BN_OUT = Cfg::BN_OUT;
+    using Cfg = GemmCfg<BM, BN, BK, STAGES, WGM, WGN, KG, SWIGLU>;
+    constexpr int MB = Cfg::MB, NB = Cfg::NB, RPW = Cfg::RPW, XRPW = Cfg::XRPW, NW = Cfg::NW;
+    constexpr int THREADS = Cfg::THREADS, BN_OUT = Cfg::BN_OUT, CPR = Cfg::CPR, RP = Cfg::RP;
+    constexpr int RPR = Cfg::RPR, KKW = Cfg::KKW;
     extern __shared__ uint4 lds[];
     __shared__ int s_pref[513];
     __shared__ int s_off[513];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave / WGN, wn = wave % WGN;
-    constexpr bool ragged = RAGGED;  // routed experts: ragged groups from device prefix sums; shared: dense
+    const int wn = wave % WGN, wm = (wave / WGN) % WGM, kg = wave / (WGN * WGM);
     const int NT = (a.N + BN_OUT - 1) / BN_OUT;
     int mt_total, mt_per = 0;
-    if (ragged) {
+    if (RAGGED) {  // routed experts: ragged groups described by device prefix sums
         for (int i = tid; i <= a.G; i += THREADS) { s_pref[i] = a.mt_prefix[i]; s_off[i] = a.offset[i]; }
         __syncthreads();
         mt_total = s_pref[a.G];
-    } else {
+    } else {       // shared experts: every group multiplies the same dense rows
         mt_per = (a.dense_rows + BM - 1) / BM;
         mt_total = mt_per * a.G;
     }
     const int total = mt_total * NT;
     const int per_xcd = gridDim.x >> 3;
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-    const int KT = a.K / Cfg::BK;
-
-    // staging geometry of this thread: chunk column c, first row r0, swizzled LDS chunk
-    const int c_ld = tid & 7, r0_ld = tid >> 3;
-    const int st_chunk = r0_ld * 8 + (c_ld ^ ((r0_ld >> 1) & 7));
-    // fragment geometry of this lane
-    const int fr_row = lane & 31, fr_sw = (lane >> 1) & 7, fr_kh = lane >> 5;
+    const int KT = a.K / BK;
+    // fragment geometry of this lane: row inside a 32-row block, swizzle term, k half
+    const int fr_row = lane & 31, fr_sw = ((lane & 31) / RP) % CPR, fr_kh = lane >> 5;
+    // load geometry of this lane: row inside a 1 KB region, physical chunk slot
+    const int ld_row = lane / CPR, ld_p = lane % CPR;
 
     for (int it = 0;; ++it) {
         const int L = (it * 8 + xcd) * per_xcd + slot;
         if (L >= total) break;
         int g, mi, ni, row0, nrows;
-        if (ragged) {
+        if (RAGGED) {
             int lo = 0, hi = a.G;
             while (hi - lo > 1) {
                 const int mid = (lo + hi) >> 1;
@@ -107,26 +120,28 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_kernel(GemmArgs a)
         const int n0 = ni * BN_OUT;
         const uint16_t* Wg = a.W + (size_t)g * a.w_group_stride;
 
-        // row pointers of the chunks this thread stages (rows past the end re-read the last valid row)
-        const uint16_t* xptr[XL];
-        const uint16_t* wptr[WL];
+        // per region this wavefront loads: the lane's global source (row, swizzled chunk)
+        const uint16_t* gptr[RPW];
 #pragma unroll
-        for (int i = 0; i < XL; ++i) {
-            const int r = min(r0_ld + i * Cfg::ROWS_PER_PASS, nrows - 1);
-            xptr[i] = a.A + (size_t)(row0 + r) * a.lda + c_ld * 8;
-        }
-#pragma unroll
-        for (int i = 0; i < WL; ++i) {
-            const int j = r0_ld + i * Cfg::ROWS_PER_PASS;  // row of the LDS weight tile
-            int n;
-            const uint16_t* base = Wg;
-            if (SWIGLU) {
-                if (j < BN / 2) n = n0 + j; else { n = n0 + j - BN / 2; base = Wg + a.w_up_offset; }
+        for (int i = 0; i < RPW; ++i) {
+            const int j = wave + NW * i;                 // region index inside a stage
+            const int r = j * RPR + ld_row;              // row in the stacked [activations; weights] tile
+            const int c = ld_p ^ ((r / RP) % CPR);       // logical chunk stored at physical slot ld_p
+            if (i < XRPW) {
+                const int rr = min(r, nrows - 1);        // rows past the end re-read the last valid row
+                gptr[i] = a.A + (size_t)(row0 + rr) * a.lda + c * 8;
             } else {
-                n = n0 + j;
+                const int jw = r - BM;                   // row of the weight tile
+                int n;
+                const uint16_t* base = Wg;
+                if (SWIGLU) {
+                    if (jw < BN / 2) n = n0 + jw; else { n = n0 + jw - BN / 2; base = Wg + a.w_up_offset; }
+                } else {
+                    n = n0 + jw;
+                }
+                n = min(n, a.N - 1);
+                gptr[i] = base + (size_t)n * a.ldw + c * 8;
             }
-            n = min(n, a.N - 1);
-            wptr[i] = base + (size_t)n * a.ldw + c_ld * 8;
         }
 
         f32x16_t acc[MB][NB];
@@ -137,58 +152,122 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_kernel(GemmArgs a)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[mb][nb][r] = 0.f;
 
-        uint4 xreg[XL], wreg[WL];
-        auto load_global = [&](int kt) {
-            const int k = kt * Cfg::BK;
-            const int seg = k / a.kseg_len;
-            const size_t wk = (size_t)seg * a.w_kseg_stride + (k - seg * a.kseg_len);
-#pragma unroll
-            for (int i = 0; i < XL; ++i) xreg[i] = *reinterpret_cast<const uint4*>(xptr[i] + k);
-#pragma unroll
-            for (int i = 0; i < WL; ++i) wreg[i] = *reinterpret_cast<const uint4*>(wptr[i] + wk);
+        // first LDS row of accumulator column block nb of this wavefront (stacked tile coordinates)
+        auto w_row_base = [&](int nb) -> int {
+            if (SWIGLU) return BM + ((nb < NB / 2) ? wn * (Cfg::WTN / 2) + nb * 32
+                                                   : BN / 2 + wn * (Cfg::WTN / 2) + (nb - NB / 2) * 32);
+            return BM + wn * Cfg::WTN + nb * 32;
         };
-        auto store_lds = [&](int buf) {
-            uint4* sX = lds + buf * Cfg::STAGE_CHUNKS;
-            uint4* sW = sX + BM * 8;
-#pragma unroll
-            for (int i = 0; i < XL; ++i) sX[st_chunk + i * Cfg::ROWS_PER_PASS * 8] = xreg[i];
-#pragma unroll
-            for (int i = 0; i < WL; ++i) sW[st_chunk + i * Cfg::ROWS_PER_PASS * 8] = wreg[i];
-        };
+        bf16x8_t xf[2][MB], wf[2][NB];
+        // one LDS fragment read: index f < MB is an activation block, f >= MB a weight block
+#define MOE_EP_FRAG1(kk_, set_, f_)                                                               \
+        {                                                                                         \
+            const int csw_ = ((kk_) * 2 + fr_kh) ^ fr_sw;                                         \
+            if ((f_) < MB) xf[set_][(f_) < MB ? (f_) : 0] = __builtin_bit_cast(bf16x8_t,          \
+                sT[(wm * Cfg::WTM + (f_) * 32 + fr_row) * CPR + csw_]);                           \
+            else wf[set_][(f_) >= MB ? (f_) - MB : 0] = __builtin_bit_cast(bf16x8_t,              \
+                sT[(w_row_base((f_) >= MB ? (f_) - MB : 0) + fr_row) * CPR + csw_]);              \
+        }
+        // one direct-to-LDS load: region i of this wavefront, K step kt_, ring slot stage_
+#define MOE_EP_ISSUE1(kt_, stage_, i_)                                                            \
+        {                                                                                         \
+            const int k_ = (kt_) * BK;                                                            \
+            const int seg_ = k_ / a.kseg_len;                                                     \
+            const size_t wk_ = (size_t)seg_ * a.w_kseg_stride + (k_ - seg_ * a.kseg_len);         \
+            uint4* dst_ = lds + (stage_) * Cfg::STAGE_CHUNKS + wave * 64 + NW * 64 * (i_);        \
+            __builtin_amdgcn_global_load_lds(                                                     \
+                reinterpret_cast<const uint4*>(gptr[i_] + ((i_) < XRPW ? (size_t)k_ : wk_)),      \
+                dst_, 16, 0, 0);                                                                  \
+        }
+#define SB() __builtin_amdgcn_sched_barrier(0)
+        // One K step.  The source order below is the issue order: sched_barrier(0) after every
+        // MFMA keeps the compiler from regrouping.  This wavefront multiplies k16 steps
+        // kg*KKW .. kg*KKW+KKW-1 of the K step; step i works out of fragment set i & 1 while the
+        // LDS reads of step i+1 and the global loads STAGES-1 K steps ahead are slipped between
+        // its MFMAs.  Fragment reads are ordered so that the first MFMA needs only the first two.
+#define MOE_EP_FRAG_ORDER(f_) ((f_) == 0 ? MB : (f_) <= MB ? (f_) - 1 : (f_))
+#define MOE_EP_STEP(kt_, pending_, issue_)                                                        \
+        {                                                                                         \
+            MOE_EP_WAIT_VMCNT(pending_);                                                          \
+            __builtin_amdgcn_s_barrier();                                                         \
+            asm volatile("" ::: "memory");                                                        \
+            const uint4* sT = lds + stage * Cfg::STAGE_CHUNKS;                                    \
+            const int st2 = stage == 0 ? STAGES - 1 : stage - 1;                                  \
+            _Pragma("unroll") for (int f = 0; f < MB + NB; ++f) MOE_EP_FRAG1(kg * KKW, 0, MOE_EP_FRAG_ORDER(f)) \
+            SB();                                                                                 \
+            _Pragma("unroll") for (int i = 0; i < KKW; ++i) {                                     \
+                _Pragma("unroll") for (int q = 0; q < MB * NB; ++q) {                             \
+                    const int nb = q / MB, mb = q % MB;                                           \
+                    acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[i & 1][nb], xf[i & 1][mb], acc[mb][nb], 0, 0, 0); \
+                    if (i + 1 < KKW && q < MB + NB) MOE_EP_FRAG1(kg * KKW + i + 1, (i + 1) & 1, MOE_EP_FRAG_ORDER(q)) \
+                    if (issue_) {                                              \
+                        _Pragma("unroll") for (int l = i * MB * NB + q; l < RPW; l += KKW * MB * NB) \
+                            MOE_EP_ISSUE1((kt_) + STAGES - 1, st2, l)                             \
+                    }                                                                             \
+                    SB();                                                                         \
+                }                                                                                 \
+            }                                                                                     \
+            stage = stage == STAGES - 1 ? 0 : stage + 1;                                          \
+        }
 
-        load_global(0);
-        store_lds(0);
-        __syncthreads();
-        for (int kt = 0; kt < KT; ++kt) {
-            const int buf = kt & 1;
-            if (kt + 1 < KT) load_global(kt + 1);
-            const uint4* sX = lds + buf * Cfg::STAGE_CHUNKS;
-            const uint4* sW = sX + BM * 8;
+        // prologue: the first STAGES-1 K steps go in flight
 #pragma unroll
-            for (int kk = 0; kk < 4; ++kk) {
-                const int csw = (kk * 2 + fr_kh) ^ fr_sw;
-                bf16x8_t xf[MB], wf[NB];
+        for (int p = 0; p < STAGES - 1; ++p)
+            if (p < KT) {
 #pragma unroll
-                for (int mb = 0; mb < MB; ++mb) {
-                    const int row = wm * Cfg::WTM + mb * 32 + fr_row;
-                    xf[mb] = __builtin_bit_cast(bf16x8_t, sX[row * 8 + csw]);
-                }
+                for (int i = 0; i < RPW; ++i) MOE_EP_ISSUE1(p, p, i)
+            }
+        int stage = 0;
+        int kt = 0;
+        for (; kt + STAGES - 1 < KT; ++kt) MOE_EP_STEP(kt, (STAGES - 2) * RPW, true)
+        // tail: no more loads to issue; the step that leaves p K steps in flight runs if KT > p
+        if constexpr (STAGES >= 5) { if (KT >= 4) MOE_EP_STEP(kt, 3 * RPW, false) }
+        if constexpr (STAGES >= 4) { if (KT >= 3) MOE_EP_STEP(kt, 2 * RPW, false) }
+        if constexpr (STAGES >= 3) { if (KT >= 2) MOE_EP_STEP(kt, 1 * RPW, false) }
+        MOE_EP_STEP(kt, 0, false)
+#undef MOE_EP_STEP
+#undef MOE_EP_FRAG_ORDER
+#undef SB
+#undef MOE_EP_ISSUE1
+#undef MOE_EP_FRAG1
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();  // every wavefront is done reading the ring
+        // K split: the two wavefronts that share an output block swap halves of their partial
+        // sums through LDS (lane-major, so both sides index identically) and each finishes one half.
+        int mb_lo = 0, mb_hi = MB;
+        if constexpr (KG == 2) {
+            constexpr int HB = (MB / 2) * NB;                 // blocks given away
+            const int give_lo = kg == 0 ? MB / 2 : 0;         // first row block given away
+            mb_lo = kg == 0 ? 0 : MB / 2; mb_hi = mb_lo + MB / 2;
+            f32x4_t* ex = reinterpret_cast<f32x4_t*>(lds);
 #pragma unroll
-                for (int nb = 0; nb < NB; ++nb) {
-                    int rb;
-                    if (SWIGLU) rb = (nb < NB / 2) ? wn * (Cfg::WTN / 2) + nb * 32
-                                                   : BN / 2 + wn * (Cfg::WTN / 2) + (nb - NB / 2) * 32;
-                    else rb = wn * Cfg::WTN + nb * 32;
-                    wf[nb] = __builtin_bit_cast(bf16x8_t, sW[(rb + fr_row) * 8 + csw]);
-                }
+            for (int mbb = 0; mbb < MB / 2; ++mbb)
 #pragma unroll
                 for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-                    for (int mb = 0; mb < MB; ++mb)
-                        acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[nb], xf[mb], acc[mb][nb], 0, 0, 0);
-            }
-            if (kt + 1 < KT) store_lds(buf ^ 1);
+                    for (int q = 0; q < 4; ++q) {
+                        f32x4_t v;
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) v[i] = kg == 0 ? acc[MB / 2 + mbb][nb][q * 4 + i] : acc[mbb][nb][q * 4 + i];
+                        ex[((wave * HB + mbb * NB + nb) * 4 + q) * 64 + lane] = v;
+                    }
+            (void)give_lo;
             __syncthreads();
+            const int partner = wave < WGN * WGM ? wave + WGN * WGM : wave - WGN * WGM;
+#pragma unroll
+            for (int mbb = 0; mbb < MB / 2; ++mbb)
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const f32x4_t v = ex[((partner * HB + mbb * NB + nb) * 4 + q) * 64 + lane];
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            if (kg == 0) acc[mbb][nb][q * 4 + i] += v[i];
+                            else acc[MB / 2 + mbb][nb][q * 4 + i] += v[i];
+                        }
+                    }
+            __syncthreads();  // the next tile's first loads overwrite the exchange area
         }
 
         // epilogue: lane holds token row (lane & 31) of each block and, per register quad q,
@@ -196,6 +275,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_kernel(GemmArgs a)
         uint16_t* Cg = a.C + (size_t)g * a.c_group_col_stride;
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) {
+            if (mb < mb_lo || mb >= mb_hi) continue;
             const int m = wm * Cfg::WTM + mb * 32 + fr_row;
             if (m >= nrows) continue;
             uint16_t* crow = Cg + (size_t)(row0 + m) * a.ldc;
@@ -231,64 +311,86 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_kernel(GemmArgs a)
     }
 }
 
-template <int BM, int BN, int WGM, int WGN, bool SWIGLU, bool RAGGED>
-static hipError_t launch_variant(const GemmArgs& a, int n_cu, int max_row_tiles, hipStream_t s)
+template <int BM, int BN, int BK, int STAGES, int WGM, int WGN, int KG, bool SWIGLU, bool RAGGED>
+static hipError_t launch_one(const GemmArgs& a, int n_cu, int max_row_tiles, hipStream_t s)
 {
-    using Cfg = GemmCfg<BM, BN, WGM, WGN, SWIGLU>;
+    using Cfg = GemmCfg<BM, BN, BK, STAGES, WGM, WGN, KG, SWIGLU>;
     const int NT = (a.N + Cfg::BN_OUT - 1) / Cfg::BN_OUT;
     const long long max_tiles = (long long)max_row_tiles * NT;
     if (max_tiles <= 0) return hipSuccess;
-    const int occ = (160 * 1024) / Cfg::LDS_BYTES >= 2 ? 2 : 1;
+    // workgroups per CU: LDS (160 KB minus the kernel's small static tables) and 8 wavefront slots
+    int occ = (156 * 1024) / Cfg::LDS_BYTES;
+    const int by_waves = 8 / Cfg::NW;
+    if (occ > by_waves) occ = by_waves;
+    if (occ < 1) occ = 1;
     long long grid = (long long)n_cu * occ;
     if (grid > max_tiles) grid = max_tiles;
     grid = (grid + 7) / 8 * 8;
-    hipLaunchKernelGGL((grouped_gemm_kernel<BM, BN, WGM, WGN, SWIGLU, RAGGED>), dim3((unsigned)grid),
-                       dim3(Cfg::THREADS), Cfg::LDS_BYTES, s, a);
+    hipLaunchKernelGGL((grouped_gemm_kernel<BM, BN, BK, STAGES, WGM, WGN, KG, SWIGLU, RAGGED>),
+                       dim3((unsigned)grid), dim3(Cfg::THREADS), Cfg::LDS_BYTES, s, a);
     return hipGetLastError();
 }
 
-template <int BM, int BN, int WGM, int WGN, bool SWIGLU, bool RAGGED>
-static hipError_t raise_lds_limit()
-{
-    using Cfg = GemmCfg<BM, BN, WGM, WGN, SWIGLU>;
-    return hipFuncSetAttribute(
-        reinterpret_cast<const void*>(&grouped_gemm_kernel<BM, BN, WGM, WGN, SWIGLU, RAGGED>),
-        hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::LDS_BYTES);
-}
-
-template <int BN>
+template <int BM, int BN, int BK, int STAGES, int WGM, int WGN, int KG>
 static hipError_t raise_all()
 {
     hipError_t e;
-    if ((e = raise_lds_limit<kBM, BN, 2, 2, true, true>()) != hipSuccess) return e;
-    if ((e = raise_lds_limit<kBM, BN, 2, 2, true, false>()) != hipSuccess) return e;
-    if ((e = raise_lds_limit<kBM, BN, 2, 2, false, true>()) != hipSuccess) return e;
-    return raise_lds_limit<kBM, BN, 2, 2, false, false>();
+#define R(SW, RG)                                                                                       \
+    if ((e = hipFuncSetAttribute(                                                                       \
+             reinterpret_cast<const void*>(&grouped_gemm_kernel<BM, BN, BK, STAGES, WGM, WGN, KG, SW, RG>), \
+             hipFuncAttributeMaxDynamicSharedMemorySize,                                                \
+             GemmCfg<BM, BN, BK, STAGES, WGM, WGN, KG, SW>::LDS_BYTES)) != hipSuccess) return e;
+    R(true, true) R(true, false) R(false, true) R(false, false)
+#undef R
+    return hipSuccess;
 }
+
+template <int BM, int BN, int BK, int STAGES, int WGM, int WGN, int KG>
+static hipError_t launch_cfg(const GemmArgs& a, bool swiglu, int n_cu, int max_row_tiles, hipStream_t s)
+{
+    const bool ragged = a.offset != nullptr;
+    if (swiglu) return ragged ? launch_one<BM, BN, BK, STAGES, WGM, WGN, KG, true, true>(a, n_cu, max_row_tiles, s)
+                              : launch_one<BM, BN, BK, STAGES, WGM, WGN, KG, true, false>(a, n_cu, max_row_tiles, s);
+    return ragged ? launch_one<BM, BN, BK, STAGES, WGM, WGN, KG, false, true>(a, n_cu, max_row_tiles, s)
+                  : launch_one<BM, BN, BK, STAGES, WGM, WGN, KG, false, false>(a, n_cu, max_row_tiles, s);
+}
+
+// tile variants: id, BM, BN, BK, ring stages, wavefronts in m, in n, K-split groups
+#define MOE_EP_VARIANTS(X)         \
+    X(0, 128, 256, 64, 3, 1, 2, 2) \
+    X(1, 128, 256, 64, 3, 2, 2, 1) \
+    X(2, 256, 256, 64, 2, 2, 2, 1) \
+    X(3, 256, 256, 32, 4, 2, 2, 1) \
+    X(4, 128, 128, 64, 2, 2, 2, 1)
 
 hipError_t grouped_gemm_init()
 {
-    hipError_t e = raise_all<256>();
-    return e != hipSuccess ? e : raise_all<128>();
+    hipError_t e;
+#define X(id, BM, BN, BK, ST, WGM, WGN, KG) if ((e = raise_all<BM, BN, BK, ST, WGM, WGN, KG>()) != hipSuccess) return e;
+    MOE_EP_VARIANTS(X)
+#undef X
+    return hipSuccess;
 }
 
-int grouped_gemm_row_tile() { return kBM; }
-
-template <int BN>
-static hipError_t launch_bn(const GemmArgs& a, bool swiglu, int n_cu, int max_row_tiles, hipStream_t s)
+int grouped_gemm_row_tile(int variant)
 {
-    const bool ragged = a.offset != nullptr;
-    if (swiglu) return ragged ? launch_variant<kBM, BN, 2, 2, true, true>(a, n_cu, max_row_tiles, s)
-                              : launch_variant<kBM, BN, 2, 2, true, false>(a, n_cu, max_row_tiles, s);
-    return ragged ? launch_variant<kBM, BN, 2, 2, false, true>(a, n_cu, max_row_tiles, s)
-                  : launch_variant<kBM, BN, 2, 2, false, false>(a, n_cu, max_row_tiles, s);
+    switch (variant) {
+#define X(id, BM, BN, BK, ST, WGM, WGN, KG) case id: return BM;
+        MOE_EP_VARIANTS(X)
+#undef X
+        default: return 128;
+    }
 }
 
 hipError_t launch_grouped_gemm(const GemmArgs& a, bool swiglu, int variant, int n_cu,
                                int max_row_tiles, hipStream_t s)
 {
-    if (variant == 1) return launch_bn<128>(a, swiglu, n_cu, max_row_tiles, s);
-    return launch_bn<256>(a, swiglu, n_cu, max_row_tiles, s);
+    switch (variant) {
+#define X(id, BM, BN, BK, ST, WGM, WGN, KG) case id: return launch_cfg<BM, BN, BK, ST, WGM, WGN, KG>(a, swiglu, n_cu, max_row_tiles, s);
+        MOE_EP_VARIANTS(X)
+#undef X
+        default: return launch_cfg<128, 256, 64, 3, 1, 2, 2>(a, swiglu, n_cu, max_row_tiles, s);
+    }
 }
 
 }  // namespace moe_ep

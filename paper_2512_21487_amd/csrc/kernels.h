@@ -44,10 +44,10 @@ struct GemmArgs {
     long long w_kseg_stride;   // ... whose weight blocks are this many elements apart
     int c_group_col_stride;    // dense mode: group g writes columns starting at g * this
 };
-// variant: 0 = 128x256 tile (default), 1 = 128x128 tile
+// variant: index into the tile-shape table of grouped_gemm.hip (0 = default)
 hipError_t launch_grouped_gemm(const GemmArgs& a, bool swiglu, int variant, int n_cu,
                                int max_row_tiles, hipStream_t s);
 hipError_t grouped_gemm_init();   // raises the dynamic-LDS limit of every instantiation once
-int grouped_gemm_row_tile();      // BM: rows per tile (all variants share it)
+int grouped_gemm_row_tile(int variant);  // BM: rows per tile of a variant (the scan kernel counts row tiles with it)
 
 }  // namespace moe_ep

@@ -28,7 +28,8 @@ struct ProfSpan { hipEvent_t a, b; int stage; };
 struct moe_ep_ctx {
     moe_ep_config cfg;
     int n_cu = 0;
-    int gemm_variant = 0;
+    int gemm_variant = 1;    // routed experts: 128-row tiles keep the padding of ragged groups small
+    int shared_variant = 2;  // shared experts: dense rows, 256-row tiles
     int BM = 128;
     // device workspaces
     void* d_tokens = nullptr; float* d_logits = nullptr; void* d_out = nullptr;  // pinned-host mode staging
@@ -205,8 +206,10 @@ int moe_ep_create(const moe_ep_config* cfg, moe_ep_ctx** out_ctx)
     hipDeviceProp_t prop;
     if (hipGetDeviceProperties(&prop, cfg->device) != hipSuccess) { delete ctx; return MOE_EP_EHIP; }
     ctx->n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
-    ctx->BM = grouped_gemm_row_tile();
+    // tile-shape overrides for tuning (indices into the variant table of grouped_gemm.hip)
     if (const char* v = getenv("MOE_EP_GEMM_VARIANT")) ctx->gemm_variant = atoi(v);
+    if (const char* v = getenv("MOE_EP_SHARED_VARIANT")) ctx->shared_variant = atoi(v);
+    ctx->BM = grouped_gemm_row_tile(ctx->gemm_variant);
     if (grouped_gemm_init() != hipSuccess) { delete ctx; return MOE_EP_EHIP; }
 
     const WsLayout L = ws_layout(*cfg);
@@ -339,9 +342,10 @@ int moe_ep_forward(moe_ep_ctx* ctx, const void* tokens, const float* gate_logits
         g1.K = M; g1.N = Hs; g1.lda = M; g1.ldc = Ns * Hs; g1.ldw = M;
         g1.w_group_stride = (long long)3 * Hs * M; g1.w_up_offset = (long long)Hs * M;
         g1.kseg_len = M; g1.w_kseg_stride = 0; g1.c_group_col_stride = Hs;
-        const int mt = (Tn + ctx->BM - 1) / ctx->BM;
+        const int sbm = grouped_gemm_row_tile(ctx->shared_variant);
+        const int mt = (Tn + sbm - 1) / sbm;
         int sp = prof_begin(ctx, prof, ST_SGEMM1, s_comp);
-        HIP_TRY(ctx, launch_grouped_gemm(g1, true, ctx->gemm_variant, ctx->n_cu, mt * Ns, s_comp));
+        HIP_TRY(ctx, launch_grouped_gemm(g1, true, ctx->shared_variant, ctx->n_cu, mt * Ns, s_comp));
         prof_end(ctx, sp, s_comp);
         GemmArgs g2{};
         g2.A = ctx->hs + (size_t)t0 * Ns * Hs; g2.W = sw + (size_t)2 * Hs * M; g2.C = ctx->ysh + (size_t)t0 * M;
@@ -350,7 +354,7 @@ int moe_ep_forward(moe_ep_ctx* ctx, const void* tokens, const float* gate_logits
         g2.w_group_stride = 0; g2.w_up_offset = 0;
         g2.kseg_len = Hs; g2.w_kseg_stride = (long long)3 * Hs * M; g2.c_group_col_stride = 0;
         sp = prof_begin(ctx, prof, ST_SGEMM2, s_comp);
-        HIP_TRY(ctx, launch_grouped_gemm(g2, false, ctx->gemm_variant, ctx->n_cu, mt, s_comp));
+        HIP_TRY(ctx, launch_grouped_gemm(g2, false, ctx->shared_variant, ctx->n_cu, mt, s_comp));
         prof_end(ctx, sp, s_comp);
         return MOE_EP_OK;
     };
