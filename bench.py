@@ -61,6 +61,9 @@ def main() -> int:
     ap.add_argument("--order", type=int, default=0, help="0 shared first, 1 interleaved")
     ap.add_argument("--variant", type=int, default=None, help="GEMM tile variant (tuning)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run one 1 GiB device-to-device copy kernel: the known-size reference "
+                         "that rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled by")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build drives one GPU only (no collectives, no sharding); "
@@ -172,6 +175,12 @@ def main() -> int:
     }
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(wl, inp)
+    if args.copy_probe:
+        src = torch.ones(1 << 29, dtype=torch.int16, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)                      # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
     ctx.destroy()
     print(json.dumps(line))
     return 0

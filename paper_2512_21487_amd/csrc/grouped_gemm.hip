@@ -9,9 +9,9 @@
 //
 // One launch covers all experts.  Workgroups are persistent and walk a tile list that is
 // defined by device-side prefix sums (the host never learns the routing): tile id ->
-// (expert, column tile, row tile), row tiles fastest so that the workgroups of one XCD
-// share a weight panel through that XCD's L2.  The id -> workgroup map hands each XCD
-// contiguous runs of tile ids (workgroup b runs on XCD b mod 8).
+// (expert, band of row tiles, column tile, row tile in the band), so that the workgroups of
+// one XCD share a few weight panels and a few row panels through that XCD's L2.  The id ->
+// workgroup map hands each XCD contiguous runs of tile ids (workgroup b runs on XCD b mod 8).
 //
 // Data movement: global_load_lds_dwordx4 moves 16 bytes per lane from global memory straight
 // into LDS (no staging registers, no ds_write), into a ring of STAGES K-steps: while step kt
@@ -96,7 +96,12 @@ __global__ __launch_bounds__(WGM* WGN* KG * 64) void grouped_gemm_kernel(GemmArg
     for (int it = 0;; ++it) {
         const int L = (it * 8 + xcd) * per_xcd + slot;
         if (L >= total) break;
-        int g, mi, ni, row0, nrows;
+        // tile id -> (group, row tile, column tile): inside a group the row tiles are taken in bands
+        // of kBand; inside a band the row tile runs fastest, then the column tile.  A run of 32
+        // consecutive ids (one XCD's share) then covers about kBand row panels x 32/kBand
+        // weight panels instead of 32 x 1, which is what that XCD's L2 has to fetch.
+        constexpr int kBand = 8;
+        int g, mi, ni, row0, nrows, mt_g, l;
         if (RAGGED) {
             int lo = 0, hi = a.G;
             while (hi - lo > 1) {
@@ -104,16 +109,25 @@ __global__ __launch_bounds__(WGM* WGN* KG * 64) void grouped_gemm_kernel(GemmArg
                 if (s_pref[mid] * NT <= L) lo = mid; else hi = mid;
             }
             g = lo;
-            const int mt_g = s_pref[g + 1] - s_pref[g];
-            const int l = L - s_pref[g] * NT;
-            ni = l / mt_g; mi = l - ni * mt_g;
-            row0 = s_off[g] + mi * BM;
-            nrows = min(BM, s_off[g + 1] - row0);
+            mt_g = s_pref[g + 1] - s_pref[g];
+            l = L - s_pref[g] * NT;
         } else {
             const int per_g = mt_per * NT;
             g = L / per_g;
-            const int l = L - g * per_g;
-            ni = l / mt_per; mi = l - ni * mt_per;
+            mt_g = mt_per;
+            l = L - g * per_g;
+        }
+        {
+            const int band = l / (kBand * NT);
+            const int band_h = min(kBand, mt_g - band * kBand);
+            const int lb = l - band * kBand * NT;
+            ni = lb / band_h;
+            mi = band * kBand + (lb - ni * band_h);
+        }
+        if (RAGGED) {
+            row0 = s_off[g] + mi * BM;
+            nrows = min(BM, s_off[g + 1] - row0);
+        } else {
             row0 = mi * BM;
             nrows = min(BM, a.dense_rows - row0);
         }
@@ -361,7 +375,9 @@ static hipError_t launch_cfg(const GemmArgs& a, bool swiglu, int n_cu, int max_r
     X(1, 128, 256, 64, 3, 2, 2, 1) \
     X(2, 256, 256, 64, 2, 2, 2, 1) \
     X(3, 256, 256, 32, 4, 2, 2, 1) \
-    X(4, 128, 128, 64, 2, 2, 2, 1)
+    X(4, 128, 128, 64, 2, 2, 2, 1) \
+    X(5, 128, 256, 32, 3, 2, 2, 1) \
+    X(6, 128, 256, 32, 2, 2, 2, 1)
 
 hipError_t grouped_gemm_init()
 {
