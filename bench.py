@@ -22,6 +22,8 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 matrix peak
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E peak
+# (workload, r_chunks) -> fetched + written bytes per launch of the routed gate/up grouped GEMM
+MEASURED_TRAFFIC_BYTES = {("dsv2_eg", 1): 1066.8e6 + 37.8e6}
 
 
 def cpu_baseline(wl, inp, budget_s=15.0):
@@ -157,8 +159,10 @@ def main() -> int:
     routed = gemm_line(6.0 * kept * M * H, routed_ms)
     roof = dict(kernels["routed_gate_up_gemm"] or {})
     roof.pop("ms_per_step", None)
-    roof["traffic"] = None
-    roof["kernel"] = "grouped_gemm_kernel<128,256,2,2,swiglu,ragged> (routed gate/up projection)"
+    # HBM-side bytes of one launch of that kernel, from rocprofv3 FETCH_SIZE + WRITE_SIZE runs scaled
+    # by a 1 GiB copy kernel (profiles/hbm_traffic_dsv2_eg.txt); measured for the default workload only
+    roof["traffic"] = MEASURED_TRAFFIC_BYTES.get((wl.name, args.r))
+    roof["kernel"] = "grouped_gemm_kernel<128,256,64,3,2,2,1,swiglu,ragged> (routed gate/up projection)"
 
     line = {
         "metric": "expert-layer tokens/sec at 1 GPU; grouped-GEMM % of bf16 MFMA peak",

@@ -57,3 +57,21 @@ def rel_err(got, ref):
     rms = float(np.sqrt(np.mean(ref * ref))) if ref.size else 0.0
     den = np.maximum(np.abs(ref), max(rms, 1e-30))
     return float(np.max(np.abs(got - ref) / den)) if ref.size else 0.0
+
+
+def load_tiny_golden(path):
+    """Parse tests/golden/tiny_oracle_values.txt -> (count, routing rows, output samples, rms)."""
+    sections, cur = [], None
+    for line in open(path):
+        line = line.strip()
+        if not line:
+            continue
+        if line.startswith("#"):
+            cur = []
+            sections.append(cur)
+            continue
+        cur.append(line.split())
+    _, count, routing, samples, rms = sections
+    return ([int(v) for v in count[0]],
+            [(int(r[0]), int(r[1]), int(r[2]), float(r[3]), float(r[4])) for r in routing],
+            [(int(r[0]), int(r[1]), float(r[2])) for r in samples], float(rms[0][0]))

@@ -6,7 +6,9 @@ import numpy as np
 import pytest
 
 import oracle
-from helpers import rel_err
+import os
+
+from helpers import load_tiny_golden, rel_err
 from workloads import CONFIGS, bf16_bits_to_f32, make_inputs, tiny_workload
 
 torch = pytest.importorskip("torch")
@@ -68,6 +70,25 @@ def _full_parity(wl, seed=0, r=1, order=0, mutate=None):
 # ------------------------------------------------------------------ element by element
 def test_tiny_config_matches_oracle():
     _full_parity(CONFIGS["tiny"])
+
+
+def test_tiny_against_stored_oracle_values():
+    """The GPU output against oracle values stored in tests/golden (no oracle run needed)."""
+    g = _gpu()
+    path = os.path.join(os.path.dirname(__file__), "golden", "tiny_oracle_values.txt")
+    count, routing, samples, rms = load_tiny_golden(path)
+    wl = CONFIGS["tiny"]
+    ctx = g.make_ctx(wl)
+    d = g.DeviceInputs(wl, make_inputs(wl))
+    out = bf16_bits_to_f32(g.run_forward(ctx, wl, d))
+    got = ctx.get_routing(0)
+    assert got["count"].tolist() == count
+    for t, i0, i1, w0, w1 in routing:
+        assert got["idx"][t].tolist() == [i0, i1]
+        assert abs(got["w"][t, 0] - w0) <= W_TOL and abs(got["w"][t, 1] - w1) <= W_TOL
+    for t, c, v in samples:
+        assert abs(out[t, c] - v) / max(abs(v), rms) <= TOL
+    ctx.destroy()
 
 
 @pytest.mark.parametrize("r,order", [(1, 0), (3, 1), (8, 0)])

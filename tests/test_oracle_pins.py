@@ -7,13 +7,15 @@ and invariants the definitions imply (Sec. 2.1, Sec. 3.1, Sec. 2.3, and the
 token-conservation rule of Eq. 'limitation').
 """
 import math
+import os
 
 import numpy as np
 import pytest
 from scipy.special import softmax
 
 import oracle
-from helpers import brute_force_layer, dense_ffn, f64, rel_err, split_expert, topk_by_sort
+from helpers import (brute_force_layer, dense_ffn, f64, load_tiny_golden, rel_err, split_expert,
+                     topk_by_sort)
 from workloads import CONFIGS, f32_to_bf16_bits, make_inputs, tiny_workload
 
 
@@ -302,3 +304,18 @@ def test_bad_arguments_are_rejected():
         oracle.router(logits, 0)
     with pytest.raises(ValueError):
         oracle.router(logits, 5)
+
+
+def test_stored_tiny_values():
+    """The committed oracle-written values of the tiny workload still come out of the oracle."""
+    path = os.path.join(os.path.dirname(__file__), "golden", "tiny_oracle_values.txt")
+    count, routing, samples, rms = load_tiny_golden(path)
+    wl = CONFIGS["tiny"]
+    res = _fwd(make_inputs(wl), wl)
+    assert res["count"][0].tolist() == count
+    for t, i0, i1, w0, w1 in routing:
+        assert res["idx"][t].tolist() == [i0, i1]
+        np.testing.assert_allclose(res["w"][t], [w0, w1], atol=1e-11)
+    for t, c, v in samples:
+        assert abs(res["out"][t, c] - v) <= 1e-10 * max(1.0, abs(v))
+    assert abs(np.sqrt(np.mean(res["out"] ** 2)) - rms) <= 1e-10
