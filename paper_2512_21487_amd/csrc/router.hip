@@ -1,6 +1,7 @@
 // Gate: per token, the top-k of E routing scores and their renormalised softmax weights
-// (Sec. 2.1).  One 64-lane wavefront owns a token: lane l holds scores l, l+64, ... in
-// registers, each of the k rounds is a lane-local scan plus a 6-step butterfly arg-max.
+// (Sec. 2.1).  One 64-lane wavefront owns a token at a time (four tokens in turn, their scores
+// all requested up front): lane l holds scores l, l+64, ... in registers, each of the k rounds
+// is a lane-local scan plus a 6-step butterfly arg-max.
 // The same workgroup (64 tokens) also records, per local expert, a 64-bit mask of the
 // tokens that selected it; the partition kernels derive counts and stable ranks from it,
 // so no atomically allocated slot ever decides an order.
@@ -11,31 +12,40 @@ namespace moe_ep {
 
 constexpr int kMaxEpl = 8;  // scores per lane: E <= 512
 
-__global__ __launch_bounds__(256) void router_topk_kernel(
+constexpr int kRouterThreads = 1024;                                   // 16 wavefronts per 64-token workgroup
+constexpr int kTokPerWave = kTokPerBlock / (kRouterThreads / 64);      // 4 tokens per wavefront
+
+__global__ __launch_bounds__(kRouterThreads) void router_topk_kernel(
     const float* __restrict__ logits, int Tn, int E, int k, int e0, int El,
     int32_t* __restrict__ idx, float* __restrict__ w, unsigned long long* __restrict__ blk_mask)
 {
     extern __shared__ unsigned long long smask[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    for (int i = tid; i < El; i += 256) smask[i] = 0ull;
+    for (int i = tid; i < El; i += kRouterThreads) smask[i] = 0ull;
     __syncthreads();
 
     const int epl = (E + 63) >> 6;
-    constexpr int kTokPerWave = kTokPerBlock / 4;
+    // all of this wavefront's scores are requested before the first one is used
+    float v[kTokPerWave][kMaxEpl];
+#pragma unroll
+    for (int j = 0; j < kTokPerWave; ++j) {
+        const int t = blockIdx.x * kTokPerBlock + wave * kTokPerWave + j;
+        const float* row = logits + (size_t)min(t, Tn - 1) * E;
+#pragma unroll
+        for (int i = 0; i < kMaxEpl; ++i) {
+            const int e = lane + 64 * i;
+            v[j][i] = (i < epl && e < E) ? row[e] : 0.f;
+        }
+    }
+#pragma unroll
     for (int j = 0; j < kTokPerWave; ++j) {
         const int tl = wave * kTokPerWave + j;
         const int t = blockIdx.x * kTokPerBlock + tl;
         if (t >= Tn) break;  // uniform over the wavefront
-        const float* row = logits + (size_t)t * E;
-        float v[kMaxEpl];
         unsigned taken = 0;
 #pragma unroll
-        for (int i = 0; i < kMaxEpl; ++i) {
-            const int e = lane + 64 * i;
-            const bool ok = (i < epl) && (e < E);
-            v[i] = ok ? row[e] : 0.f;
-            if (!ok) taken |= 1u << i;
-        }
+        for (int i = 0; i < kMaxEpl; ++i)
+            if (!(i < epl && lane + 64 * i < E)) taken |= 1u << i;
         int my_idx = 0;
         float my_val = 0.f;
         for (int s = 0; s < k; ++s) {
@@ -44,7 +54,7 @@ __global__ __launch_bounds__(256) void router_topk_kernel(
             int bi = INT_MAX;
 #pragma unroll
             for (int i = 0; i < kMaxEpl; ++i) {
-                if (!((taken >> i) & 1u) && (bi == INT_MAX || v[i] > bv)) { bv = v[i]; bi = lane + 64 * i; }
+                if (!((taken >> i) & 1u) && (bi == INT_MAX || v[j][i] > bv)) { bv = v[j][i]; bi = lane + 64 * i; }
             }
 #pragma unroll
             for (int d = 32; d >= 1; d >>= 1) {
@@ -70,7 +80,7 @@ __global__ __launch_bounds__(256) void router_topk_kernel(
     }
     __syncthreads();
     unsigned long long* dst = blk_mask + (size_t)blockIdx.x * El;
-    for (int i = tid; i < El; i += 256) dst[i] = smask[i];
+    for (int i = tid; i < El; i += kRouterThreads) dst[i] = smask[i];
 }
 
 hipError_t launch_router(const float* logits, int Tn, int E, int k, int e0, int El, int32_t* idx,
@@ -78,7 +88,7 @@ hipError_t launch_router(const float* logits, int Tn, int E, int k, int e0, int 
 {
     if (Tn <= 0) return hipSuccess;
     const int nblk = (Tn + kTokPerBlock - 1) / kTokPerBlock;
-    hipLaunchKernelGGL(router_topk_kernel, dim3(nblk), dim3(256), El * sizeof(unsigned long long), s,
+    hipLaunchKernelGGL(router_topk_kernel, dim3(nblk), dim3(kRouterThreads), El * sizeof(unsigned long long), s,
                        logits, Tn, E, k, e0, El, idx, w, blk_mask);
     return hipGetLastError();
 }
