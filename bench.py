@@ -177,6 +177,21 @@ def main() -> int:
         "kernels": kernels,
         "stage_ms": stages,
     }
+    if pinned:
+        # Chunk pipeline against the closed form of Sec. 4.2 (layer 0, one slice): three resources
+        # (inbound link, expert compute, outbound link), r chunks, steady-state step = the slowest
+        # resource: makespan = t_in + t_e + t_out + (r - 1) * max(t_in, t_e, t_out).  The paper
+        # takes t_in = t_out = t_a2e; here the inbound copy also carries the gate scores.
+        r = args.r
+        t_in, t_out = stages["copy_in"] / r, stages["copy_out"] / r
+        t_e = sum(stages[n] for n in ("router", "partition", "routed_gate_up_gemm", "routed_down_gemm",
+                                      "shared_gate_up_gemm", "shared_down_gemm", "aggregation")) / r
+        line["pipeline"] = {
+            "t_in_ms_per_chunk": t_in, "t_e_ms_per_chunk": t_e, "t_out_ms_per_chunk": t_out,
+            "closed_form_ms": t_in + t_e + t_out + (r - 1) * max(t_in, t_e, t_out),
+            "measured_ms": stages["forward"],
+            "bytes_in_per_chunk": (T // r) * (2 * M + 4 * wl.n_experts), "bytes_out_per_chunk": (T // r) * 2 * M,
+        }
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(wl, inp)
     if args.copy_probe:

@@ -148,7 +148,8 @@ int moe_ep_get_routing(moe_ep_ctx *ctx, int32_t chunk, int32_t *idx, float *w, i
  *   ms[0] gate  ms[1] partition (scan + permute + row gather)  ms[2] routed gate/up GEMM
  *   ms[3] routed down GEMM  ms[4] shared gate/up GEMM  ms[5] shared down GEMM
  *   ms[6] aggregation  ms[7] whole forward (first enqueue to last completion)
- * each summed over the chunks of a forward.  n = floats the caller provides (<= 8 written).
+ *   ms[8] inbound copies  ms[9] outbound copies (MOE_EP_IO_PINNED_HOST only, else 0)
+ * each summed over the chunks of a forward.  n = floats the caller provides (<= 10 written).
  * Returns MOE_EP_ESTATE when nothing was recorded.
  */
 int moe_ep_set_profiling(moe_ep_ctx *ctx, int32_t depth);

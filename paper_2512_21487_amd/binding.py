@@ -16,7 +16,8 @@ ORDER_INTERLEAVED = 1
 IO_DEVICE = 0
 IO_PINNED_HOST = 1
 STAGES = ("router", "partition", "routed_gate_up_gemm", "routed_down_gemm",
-          "shared_gate_up_gemm", "shared_down_gemm", "aggregation", "forward")
+          "shared_gate_up_gemm", "shared_down_gemm", "aggregation", "forward", "copy_in",
+          "copy_out")
 
 _STATUS = {0: "OK", -1: "EINVAL", -2: "ENOMEM", -3: "EHIP", -4: "ESTATE"}
 
@@ -172,8 +173,8 @@ class MoeEp:
             raise MoeEpError(rc, self.last_error())
 
     def get_stage_ms(self) -> Dict[str, float]:
-        ms = (ctypes.c_float * 8)()
-        rc = self._lib.moe_ep_get_stage_ms(self._ctx, ctypes.cast(ms, ctypes.c_void_p), 8)
+        ms = (ctypes.c_float * len(STAGES))()
+        rc = self._lib.moe_ep_get_stage_ms(self._ctx, ctypes.cast(ms, ctypes.c_void_p), len(STAGES))
         if rc != 0:
             raise MoeEpError(rc, self.last_error())
         return {name: float(ms[i]) for i, name in enumerate(STAGES)}

@@ -19,7 +19,7 @@ using namespace moe_ep;
 
 namespace {
 
-enum Stage { ST_ROUTER = 0, ST_PARTITION, ST_GEMM1, ST_GEMM2, ST_SGEMM1, ST_SGEMM2, ST_COMBINE, ST_TOTAL, ST_COUNT };
+enum Stage { ST_ROUTER = 0, ST_PARTITION, ST_GEMM1, ST_GEMM2, ST_SGEMM1, ST_SGEMM2, ST_COMBINE, ST_TOTAL, ST_COPY_IN, ST_COPY_OUT, ST_COUNT };
 
 struct ProfSpan { hipEvent_t a, b; int stage; };
 
@@ -259,7 +259,7 @@ int moe_ep_set_profiling(moe_ep_ctx* ctx, int32_t depth)
     if (!ctx || depth < 0 || depth > 256) return MOE_EP_EINVAL;
     HIP_TRY(ctx, hipSetDevice(ctx->cfg.device));
     HIP_TRY(ctx, hipDeviceSynchronize());
-    const size_t per_forward = 2 * ((size_t)ctx->cfg.max_chunks * 8 + 4);
+    const size_t per_forward = 2 * ((size_t)ctx->cfg.max_chunks * 10 + 4);
     const size_t want = (size_t)depth * per_forward;
     while (ctx->prof_pool.size() < want) {
         hipEvent_t e = nullptr;
@@ -364,6 +364,7 @@ int moe_ep_forward(moe_ep_ctx* ctx, const void* tokens, const float* gate_logits
         for (int cidx = 0; cidx < r; ++cidx) {
             const int t0 = cidx * Tc;
             const int Tn = t0 >= T ? 0 : (T - t0 < Tc ? T - t0 : Tc);
+            const int sp_in = prof_begin(ctx, prof && Tn > 0, ST_COPY_IN, s_in);
             if (Tn > 0) {
                 HIP_TRY(ctx, hipMemcpyAsync(static_cast<char*>(ctx->d_tokens) + (size_t)t0 * M * 2,
                                             static_cast<const char*>(tokens) + (size_t)t0 * M * 2,
@@ -371,6 +372,7 @@ int moe_ep_forward(moe_ep_ctx* ctx, const void* tokens, const float* gate_logits
                 HIP_TRY(ctx, hipMemcpyAsync(ctx->d_logits + (size_t)t0 * E, gate_logits + (size_t)t0 * E,
                                             (size_t)Tn * E * 4, hipMemcpyHostToDevice, s_in));
             }
+            prof_end(ctx, sp_in, s_in);
             HIP_TRY(ctx, hipEventRecord(ctx->ev_in[cidx], s_in));
         }
     }
@@ -444,9 +446,11 @@ int moe_ep_forward(moe_ep_ctx* ctx, const void* tokens, const float* gate_logits
         if (pinned) {
             HIP_TRY(ctx, hipEventRecord(ctx->ev_comp[cidx], s_comp));
             HIP_TRY(ctx, hipStreamWaitEvent(s_out, ctx->ev_comp[cidx], 0));
+            const int sp_out = prof_begin(ctx, prof, ST_COPY_OUT, s_out);
             HIP_TRY(ctx, hipMemcpyAsync(static_cast<char*>(out) + (size_t)t0 * M * 2,
                                         reinterpret_cast<const char*>(out_dev) + (size_t)t0 * M * 2,
                                         (size_t)Tn * M * 2, hipMemcpyDeviceToHost, s_out));
+            prof_end(ctx, sp_out, s_out);
         }
     }
     if (pinned) {
