@@ -26,6 +26,9 @@ hipError_t launch_gather_rows(const void* tokens, const int32_t* perm, const int
 hipError_t launch_combine(const void* y, const void* ysh, const int32_t* pos, const float* w, int Tn,
                           int k, int M, void* out, int grid, hipStream_t s);
 
+// ---- chunk transfers over the host link (pinned-host mode); bytes must be a multiple of 4
+hipError_t launch_copy(void* dst, const void* src, size_t bytes, int grid, hipStream_t s);
+
 // ---- expert projections as one grouped GEMM launch (Sec. 3.1, Eq. moe_detail / shared_detail)
 struct GemmArgs {
     const uint16_t* A;         // activations, bf16 [rows, lda]

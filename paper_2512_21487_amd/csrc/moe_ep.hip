@@ -324,6 +324,25 @@ int moe_ep_forward(moe_ep_ctx* ctx, const void* tokens, const float* gate_logits
     const uint16_t* rw = static_cast<const uint16_t*>(routed_w);
     const uint16_t* sw = static_cast<const uint16_t*>(shared_w);
 
+    // pinned-host mode: the copy kernels address the host buffers directly, so they must be
+    // pinned (page-locked, device-visible) memory; anything else is rejected here
+    const char* h_tokens = nullptr; const char* h_logits = nullptr; char* h_out = nullptr;
+    if (pinned) {
+        const void* in[3] = {tokens, gate_logits, out};
+        void* dev[3] = {nullptr, nullptr, nullptr};
+        for (int i = 0; i < 3; ++i) {
+            hipPointerAttribute_t attr;
+            if (hipPointerGetAttributes(&attr, in[i]) != hipSuccess || attr.type != hipMemoryTypeHost ||
+                attr.devicePointer == nullptr) {
+                (void)hipGetLastError();
+                return fail(ctx, MOE_EP_EINVAL, "tokens, gate_logits and out must be pinned host memory in MOE_EP_IO_PINNED_HOST mode");
+            }
+            dev[i] = attr.devicePointer;
+        }
+        h_tokens = static_cast<const char*>(dev[0]); h_logits = static_cast<const char*>(dev[1]);
+        h_out = static_cast<char*>(dev[2]);
+    }
+    const int link_grid = 64;  // workgroups of a copy kernel: enough bytes in flight to fill the host link
     const int span_total = prof_begin(ctx, prof, ST_TOTAL, user);
     if (pinned) {
         HIP_TRY(ctx, hipEventRecord(ctx->ev_start, user));
@@ -366,11 +385,10 @@ int moe_ep_forward(moe_ep_ctx* ctx, const void* tokens, const float* gate_logits
             const int Tn = t0 >= T ? 0 : (T - t0 < Tc ? T - t0 : Tc);
             const int sp_in = prof_begin(ctx, prof && Tn > 0, ST_COPY_IN, s_in);
             if (Tn > 0) {
-                HIP_TRY(ctx, hipMemcpyAsync(static_cast<char*>(ctx->d_tokens) + (size_t)t0 * M * 2,
-                                            static_cast<const char*>(tokens) + (size_t)t0 * M * 2,
-                                            (size_t)Tn * M * 2, hipMemcpyHostToDevice, s_in));
-                HIP_TRY(ctx, hipMemcpyAsync(ctx->d_logits + (size_t)t0 * E, gate_logits + (size_t)t0 * E,
-                                            (size_t)Tn * E * 4, hipMemcpyHostToDevice, s_in));
+                HIP_TRY(ctx, launch_copy(static_cast<char*>(ctx->d_tokens) + (size_t)t0 * M * 2,
+                                         h_tokens + (size_t)t0 * M * 2, (size_t)Tn * M * 2, link_grid, s_in));
+                HIP_TRY(ctx, launch_copy(ctx->d_logits + (size_t)t0 * E, h_logits + (size_t)t0 * E * 4,
+                                         (size_t)Tn * E * 4, link_grid, s_in));
             }
             prof_end(ctx, sp_in, s_in);
             HIP_TRY(ctx, hipEventRecord(ctx->ev_in[cidx], s_in));
@@ -447,9 +465,9 @@ int moe_ep_forward(moe_ep_ctx* ctx, const void* tokens, const float* gate_logits
             HIP_TRY(ctx, hipEventRecord(ctx->ev_comp[cidx], s_comp));
             HIP_TRY(ctx, hipStreamWaitEvent(s_out, ctx->ev_comp[cidx], 0));
             const int sp_out = prof_begin(ctx, prof, ST_COPY_OUT, s_out);
-            HIP_TRY(ctx, hipMemcpyAsync(static_cast<char*>(out) + (size_t)t0 * M * 2,
-                                        reinterpret_cast<const char*>(out_dev) + (size_t)t0 * M * 2,
-                                        (size_t)Tn * M * 2, hipMemcpyDeviceToHost, s_out));
+            HIP_TRY(ctx, launch_copy(h_out + (size_t)t0 * M * 2,
+                                     reinterpret_cast<const char*>(out_dev) + (size_t)t0 * M * 2,
+                                     (size_t)Tn * M * 2, link_grid, s_out));
             prof_end(ctx, sp_out, s_out);
         }
     }

@@ -1,0 +1,39 @@
+// Stand-in for the A2E / E2A transfers (Sec. 2.2; Eq. a2e_detail) in pinned-host mode: a chunk
+// of activations crosses the host link in a copy kernel that reads (or writes) the pinned
+// host buffer directly.  A kernel launch never blocks the host thread and costs a few
+// microseconds, where the runtime's asynchronous memcpy was measured to take 25-50 us per
+// call and to block for milliseconds now and then, which serialised the chunk pipeline.
+// 16 bytes per lane, four independent loads per lane in flight; the grid is small (the link,
+// not the CUs, is the bottleneck) so the copy shares the GPU with the expert GEMMs.
+#include "common.h"
+#include "kernels.h"
+
+namespace moe_ep {
+
+template <typename V>
+__global__ __launch_bounds__(256) void copy_kernel(const V* __restrict__ src, V* __restrict__ dst, size_t n)
+{
+    const size_t stride = (size_t)gridDim.x * 256;
+    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    for (; i + 3 * stride < n; i += 4 * stride) {
+        const V a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
+        dst[i] = a; dst[i + stride] = b; dst[i + 2 * stride] = c; dst[i + 3 * stride] = d;
+    }
+    for (; i < n; i += stride) dst[i] = src[i];
+}
+
+hipError_t launch_copy(void* dst, const void* src, size_t bytes, int grid, hipStream_t s)
+{
+    if (bytes == 0) return hipSuccess;
+    const bool a16 = ((reinterpret_cast<uintptr_t>(dst) | reinterpret_cast<uintptr_t>(src) | bytes) & 15) == 0;
+    if (a16) {
+        hipLaunchKernelGGL(copy_kernel<uint4>, dim3(grid), dim3(256), 0, s, static_cast<const uint4*>(src),
+                           static_cast<uint4*>(dst), bytes / 16);
+    } else {  // 4-byte granularity (gate scores of a chunk need not start on a 16-byte boundary)
+        hipLaunchKernelGGL(copy_kernel<uint32_t>, dim3(grid), dim3(256), 0, s, static_cast<const uint32_t*>(src),
+                           static_cast<uint32_t*>(dst), bytes / 4);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace moe_ep
