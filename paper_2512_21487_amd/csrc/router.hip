@@ -37,44 +37,59 @@ __global__ __launch_bounds__(kRouterThreads) void router_topk_kernel(
             v[j][i] = (i < epl && e < E) ? row[e] : 0.f;
         }
     }
+    // the four tokens advance through the k selection rounds together: their arg-max chains are
+    // independent, so the cross-lane exchanges of one token hide behind those of the others
+    unsigned taken[kTokPerWave];
+    int my_idx[kTokPerWave];
+    float my_val[kTokPerWave];
+#pragma unroll
+    for (int j = 0; j < kTokPerWave; ++j) {
+        taken[j] = 0; my_idx[j] = 0; my_val[j] = 0.f;
+#pragma unroll
+        for (int i = 0; i < kMaxEpl; ++i)
+            if (!(i < epl && lane + 64 * i < E)) taken[j] |= 1u << i;
+    }
+    for (int s = 0; s < k; ++s) {
+        float bv[kTokPerWave];
+        int bi[kTokPerWave];
+#pragma unroll
+        for (int j = 0; j < kTokPerWave; ++j) {
+            // lane-local best: larger score first, equal scores keep the lower index
+            bv[j] = -INFINITY; bi[j] = INT_MAX;
+#pragma unroll
+            for (int i = 0; i < kMaxEpl; ++i)
+                if (!((taken[j] >> i) & 1u) && (bi[j] == INT_MAX || v[j][i] > bv[j])) { bv[j] = v[j][i]; bi[j] = lane + 64 * i; }
+        }
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) {
+#pragma unroll
+            for (int j = 0; j < kTokPerWave; ++j) {
+                const float ov = __shfl_xor(bv[j], d, 64);
+                const int oi = __shfl_xor(bi[j], d, 64);
+                if (ov > bv[j] || (ov == bv[j] && oi < bi[j])) { bv[j] = ov; bi[j] = oi; }
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < kTokPerWave; ++j) {
+            if ((bi[j] & 63) == lane) taken[j] |= 1u << (bi[j] >> 6);
+            if (lane == s) { my_idx[j] = bi[j]; my_val[j] = bv[j]; }
+        }
+    }
 #pragma unroll
     for (int j = 0; j < kTokPerWave; ++j) {
         const int tl = wave * kTokPerWave + j;
         const int t = blockIdx.x * kTokPerBlock + tl;
         if (t >= Tn) break;  // uniform over the wavefront
-        unsigned taken = 0;
-#pragma unroll
-        for (int i = 0; i < kMaxEpl; ++i)
-            if (!(i < epl && lane + 64 * i < E)) taken |= 1u << i;
-        int my_idx = 0;
-        float my_val = 0.f;
-        for (int s = 0; s < k; ++s) {
-            // lane-local best: larger score first, equal scores keep the lower index
-            float bv = -INFINITY;
-            int bi = INT_MAX;
-#pragma unroll
-            for (int i = 0; i < kMaxEpl; ++i) {
-                if (!((taken >> i) & 1u) && (bi == INT_MAX || v[j][i] > bv)) { bv = v[j][i]; bi = lane + 64 * i; }
-            }
-#pragma unroll
-            for (int d = 32; d >= 1; d >>= 1) {
-                const float ov = __shfl_xor(bv, d, 64);
-                const int oi = __shfl_xor(bi, d, 64);
-                if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
-            }
-            if ((bi & 63) == lane) taken |= 1u << (bi >> 6);
-            if (lane == s) { my_idx = bi; my_val = bv; }
-        }
         // softmax restricted to the selection = full softmax renormalised over it
-        const float v0 = __shfl(my_val, 0, 64);
-        const float ex = (lane < k) ? expf(my_val - v0) : 0.f;
+        const float v0 = __shfl(my_val[j], 0, 64);
+        const float ex = (lane < k) ? expf(my_val[j] - v0) : 0.f;
         float sum = ex;
 #pragma unroll
         for (int d = 32; d >= 1; d >>= 1) sum += __shfl_xor(sum, d, 64);
         if (lane < k) {
-            idx[(size_t)t * k + lane] = my_idx;
+            idx[(size_t)t * k + lane] = my_idx[j];
             w[(size_t)t * k + lane] = ex / sum;
-            const int el = my_idx - e0;
+            const int el = my_idx[j] - e0;
             if (el >= 0 && el < El) atomicOr(&smask[el], 1ull << tl);
         }
     }
