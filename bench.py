@@ -65,6 +65,9 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-stage-timing", action="store_true",
                     help="time the K steps without per-stage HIP events (stage figures are then absent)")
+    ap.add_argument("--fit-pipeline", action="store_true",
+                    help="pinned-host workloads: fit the linear task models of Sec. 4.1 from r=1 forwards at "
+                         "several token counts, choose r_2 from them and compare with measured r sweeps")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one 1 GiB device-to-device copy kernel: the known-size reference "
                          "that rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled by")
@@ -106,7 +109,7 @@ def main() -> int:
         out = torch.zeros((T, M), dtype=torch.int16, device="cuda")
     ctx = pkg.MoeEp(hidden=M, inter=H, n_experts=wl.n_experts, local_begin=wl.local_begin,
                     n_local=wl.n_local, n_shared=wl.n_shared, shared_inter=wl.shared_inter,
-                    max_tokens=T, max_top_k=k, max_chunks=max(args.r, 1),
+                    max_tokens=T, max_top_k=k, max_chunks=max(args.r, 8 if pinned else 1),
                     io_mode=pkg.IO_PINNED_HOST if pinned else pkg.IO_DEVICE)
     stream = torch.cuda.current_stream().cuda_stream
 
@@ -163,7 +166,7 @@ def main() -> int:
         "router": hbm_line(T * (4.0 * wl.n_experts + 8.0 * k), stages["router"]),
     }
     routed_ms = stages["routed_gate_up_gemm"] + stages["routed_down_gemm"]
-    routed = gemm_line(6.0 * kept * M * H, routed_ms)
+    routed_line = gemm_line(6.0 * kept * M * H, routed_ms)
     roof = dict(kernels["routed_gate_up_gemm"] or {})
     roof.pop("ms_per_step", None)
     # HBM-side bytes of one launch of that kernel, from rocprofv3 FETCH_SIZE + WRITE_SIZE runs scaled
@@ -179,7 +182,7 @@ def main() -> int:
         "config": {"workload": f"{wl.name}: T={T} M={M} H={H} E={wl.n_experts} local={wl.n_local} "
                                f"top_k={k} shared={Ns}x{Hs} io={'pinned_host' if pinned else 'device'}",
                    "r_chunks": args.r, "order": args.order, "kept_assignments": kept},
-        "grouped_gemm_pct_of_bf16_mfma_peak": None if routed is None else 100.0 * routed["frac"],
+        "grouped_gemm_pct_of_bf16_mfma_peak": None if routed_line is None else 100.0 * routed_line["frac"],
         "roofline": roof,
         "kernels": kernels,
         "stage_ms": stages,
@@ -199,6 +202,48 @@ def main() -> int:
             "closed_form_ms": t_in + t_e + t_out + (r - 1) * max(t_in, t_e, t_out),
             "measured_ms": stages["forward"],
             "bytes_in_per_chunk": (T // r) * (2 * M + 4 * wl.n_experts), "bytes_out_per_chunk": (T // r) * 2 * M,
+        }
+    if pinned and args.fit_pipeline:
+        # Sec. 4.1: t = alpha + beta * m for each resource, m = tokens of a chunk; fitted from r=1
+        # forwards over a sweep of m (10 warm-up + 20 timed per point, the protocol of Sec. 5.2)
+        pts = sorted({max(64, T // d) for d in (64, 32, 16, 8, 4, 2, 1)})
+        samples = {"copy_in": [], "copy_out": [], "compute": []}
+        for m_tok in pts:
+            for _ in range(10):
+                ctx.forward(tokens, logits, routed, shared, k, 1, args.order, n_tokens=m_tok, out=out, stream=stream)
+            torch.cuda.synchronize()
+            ctx.set_profiling(20)
+            for _ in range(20):
+                ctx.forward(tokens, logits, routed, shared, k, 1, args.order, n_tokens=m_tok, out=out, stream=stream)
+            st = ctx.get_stage_ms()
+            ctx.set_profiling(0)
+            samples["copy_in"].append(st["copy_in"]); samples["copy_out"].append(st["copy_out"])
+            samples["compute"].append(sum(st[n] for n in ("router", "partition", "routed_gate_up_gemm",
+                                                          "routed_down_gemm", "shared_gate_up_gemm",
+                                                          "shared_down_gemm", "aggregation")))
+        fit = {n: pkg.fit_linear(pts, v) for n, v in samples.items()}
+        model = pkg.PipelineModel(fit["copy_in"][0], fit["copy_in"][1], fit["compute"][0], fit["compute"][1],
+                                  fit["copy_out"][0], fit["copy_out"][1])
+        r_sweep = [r for r in (1, 2, 4, 8) if r <= ctx.cfg.max_chunks]
+        measured = {}
+        for r in r_sweep:
+            for _ in range(5):
+                ctx.forward(tokens, logits, routed, shared, k, r, args.order, n_tokens=T, out=out, stream=stream)
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            for _ in range(20):
+                ctx.forward(tokens, logits, routed, shared, k, r, args.order, n_tokens=T, out=out, stream=stream)
+            torch.cuda.synchronize()
+            measured[r] = (time.perf_counter() - t1) / 20 * 1e3
+        ctx.set_pipeline_model(model)
+        ctx.forward(tokens, logits, routed, shared, k, 0, args.order, n_tokens=T, out=out, stream=stream)
+        torch.cuda.synchronize()
+        line["pipeline_fit"] = {
+            "tokens_per_point": pts,
+            "alpha_beta_r2": {n: {"alpha_ms": f[0], "beta_ms_per_token": f[1], "r2": f[2]} for n, f in fit.items()},
+            "predicted_ms": {str(r): pkg.pipeline_makespan(model, T, r) for r in r_sweep},
+            "measured_ms": {str(r): measured[r] for r in r_sweep},
+            "chosen_r": ctx.last_chunks(), "measured_best_r": min(measured, key=measured.get),
         }
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(wl, inp)

@@ -101,7 +101,8 @@ int moe_ep_create(const moe_ep_config *cfg, moe_ep_ctx **out_ctx);
  *               W_up [H, M], W_down [M, H], all row-major (Sec. 3.1); experts contiguous.
  *   shared_w    bf16, device: the same triple for each shared expert with H = shared_inter;
  *               NULL exactly when n_shared == 0.
- *   top_k       1..min(E, max_top_k);   r_chunks 1..max_chunks: the token range is cut
+ *   top_k       1..min(E, max_top_k);   r_chunks 1..max_chunks (0 = chosen from the context's
+ *               timing model, see moe_ep_set_pipeline_model): the token range is cut
  *               into r_chunks contiguous pieces of ceil(n_tokens / r_chunks) tokens (the
  *               last ones may be short or empty);   order: moe_ep_order (ignored when
  *               n_shared == 0).
@@ -154,6 +155,40 @@ int moe_ep_get_routing(moe_ep_ctx *ctx, int32_t chunk, int32_t *idx, float *w, i
  */
 int moe_ep_set_profiling(moe_ep_ctx *ctx, int32_t depth);
 int moe_ep_get_stage_ms(moe_ep_ctx *ctx, float *ms, int32_t n);
+
+/*
+ * Timing model of the chunk pipeline and the choice of r_2 (Sec. 4.1 linear task models; Sec. 4.2
+ * layer-0 timeline and "Determine r_2 and m_e"; Theorem 4).  Every task time is alpha + beta * m
+ * with m = tokens per chunk; times in any one unit (milliseconds in this repository).
+ */
+typedef struct {
+    double alpha_in, beta_in;   /* inbound transfer (A2E stand-in)  */
+    double alpha_e, beta_e;     /* expert compute of a chunk        */
+    double alpha_out, beta_out; /* outbound transfer (E2A stand-in) */
+} moe_ep_pipeline_model;
+
+/* Least-squares fit of t = alpha + beta * x over n >= 2 samples (host arrays); *r2 (may be NULL)
+ * receives the coefficient of determination.  MOE_EP_EINVAL if the x are all equal. */
+int moe_ep_fit_linear(const double *x, const double *t, int32_t n, double *alpha, double *beta,
+                      double *r2);
+
+/* Finish time of one slice of n_tokens cut into r_chunks chunks on three serial resources:
+ * t_in + t_e + t_out + (r - 1) * max(t_in, t_e, t_out), each at n_tokens / r_chunks tokens
+ * (the paper's 2 t_a2e + t_e + (r_2 - 1) max(t_e, t_a2e) when both links are alike).
+ * Returns a negative value on bad arguments. */
+double moe_ep_pipeline_makespan(const moe_ep_pipeline_model *m, int32_t n_tokens, int32_t r_chunks);
+
+/* The smallest r in 1..r_max that minimises moe_ep_pipeline_makespan: golden-section search over
+ * 1/r (the objective is convex there) and a walk over the neighbouring integers.  Returns r, or
+ * MOE_EP_EINVAL (negative) on bad arguments. */
+int32_t moe_ep_choose_chunks(const moe_ep_pipeline_model *m, int32_t n_tokens, int32_t r_max);
+
+/* Give a context its timing model: afterwards moe_ep_forward accepts r_chunks == 0 and picks
+ * r = moe_ep_choose_chunks(model, n_tokens, max_chunks) itself.  m == NULL removes the model. */
+int moe_ep_set_pipeline_model(moe_ep_ctx *ctx, const moe_ep_pipeline_model *m);
+
+/* r_chunks the last forward ran with (the chosen value when 0 was passed); -1 before any forward. */
+int32_t moe_ep_last_chunks(const moe_ep_ctx *ctx);
 
 /* Last error text of this context (never NULL; valid until the next call on it). */
 const char *moe_ep_last_error(const moe_ep_ctx *ctx);

@@ -5,9 +5,11 @@ The work is done by hand-written HIP kernels in ``libmoe_ep.so`` behind the C AB
 if the library has not been built, importing the binding raises.
 """
 from .binding import (IO_DEVICE, IO_PINNED_HOST, ORDER_INTERLEAVED, ORDER_SHARED_FIRST, STAGES,
-                      MoeEp, MoeEpConfig, MoeEpError, lib_path, load_library, validate_config,
-                      validate_forward, workspace_bytes)
+                      MoeEp, MoeEpConfig, MoeEpError, PipelineModel, choose_chunks, fit_linear, lib_path,
+                      load_library, pipeline_makespan, validate_config, validate_forward,
+                      workspace_bytes)
 
 __all__ = ["MoeEp", "MoeEpConfig", "MoeEpError", "load_library", "lib_path", "validate_config",
            "validate_forward", "workspace_bytes", "ORDER_SHARED_FIRST", "ORDER_INTERLEAVED",
-           "IO_DEVICE", "IO_PINNED_HOST", "STAGES"]
+           "IO_DEVICE", "IO_PINNED_HOST", "STAGES", "PipelineModel", "fit_linear", "pipeline_makespan",
+           "choose_chunks"]

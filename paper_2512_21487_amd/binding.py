@@ -28,6 +28,12 @@ class MoeEpError(RuntimeError):
         self.code = code
 
 
+class PipelineModel(ctypes.Structure):
+    """Mirror of ``moe_ep_pipeline_model`` (alpha + beta * tokens-per-chunk for each resource)."""
+    _fields_ = [(n, ctypes.c_double) for n in (
+        "alpha_in", "beta_in", "alpha_e", "beta_e", "alpha_out", "beta_out")]
+
+
 class MoeEpConfig(ctypes.Structure):
     """Mirror of ``moe_ep_config``."""
     _fields_ = [(n, ctypes.c_int32) for n in (
@@ -69,6 +75,17 @@ def load_library() -> ctypes.CDLL:
     lib.moe_ep_set_profiling.argtypes = [vp, i32]
     lib.moe_ep_get_stage_ms.restype = ctypes.c_int
     lib.moe_ep_get_stage_ms.argtypes = [vp, vp, i32]
+    dp = ctypes.POINTER(ctypes.c_double)
+    lib.moe_ep_fit_linear.restype = ctypes.c_int
+    lib.moe_ep_fit_linear.argtypes = [dp, dp, i32, dp, dp, dp]
+    lib.moe_ep_pipeline_makespan.restype = ctypes.c_double
+    lib.moe_ep_pipeline_makespan.argtypes = [ctypes.POINTER(PipelineModel), i32, i32]
+    lib.moe_ep_choose_chunks.restype = i32
+    lib.moe_ep_choose_chunks.argtypes = [ctypes.POINTER(PipelineModel), i32, i32]
+    lib.moe_ep_set_pipeline_model.restype = ctypes.c_int
+    lib.moe_ep_set_pipeline_model.argtypes = [vp, ctypes.POINTER(PipelineModel)]
+    lib.moe_ep_last_chunks.restype = i32
+    lib.moe_ep_last_chunks.argtypes = [vp]
     lib.moe_ep_last_error.restype = ctypes.c_char_p
     lib.moe_ep_last_error.argtypes = [vp]
     lib.moe_ep_destroy.restype = ctypes.c_int
@@ -109,6 +126,30 @@ def workspace_bytes(cfg: MoeEpConfig) -> int:
     return int(load_library().moe_ep_workspace_bytes(ctypes.byref(cfg)))
 
 
+def fit_linear(x, t) -> Tuple[float, float, float]:
+    """moe_ep_fit_linear: (alpha, beta, R^2) of t = alpha + beta x."""
+    x = np.ascontiguousarray(x, dtype=np.float64)
+    t = np.ascontiguousarray(t, dtype=np.float64)
+    a, b, r2 = ctypes.c_double(), ctypes.c_double(), ctypes.c_double()
+    dp = ctypes.POINTER(ctypes.c_double)
+    rc = load_library().moe_ep_fit_linear(x.ctypes.data_as(dp), t.ctypes.data_as(dp), int(x.size),
+                                          ctypes.byref(a), ctypes.byref(b), ctypes.byref(r2))
+    if rc != 0:
+        raise MoeEpError(rc, "moe_ep_fit_linear: need >= 2 samples with distinct workloads")
+    return a.value, b.value, r2.value
+
+
+def pipeline_makespan(model: PipelineModel, n_tokens: int, r_chunks: int) -> float:
+    return float(load_library().moe_ep_pipeline_makespan(ctypes.byref(model), n_tokens, r_chunks))
+
+
+def choose_chunks(model: PipelineModel, n_tokens: int, r_max: int) -> int:
+    r = int(load_library().moe_ep_choose_chunks(ctypes.byref(model), n_tokens, r_max))
+    if r < 1:
+        raise MoeEpError(r, "moe_ep_choose_chunks: bad arguments")
+    return r
+
+
 class MoeEp:
     """Owns one ``moe_ep_ctx``.  Tensors are torch tensors (or raw addresses) that the caller
     allocated; nothing is computed on the Python side."""
@@ -143,7 +184,7 @@ class MoeEp:
                                       stream)
         if rc != 0:
             raise MoeEpError(rc, self.last_error())
-        self._last = (n_tokens, top_k, r_chunks)
+        self._last = (n_tokens, top_k, int(self._lib.moe_ep_last_chunks(self._ctx)))
         return rc
 
     # -- moe_ep_get_routing ---------------------------------------------------------------
@@ -165,6 +206,15 @@ class MoeEp:
             raise MoeEpError(rc, self.last_error())
         return {"idx": idx, "w": w, "pos": pos, "count": count, "offset": offset,
                 "perm": perm[:offset[-1]].copy()}
+
+    # -- timing model ---------------------------------------------------------------------
+    def set_pipeline_model(self, model: Optional[PipelineModel]) -> None:
+        rc = self._lib.moe_ep_set_pipeline_model(self._ctx, ctypes.byref(model) if model else None)
+        if rc != 0:
+            raise MoeEpError(rc, self.last_error())
+
+    def last_chunks(self) -> int:
+        return int(self._lib.moe_ep_last_chunks(self._ctx))
 
     # -- profiling ------------------------------------------------------------------------
     def set_profiling(self, depth: int) -> None:

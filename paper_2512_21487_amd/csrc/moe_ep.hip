@@ -48,6 +48,9 @@ struct moe_ep_ctx {
     int prof_depth = 0, prof_recorded = 0;
     std::vector<hipEvent_t> prof_pool; size_t prof_next = 0;
     std::vector<ProfSpan> prof_spans;
+    // timing model for r_chunks == 0
+    bool has_model = false;
+    moe_ep_pipeline_model model{};
     char err[256] = {0};
 };
 
@@ -156,7 +159,7 @@ int moe_ep_validate_forward(const moe_ep_config* c, const void* tokens, const fl
     if (rc != MOE_EP_OK) return rc;
     if (n_tokens < 0 || n_tokens > c->max_tokens) { set_why(why, "n_tokens must be in 0..max_tokens"); return MOE_EP_EINVAL; }
     if (top_k < 1 || top_k > c->max_top_k || top_k > c->n_experts) { set_why(why, "top_k must be in 1..min(n_experts, max_top_k)"); return MOE_EP_EINVAL; }
-    if (r_chunks < 1 || r_chunks > c->max_chunks) { set_why(why, "r_chunks must be in 1..max_chunks"); return MOE_EP_EINVAL; }
+    if (r_chunks < 0 || r_chunks > c->max_chunks) { set_why(why, "r_chunks must be in 0..max_chunks (0 = from the timing model)"); return MOE_EP_EINVAL; }
     if (c->n_shared > 0 && order != MOE_EP_ORDER_SHARED_FIRST && order != MOE_EP_ORDER_INTERLEAVED) {
         set_why(why, "unknown order"); return MOE_EP_EINVAL; }
     if (!routed_w) { set_why(why, "routed_w is NULL"); return MOE_EP_EINVAL; }
@@ -254,6 +257,16 @@ int moe_ep_create(const moe_ep_config* cfg, moe_ep_ctx** out_ctx)
 
 const char* moe_ep_last_error(const moe_ep_ctx* ctx) { return ctx ? ctx->err : "context is NULL"; }
 
+int32_t moe_ep_last_chunks(const moe_ep_ctx* ctx) { return (ctx && ctx->last_T >= 0) ? ctx->last_r : -1; }
+
+int moe_ep_set_pipeline_model(moe_ep_ctx* ctx, const moe_ep_pipeline_model* m)
+{
+    if (!ctx) return MOE_EP_EINVAL;
+    ctx->has_model = m != nullptr;
+    if (m) ctx->model = *m;
+    return MOE_EP_OK;
+}
+
 int moe_ep_set_profiling(moe_ep_ctx* ctx, int32_t depth)
 {
     if (!ctx || depth < 0 || depth > 256) return MOE_EP_EINVAL;
@@ -303,6 +316,10 @@ int moe_ep_forward(moe_ep_ctx* ctx, const void* tokens, const float* gate_logits
                                 order, n_tokens, out, &why) != MOE_EP_OK)
         return fail(ctx, MOE_EP_EINVAL, why);
     ctx->err[0] = 0;
+    if (r_chunks == 0) {
+        if (!ctx->has_model) return fail(ctx, MOE_EP_ESTATE, "r_chunks == 0 needs moe_ep_set_pipeline_model first");
+        r_chunks = moe_ep_choose_chunks(&ctx->model, n_tokens, ctx->cfg.max_chunks);
+    }
     const moe_ep_config& c = ctx->cfg;
     const int T = n_tokens, k = top_k, r = r_chunks;
     const int M = c.hidden, H = c.inter, E = c.n_experts, El = c.n_local, e0 = c.local_begin;

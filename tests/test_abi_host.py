@@ -76,7 +76,7 @@ def test_create_rejects_bad_config_without_touching_hip():
 
 
 @pytest.mark.parametrize("kw,word", [
-    (dict(top_k=0), "top_k"), (dict(top_k=3), "top_k"), (dict(r_chunks=0), "r_chunks"),
+    (dict(top_k=0), "top_k"), (dict(top_k=3), "top_k"), (dict(r_chunks=-1), "r_chunks"),
     (dict(r_chunks=9), "r_chunks"), (dict(n_tokens=-1), "n_tokens"),
     (dict(n_tokens=129), "n_tokens"), (dict(order=2), "order"), (dict(routed_w=None), "routed_w"),
     (dict(shared_w=None), "shared_w"), (dict(tokens=None), "tokens"), (dict(out=None), "tokens"),
@@ -95,6 +95,7 @@ def test_forward_edge_arguments_that_are_legal():
     base = dict(tokens=0x1000, gate_logits=0x2000, routed_w=0x3000, shared_w=0x4000, top_k=2,
                 r_chunks=8, order=1, n_tokens=3, out=0x5000)
     assert pkg.validate_forward(_good(), **base)[0] == 0          # r_chunks > n_tokens
+    assert pkg.validate_forward(_good(), **dict(base, r_chunks=0))[0] == 0   # 0 = from the timing model
     base.update(n_tokens=0, tokens=None, gate_logits=None, out=None)
     assert pkg.validate_forward(_good(), **base)[0] == 0          # empty call is a no-op
     noshared = _good(n_shared=0, shared_inter=0)

@@ -200,6 +200,30 @@ def test_pinned_host_pipeline_matches_device_mode():
     pctx.destroy()
 
 
+def test_auto_chunks_from_timing_model():
+    """r_chunks = 0 takes r_2 from the context's timing model (Sec. 4.2) and changes no output bit."""
+    g = _gpu()
+    import paper_2512_21487_amd as pkg
+    wl = CONFIGS["tiny"]
+    ctx = g.make_ctx(wl, max_chunks=8)
+    d = g.DeviceInputs(wl, make_inputs(wl))
+    base = g.run_forward(ctx, wl, d, r=1)
+    with pytest.raises(pkg.MoeEpError) as ei:       # no model yet
+        g.run_forward(ctx, wl, d, r=0)
+    assert ei.value.code == -4
+    # transfers dominate and scale with tokens, start-up costs are small: chunking pays off
+    model = pkg.PipelineModel(0.001, 0.01, 0.001, 0.005, 0.001, 0.01)
+    ctx.set_pipeline_model(model)
+    out = g.run_forward(ctx, wl, d, r=0)
+    want = pkg.choose_chunks(model, wl.n_tokens, 8)
+    assert ctx.last_chunks() == want and want > 1
+    assert np.array_equal(out, base)
+    ctx.set_pipeline_model(pkg.PipelineModel(1.0, 0.0, 1.0, 0.0, 1.0, 0.0))   # start-up only -> 1
+    g.run_forward(ctx, wl, d, r=0)
+    assert ctx.last_chunks() == 1
+    ctx.destroy()
+
+
 def test_errors_surface_as_status_codes():
     g = _gpu()
     import paper_2512_21487_amd as pkg
