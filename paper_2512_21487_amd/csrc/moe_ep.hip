@@ -236,18 +236,21 @@ int moe_ep_create(const moe_ep_config* cfg, moe_ep_ctx** out_ctx)
     ctx->hs = reinterpret_cast<uint16_t*>(slab + L.hs);
     ctx->ysh = reinterpret_cast<uint16_t*>(slab + L.ysh);
 
+    // the chunk events order GPU work against GPU work only, so they skip the system-scope cache
+    // write-back a default event record implies (it stalled the other streams' kernels)
+    const unsigned ev_flags = hipEventDisableTiming | hipEventDisableSystemFence;
     bool ok = true;
     ok = ok && hipStreamCreateWithFlags(&ctx->s_in, hipStreamNonBlocking) == hipSuccess;
     ok = ok && hipStreamCreateWithFlags(&ctx->s_comp, hipStreamNonBlocking) == hipSuccess;
     ok = ok && hipStreamCreateWithFlags(&ctx->s_out, hipStreamNonBlocking) == hipSuccess;
-    ok = ok && hipEventCreateWithFlags(&ctx->ev_start, hipEventDisableTiming) == hipSuccess;
+    ok = ok && hipEventCreateWithFlags(&ctx->ev_start, ev_flags) == hipSuccess;
     ok = ok && hipEventCreateWithFlags(&ctx->ev_done, hipEventDisableTiming) == hipSuccess;
-    ok = ok && hipEventCreateWithFlags(&ctx->ev_comp_done, hipEventDisableTiming) == hipSuccess;
+    ok = ok && hipEventCreateWithFlags(&ctx->ev_comp_done, ev_flags) == hipSuccess;
     for (int i = 0; ok && i < cfg->max_chunks; ++i) {
         hipEvent_t a = nullptr, b = nullptr;
-        ok = ok && hipEventCreateWithFlags(&a, hipEventDisableTiming) == hipSuccess;
+        ok = ok && hipEventCreateWithFlags(&a, ev_flags) == hipSuccess;
         if (a) ctx->ev_in.push_back(a);
-        ok = ok && hipEventCreateWithFlags(&b, hipEventDisableTiming) == hipSuccess;
+        ok = ok && hipEventCreateWithFlags(&b, ev_flags) == hipSuccess;
         if (b) ctx->ev_comp.push_back(b);
     }
     if (!ok) { moe_ep_destroy(ctx); return MOE_EP_EHIP; }
@@ -359,7 +362,10 @@ int moe_ep_forward(moe_ep_ctx* ctx, const void* tokens, const float* gate_logits
         h_tokens = static_cast<const char*>(dev[0]); h_logits = static_cast<const char*>(dev[1]);
         h_out = static_cast<char*>(dev[2]);
     }
-    const int link_grid = 64;  // workgroups of a copy kernel: enough bytes in flight to fill the host link
+    // workgroups of a copy kernel: ~128 KB in flight fills the host link; more only queues up in the
+    // memory fabric in front of the other streams' kernels (measured: they ran 3-10x slower)
+    int link_grid = 8;
+    if (const char* v = getenv("MOE_EP_LINK_GRID")) link_grid = atoi(v) > 0 ? atoi(v) : 8;
     const int span_total = prof_begin(ctx, prof, ST_TOTAL, user);
     if (pinned) {
         HIP_TRY(ctx, hipEventRecord(ctx->ev_start, user));
