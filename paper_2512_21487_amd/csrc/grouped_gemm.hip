@@ -53,13 +53,17 @@ struct GemmCfg {
     static_assert((BM / RPR) % NW == 0 && (BN / RPR) % NW == 0, "regions split evenly over wavefronts");
     static_assert(STAGES >= 2 && STAGES <= 5 && (STAGES - 2) * RPW <= 63, "ring depth and vmcnt budget");
     static_assert(KG == 1 || (KG == 2 && MB % 2 == 0 && KKW >= 1), "K split over two wavefront groups");
+    static_assert(KKW % 2 == 0, "a K step starts and ends on fragment set 0 / 1");
+    static_assert(RPW <= (KKW - 1) * MB * NB, "a K step's loads are issued before it hands over the next ring slot");
+    static_assert(MB + NB <= MB * NB, "one fragment read per MFMA slot");
     static_assert(KG == 1 || LDS_BYTES >= NW * (MB / 2) * NB * 1024, "partial sums are exchanged through the ring's LDS");
 };
 
 __device__ __forceinline__ float silu_f(float g) { return g / (1.0f + __expf(-g)); }
 
-// s_waitcnt with only vmcnt constrained (gfx9 encoding: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[5:4] << 14)
-#define MOE_EP_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | (((n) >> 4) << 14) | 0x0F70)
+// s_waitcnt vmcnt(n) lgkmcnt(0): all but the newest n vector-memory loads have landed and every LDS
+// read has returned (gfx9 encoding: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[5:4] << 14)
+#define MOE_EP_WAIT_VMCNT_LGKM0(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | (((n) >> 4) << 14) | 0x0070)
 
 template <int BM, int BN, int BK, int STAGES, int WGM, int WGN, int KG, bool SWIGLU, bool RAGGED>
 __global__ __launch_bounds__(WGM* WGN* KG * 64) void grouped_gemm_kernel(GemmArgs a)
@@ -72,7 +76,8 @@ __global__ __launch_bounds__(WGM* WGN* KG * 64) void grouped_gemm_kernel(GemmArg
     __shared__ int s_pref[513];
     __shared__ int s_off[513];
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform: LDS destinations stay scalar
     const int wn = wave % WGN, wm = (wave / WGN) % WGM, kg = wave / (WGN * WGM);
     const int NT = (a.N + BN_OUT - 1) / BN_OUT;
     int mt_total, mt_per = 0;
@@ -131,11 +136,19 @@ __global__ __launch_bounds__(WGM* WGN* KG * 64) void grouped_gemm_kernel(GemmArg
             row0 = mi * BM;
             nrows = min(BM, a.dense_rows - row0);
         }
-        const int n0 = ni * BN_OUT;
+        // the tile's coordinates came through LDS; telling the compiler they are wavefront-uniform
+        // keeps base addresses in scalar registers and leaves the lanes 32-bit offsets only
+        g = __builtin_amdgcn_readfirstlane(g);
+        row0 = __builtin_amdgcn_readfirstlane(row0);
+        nrows = __builtin_amdgcn_readfirstlane(nrows);
+        const int n0 = __builtin_amdgcn_readfirstlane(ni * BN_OUT);
         const uint16_t* Wg = a.W + (size_t)g * a.w_group_stride;
+        const uint16_t* Xg = a.A + (size_t)row0 * a.lda;
 
-        // per region this wavefront loads: the lane's global source (row, swizzled chunk)
-        const uint16_t* gptr[RPW];
+        // per region this wavefront loads: the lane's global source (row, swizzled chunk) as a byte
+        // offset from the tile's activation rows Xg or the group's weights Wg (one group's matrices
+        // and one activation panel are checked by the launcher to span less than 2^32 bytes)
+        uint32_t goff[RPW];
 #pragma unroll
         for (int i = 0; i < RPW; ++i) {
             const int j = wave + NW * i;                 // region index inside a stage
@@ -143,18 +156,18 @@ __global__ __launch_bounds__(WGM* WGN* KG * 64) void grouped_gemm_kernel(GemmArg
             const int c = ld_p ^ ((r / RP) % CPR);       // logical chunk stored at physical slot ld_p
             if (i < XRPW) {
                 const int rr = min(r, nrows - 1);        // rows past the end re-read the last valid row
-                gptr[i] = a.A + (size_t)(row0 + rr) * a.lda + c * 8;
+                goff[i] = ((uint32_t)rr * (uint32_t)a.lda + c * 8) * 2u;
             } else {
                 const int jw = r - BM;                   // row of the weight tile
                 int n;
-                const uint16_t* base = Wg;
+                uint32_t base = 0;
                 if (SWIGLU) {
-                    if (jw < BN / 2) n = n0 + jw; else { n = n0 + jw - BN / 2; base = Wg + a.w_up_offset; }
+                    if (jw < BN / 2) n = n0 + jw; else { n = n0 + jw - BN / 2; base = (uint32_t)a.w_up_offset; }
                 } else {
                     n = n0 + jw;
                 }
                 n = min(n, a.N - 1);
-                gptr[i] = base + (size_t)n * a.ldw + c * 8;
+                goff[i] = (base + (uint32_t)n * (uint32_t)a.ldw + c * 8) * 2u;
             }
         }
 
@@ -173,14 +186,15 @@ __global__ __launch_bounds__(WGM* WGN* KG * 64) void grouped_gemm_kernel(GemmArg
             return BM + wn * Cfg::WTN + nb * 32;
         };
         bf16x8_t xf[2][MB], wf[2][NB];
-        // one LDS fragment read: index f < MB is an activation block, f >= MB a weight block
-#define MOE_EP_FRAG1(kk_, set_, f_)                                                               \
+        // one LDS fragment read from ring slot base sT_: index f < MB is an activation block,
+        // f >= MB a weight block
+#define MOE_EP_FRAG1(sT_, kk_, set_, f_)                                                          \
         {                                                                                         \
             const int csw_ = ((kk_) * 2 + fr_kh) ^ fr_sw;                                         \
             if ((f_) < MB) xf[set_][(f_) < MB ? (f_) : 0] = __builtin_bit_cast(bf16x8_t,          \
-                sT[(wm * Cfg::WTM + (f_) * 32 + fr_row) * CPR + csw_]);                           \
+                (sT_)[(wm * Cfg::WTM + (f_) * 32 + fr_row) * CPR + csw_]);                        \
             else wf[set_][(f_) >= MB ? (f_) - MB : 0] = __builtin_bit_cast(bf16x8_t,              \
-                sT[(w_row_base((f_) >= MB ? (f_) - MB : 0) + fr_row) * CPR + csw_]);              \
+                (sT_)[(w_row_base((f_) >= MB ? (f_) - MB : 0) + fr_row) * CPR + csw_]);           \
         }
         // one direct-to-LDS load: region i of this wavefront, K step kt_, ring slot stage_
 #define MOE_EP_ISSUE1(kt_, stage_, i_)                                                            \
@@ -190,55 +204,84 @@ __global__ __launch_bounds__(WGM* WGN* KG * 64) void grouped_gemm_kernel(GemmArg
             const size_t wk_ = (size_t)seg_ * a.w_kseg_stride + (k_ - seg_ * a.kseg_len);         \
             uint4* dst_ = lds + (stage_) * Cfg::STAGE_CHUNKS + wave * 64 + NW * 64 * (i_);        \
             __builtin_amdgcn_global_load_lds(                                                     \
-                reinterpret_cast<const uint4*>(gptr[i_] + ((i_) < XRPW ? (size_t)k_ : wk_)),      \
+                reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(                     \
+                    (i_) < XRPW ? Xg + k_ : Wg + wk_) + goff[i_]),                                \
                 dst_, 16, 0, 0);                                                                  \
         }
 #define SB() __builtin_amdgcn_sched_barrier(0)
-        // One K step.  The source order below is the issue order: sched_barrier(0) after every
-        // MFMA keeps the compiler from regrouping.  This wavefront multiplies k16 steps
-        // kg*KKW .. kg*KKW+KKW-1 of the K step; step i works out of fragment set i & 1 while the
-        // LDS reads of step i+1 and the global loads STAGES-1 K steps ahead are slipped between
-        // its MFMAs.  Fragment reads are ordered so that the first MFMA needs only the first two.
-#define MOE_EP_FRAG_ORDER(f_) ((f_) == 0 ? MB : (f_) <= MB ? (f_) - 1 : (f_))
-#define MOE_EP_STEP(kt_, pending_, issue_)                                                        \
+        // The hand-over of ring slot `slot_` to the MFMAs: this wavefront's loads into it have landed
+        // (all but the newest pending_ loads), its own LDS reads of older slots have returned, and
+        // after the barrier the same holds for every wavefront, so the slot may be read and the
+        // slot read before it may be refilled.
+#define MOE_EP_HANDOVER(pending_)                                                                 \
         {                                                                                         \
-            MOE_EP_WAIT_VMCNT(pending_);                                                          \
+            MOE_EP_WAIT_VMCNT_LGKM0(pending_);                                                    \
             __builtin_amdgcn_s_barrier();                                                         \
             asm volatile("" ::: "memory");                                                        \
+        }
+        // One K step.  The source order below is the issue order: sched_barrier(0) after every
+        // MFMA keeps the compiler from regrouping.  This wavefront multiplies k16 steps
+        // kg*KKW .. kg*KKW+KKW-1 of the K step; k16 step i works out of fragment set i & 1 while
+        // the LDS reads of step i+1 and the global loads STAGES-1 K steps ahead are slipped between
+        // its MFMAs.  The fragments of a K step's first k16 step are read during the LAST k16
+        // step of the K step before it: the hand-over of the next ring slot sits in front of those
+        // MFMAs (next_pending_ = loads that may still be in flight then; has_next_ = false for the
+        // tile's last K step), so the LDS latency after a barrier hides behind MB*NB MFMAs.
+        // Fragment reads are ordered so that the first MFMA needs only the first two.
+#define MOE_EP_FRAG_ORDER(f_) ((f_) == 0 ? MB : (f_) <= MB ? (f_) - 1 : (f_))
+#define MOE_EP_STEP(kt_, issue_, has_next_, next_pending_)                                        \
+        {                                                                                         \
             const uint4* sT = lds + stage * Cfg::STAGE_CHUNKS;                                    \
+            const int st_next = stage == STAGES - 1 ? 0 : stage + 1;                              \
+            const uint4* sN = lds + st_next * Cfg::STAGE_CHUNKS;                                  \
             const int st2 = stage == 0 ? STAGES - 1 : stage - 1;                                  \
-            _Pragma("unroll") for (int f = 0; f < MB + NB; ++f) MOE_EP_FRAG1(kg * KKW, 0, MOE_EP_FRAG_ORDER(f)) \
-            SB();                                                                                 \
             _Pragma("unroll") for (int i = 0; i < KKW; ++i) {                                     \
+                if (i == KKW - 1 && (has_next_)) MOE_EP_HANDOVER(next_pending_)                   \
                 _Pragma("unroll") for (int q = 0; q < MB * NB; ++q) {                             \
                     const int nb = q / MB, mb = q % MB;                                           \
                     acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[i & 1][nb], xf[i & 1][mb], acc[mb][nb], 0, 0, 0); \
-                    if (i + 1 < KKW && q < MB + NB) MOE_EP_FRAG1(kg * KKW + i + 1, (i + 1) & 1, MOE_EP_FRAG_ORDER(q)) \
-                    if (issue_) {                                              \
+                    if (q < MB + NB) {                                                            \
+                        if (i + 1 < KKW) MOE_EP_FRAG1(sT, kg * KKW + i + 1, (i + 1) & 1, MOE_EP_FRAG_ORDER(q)) \
+                        else if (has_next_) MOE_EP_FRAG1(sN, kg * KKW, 0, MOE_EP_FRAG_ORDER(q))   \
+                    }                                                                             \
+                    if (issue_) {                                                                 \
                         _Pragma("unroll") for (int l = i * MB * NB + q; l < RPW; l += KKW * MB * NB) \
                             MOE_EP_ISSUE1((kt_) + STAGES - 1, st2, l)                             \
                     }                                                                             \
                     SB();                                                                         \
                 }                                                                                 \
             }                                                                                     \
-            stage = stage == STAGES - 1 ? 0 : stage + 1;                                          \
+            stage = st_next;                                                                      \
         }
 
-        // prologue: the first STAGES-1 K steps go in flight
+        // prologue: the first STAGES-1 K steps go in flight, the first one is handed over and its
+        // first fragments are read
 #pragma unroll
         for (int p = 0; p < STAGES - 1; ++p)
             if (p < KT) {
 #pragma unroll
                 for (int i = 0; i < RPW; ++i) MOE_EP_ISSUE1(p, p, i)
             }
+        {
+            const int ahead = min(STAGES - 2, KT - 1);  // K steps in flight behind the first
+            if (STAGES >= 5 && ahead == 3) MOE_EP_HANDOVER(3 * RPW)
+            else if (STAGES >= 4 && ahead == 2) MOE_EP_HANDOVER(2 * RPW)
+            else if (STAGES >= 3 && ahead == 1) MOE_EP_HANDOVER(1 * RPW)
+            else MOE_EP_HANDOVER(0)
+#pragma unroll
+            for (int f = 0; f < MB + NB; ++f) MOE_EP_FRAG1(lds, kg * KKW, 0, MOE_EP_FRAG_ORDER(f))
+            SB();
+        }
         int stage = 0;
         int kt = 0;
-        for (; kt + STAGES - 1 < KT; ++kt) MOE_EP_STEP(kt, (STAGES - 2) * RPW, true)
-        // tail: no more loads to issue; the step that leaves p K steps in flight runs if KT > p
-        if constexpr (STAGES >= 5) { if (KT >= 4) MOE_EP_STEP(kt, 3 * RPW, false) }
-        if constexpr (STAGES >= 4) { if (KT >= 3) MOE_EP_STEP(kt, 2 * RPW, false) }
-        if constexpr (STAGES >= 3) { if (KT >= 2) MOE_EP_STEP(kt, 1 * RPW, false) }
-        MOE_EP_STEP(kt, 0, false)
+        // K step kt hands over K step kt+1, behind which STAGES-2 more are in flight
+        for (; kt + STAGES - 1 < KT; ++kt) MOE_EP_STEP(kt, true, true, (STAGES - 2) * RPW)
+        // tail: no more loads to issue; the step that leaves p K steps to go runs if KT > p
+        if constexpr (STAGES >= 5) { if (KT >= 4) MOE_EP_STEP(kt, false, true, 2 * RPW) }
+        if constexpr (STAGES >= 4) { if (KT >= 3) MOE_EP_STEP(kt, false, true, 1 * RPW) }
+        if constexpr (STAGES >= 3) { if (KT >= 2) MOE_EP_STEP(kt, false, true, 0) }
+        MOE_EP_STEP(kt, false, false, 0)
+#undef MOE_EP_HANDOVER
 #undef MOE_EP_STEP
 #undef MOE_EP_FRAG_ORDER
 #undef SB
@@ -332,6 +375,10 @@ static hipError_t launch_one(const GemmArgs& a, int n_cu, int max_row_tiles, hip
     const int NT = (a.N + Cfg::BN_OUT - 1) / Cfg::BN_OUT;
     const long long max_tiles = (long long)max_row_tiles * NT;
     if (max_tiles <= 0) return hipSuccess;
+    // lanes address with 32-bit byte offsets inside one group's weights and one activation panel
+    const long long w_span = ((SWIGLU ? a.w_up_offset : 0) + (long long)a.N * a.ldw) * 2;
+    const long long x_span = (long long)BM * a.lda * 2;
+    if (w_span >= (1ll << 32) || x_span >= (1ll << 32) || w_span < 0) return hipErrorInvalidValue;
     // workgroups per CU: LDS (160 KB minus the kernel's small static tables) and 8 wavefront slots
     int occ = (156 * 1024) / Cfg::LDS_BYTES;
     const int by_waves = 8 / Cfg::NW;
