@@ -190,6 +190,82 @@ int moe_ep_set_pipeline_model(moe_ep_ctx *ctx, const moe_ep_pipeline_model *m);
 /* r_chunks the last forward ran with (the chosen value when 0 was passed); -1 before any forward. */
 int32_t moe_ep_last_chunks(const moe_ep_ctx *ctx);
 
+/*
+ * Schedule model of disaggregated expert parallelism and the configuration search (host only, no
+ * GPU call).  Notation of the paper: m_a samples per attention micro-batch, r_1 micro-batches,
+ * m_e tokens per expert and chunk, r_2 chunks, T layers, ag / eg group sizes, S sequence length.
+ * Task times are linear (Sec. 4.1): t_a(m_a), t_s(m_a), t_e(m_e), t_a2e(m_e) = t_e2a(m_e); m_e follows
+ * from the conservation rule m_e * r_2 * E = m_a * ag * top_k * S (Sec. 3.2, Eq. limitation).
+ */
+typedef struct {
+    double alpha_a, beta_a; /* attention of one micro-batch, argument m_a              */
+    double alpha_s, beta_s; /* shared experts of one micro-batch, argument m_a         */
+    double alpha_e, beta_e; /* routed experts of one chunk on one device, argument m_e */
+    double alpha_c, beta_c; /* A2E (= E2A) transfer of one chunk, argument m_e         */
+} moe_ep_dep_models;
+
+typedef struct {
+    int32_t ag;        /* attention-group size   */
+    int32_t n_experts; /* E                      */
+    int32_t top_k;
+    int32_t seq_len;   /* S                      */
+    int32_t n_layers;  /* T                      */
+} moe_ep_dep_problem;
+
+/* Order in which the attention group takes a layer's tasks (Sec. 4.2): a_0 s_0 a_1 s_1 ... or
+ * a_0 a_1 ... s_0 s_1 ... */
+typedef enum { MOE_EP_DEP_ASAS = 0, MOE_EP_DEP_AASS = 1 } moe_ep_dep_order;
+
+typedef struct {
+    int32_t m_a, r_1, r_2, order;
+    double m_e;        /* tokens per expert and chunk                         */
+    double makespan;   /* of the T layers, in the unit of the models          */
+    double throughput; /* r_1 * m_a * ag / makespan (Sec. 3.2, Eq. final-objective) */
+} moe_ep_dep_config;
+
+/* Primitives of Sec. 4.1: GEMM time alpha_gm + beta_gm * (m k n), attention time alpha_attn +
+ * beta_attn * y, link time alpha_c + beta_c * z, and the layer's shape. */
+typedef struct {
+    double alpha_gm, beta_gm, alpha_attn, beta_attn, alpha_c, beta_c;
+    int32_t seq_len, hidden, inter, n_heads, d_k, d_v, n_shared, n_experts, eg;
+} moe_ep_dep_primitives;
+
+/* Coefficients of the four task models from the primitives (Sec. 4.1, "Performance models of
+ * different layers"; alpha_e includes the factor 3 of Eq. moe_detail). */
+int moe_ep_dep_layer_models(const moe_ep_dep_primitives *q, moe_ep_dep_models *out);
+
+/* m_e for (m_a, r_2); negative on bad arguments. */
+double moe_ep_dep_tokens_per_expert(const moe_ep_dep_problem *p, int32_t m_a, int32_t r_2);
+
+/*
+ * Earliest-start replay of the timing rules of Eq. limitation: attention group, A2E link, expert
+ * group and E2A link each run one task at a time in a fixed sequence (links and experts by layer,
+ * micro-batch, chunk; the attention group by `order`), and a task starts when its resource is free
+ * and what it depends on has finished.  *makespan = max(end of the last shared expert, end of the
+ * last E2A).  The tau arrays (host, may be NULL) receive the start times, row-major
+ * tau_a, tau_s [T][r_1];  tau_a2e, tau_e, tau_e2a [T][r_1][r_2].
+ */
+int moe_ep_dep_replay(const moe_ep_dep_models *m, const moe_ep_dep_problem *p, int32_t m_a, int32_t r_1,
+                      int32_t r_2, int32_t order, double *makespan, double *tau_a, double *tau_s,
+                      double *tau_a2e, double *tau_e, double *tau_e2a);
+
+/* Makespan model of the ASAS order over T layers (Sec. 4.2, denominator of Eq. simplify-objective):
+ * (T-1) max(G, r_1 F) + max(X, G) + (r_1 - 1) F.  Negative on bad arguments. */
+double moe_ep_dep_makespan(const moe_ep_dep_models *m, const moe_ep_dep_problem *p, int32_t m_a,
+                           int32_t r_1, int32_t r_2);
+
+/* The smallest r_2 in 1..r2_max with the smallest makespan for (m_a, r_1, order) (Sec. 4.2,
+ * "Determine r_2 and m_e"; Theorem 4): ASAS by a convex search over 1 / r_2 on the model above,
+ * AASS, for which the paper gives no closed form, by replaying every r_2. */
+int moe_ep_dep_solve_r2(const moe_ep_dep_models *m, const moe_ep_dep_problem *p, int32_t m_a, int32_t r_1,
+                        int32_t order, int32_t r2_max, int32_t *r_2, double *makespan);
+
+/* Algorithm 1: m_a from m_a_max down to 1, r_1 = min(r1_cap, mem_cap / m_a) (the memory rule
+ * r_1 * m_a <= mem_cap), pairs whose r_1 equals the previous one skipped, both orders, r_2 as above;
+ * *best receives the configuration of highest throughput.  MOE_EP_ESTATE if no pair fits. */
+int moe_ep_dep_search(const moe_ep_dep_models *m, const moe_ep_dep_problem *p, int32_t m_a_max,
+                      int32_t mem_cap, int32_t r1_cap, int32_t r2_max, moe_ep_dep_config *best);
+
 /* Last error text of this context (never NULL; valid until the next call on it). */
 const char *moe_ep_last_error(const moe_ep_ctx *ctx);
 

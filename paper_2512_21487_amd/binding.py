@@ -34,6 +34,35 @@ class PipelineModel(ctypes.Structure):
         "alpha_in", "beta_in", "alpha_e", "beta_e", "alpha_out", "beta_out")]
 
 
+class DepModels(ctypes.Structure):
+    """Mirror of ``moe_ep_dep_models`` (linear task models of attention, shared experts, experts, link)."""
+    _fields_ = [(n, ctypes.c_double) for n in (
+        "alpha_a", "beta_a", "alpha_s", "beta_s", "alpha_e", "beta_e", "alpha_c", "beta_c")]
+
+
+class DepProblem(ctypes.Structure):
+    """Mirror of ``moe_ep_dep_problem``."""
+    _fields_ = [(n, ctypes.c_int32) for n in ("ag", "n_experts", "top_k", "seq_len", "n_layers")]
+
+
+class DepConfig(ctypes.Structure):
+    """Mirror of ``moe_ep_dep_config``."""
+    _fields_ = [("m_a", ctypes.c_int32), ("r_1", ctypes.c_int32), ("r_2", ctypes.c_int32),
+                ("order", ctypes.c_int32), ("m_e", ctypes.c_double), ("makespan", ctypes.c_double),
+                ("throughput", ctypes.c_double)]
+
+
+class DepPrimitives(ctypes.Structure):
+    """Mirror of ``moe_ep_dep_primitives``."""
+    _fields_ = [(n, ctypes.c_double) for n in (
+        "alpha_gm", "beta_gm", "alpha_attn", "beta_attn", "alpha_c", "beta_c")] + [
+        (n, ctypes.c_int32) for n in (
+            "seq_len", "hidden", "inter", "n_heads", "d_k", "d_v", "n_shared", "n_experts", "eg")]
+
+
+DEP_ASAS, DEP_AASS = 0, 1
+
+
 class MoeEpConfig(ctypes.Structure):
     """Mirror of ``moe_ep_config``."""
     _fields_ = [(n, ctypes.c_int32) for n in (
@@ -86,6 +115,19 @@ def load_library() -> ctypes.CDLL:
     lib.moe_ep_set_pipeline_model.argtypes = [vp, ctypes.POINTER(PipelineModel)]
     lib.moe_ep_last_chunks.restype = i32
     lib.moe_ep_last_chunks.argtypes = [vp]
+    mp, pp = ctypes.POINTER(DepModels), ctypes.POINTER(DepProblem)
+    lib.moe_ep_dep_layer_models.restype = ctypes.c_int
+    lib.moe_ep_dep_layer_models.argtypes = [ctypes.POINTER(DepPrimitives), mp]
+    lib.moe_ep_dep_tokens_per_expert.restype = ctypes.c_double
+    lib.moe_ep_dep_tokens_per_expert.argtypes = [pp, i32, i32]
+    lib.moe_ep_dep_replay.restype = ctypes.c_int
+    lib.moe_ep_dep_replay.argtypes = [mp, pp, i32, i32, i32, i32, dp, dp, dp, dp, dp, dp]
+    lib.moe_ep_dep_makespan.restype = ctypes.c_double
+    lib.moe_ep_dep_makespan.argtypes = [mp, pp, i32, i32, i32]
+    lib.moe_ep_dep_solve_r2.restype = ctypes.c_int
+    lib.moe_ep_dep_solve_r2.argtypes = [mp, pp, i32, i32, i32, i32, ctypes.POINTER(i32), dp]
+    lib.moe_ep_dep_search.restype = ctypes.c_int
+    lib.moe_ep_dep_search.argtypes = [mp, pp, i32, i32, i32, i32, ctypes.POINTER(DepConfig)]
     lib.moe_ep_last_error.restype = ctypes.c_char_p
     lib.moe_ep_last_error.argtypes = [vp]
     lib.moe_ep_destroy.restype = ctypes.c_int
@@ -148,6 +190,60 @@ def choose_chunks(model: PipelineModel, n_tokens: int, r_max: int) -> int:
     if r < 1:
         raise MoeEpError(r, "moe_ep_choose_chunks: bad arguments")
     return r
+
+
+def dep_layer_models(prim: DepPrimitives) -> DepModels:
+    out = DepModels()
+    rc = load_library().moe_ep_dep_layer_models(ctypes.byref(prim), ctypes.byref(out))
+    if rc != 0:
+        raise MoeEpError(rc, "moe_ep_dep_layer_models: bad arguments")
+    return out
+
+
+def dep_tokens_per_expert(problem: DepProblem, m_a: int, r_2: int) -> float:
+    return float(load_library().moe_ep_dep_tokens_per_expert(ctypes.byref(problem), m_a, r_2))
+
+
+def dep_replay(models: DepModels, problem: DepProblem, m_a: int, r_1: int, r_2: int, order: int):
+    """moe_ep_dep_replay: (makespan, dict of start-time arrays shaped [T, r_1] / [T, r_1, r_2])."""
+    T = problem.n_layers
+    tau = {"tau_a": np.empty((T, r_1)), "tau_s": np.empty((T, r_1)), "tau_a2e": np.empty((T, r_1, r_2)),
+           "tau_e": np.empty((T, r_1, r_2)), "tau_e2a": np.empty((T, r_1, r_2))}
+    span = ctypes.c_double()
+    dp = ctypes.POINTER(ctypes.c_double)
+    rc = load_library().moe_ep_dep_replay(
+        ctypes.byref(models), ctypes.byref(problem), m_a, r_1, r_2, order, ctypes.byref(span),
+        *(tau[k].ctypes.data_as(dp) for k in ("tau_a", "tau_s", "tau_a2e", "tau_e", "tau_e2a")))
+    if rc != 0:
+        raise MoeEpError(rc, "moe_ep_dep_replay: bad arguments")
+    return span.value, tau
+
+
+def dep_makespan(models: DepModels, problem: DepProblem, m_a: int, r_1: int, r_2: int) -> float:
+    return float(load_library().moe_ep_dep_makespan(ctypes.byref(models), ctypes.byref(problem), m_a, r_1, r_2))
+
+
+def dep_solve_r2(models: DepModels, problem: DepProblem, m_a: int, r_1: int, order: int,
+                 r2_max: int) -> Tuple[int, float]:
+    r2, span = ctypes.c_int32(), ctypes.c_double()
+    rc = load_library().moe_ep_dep_solve_r2(ctypes.byref(models), ctypes.byref(problem), m_a, r_1, order,
+                                            r2_max, ctypes.byref(r2), ctypes.byref(span))
+    if rc != 0:
+        raise MoeEpError(rc, "moe_ep_dep_solve_r2: bad arguments")
+    return r2.value, span.value
+
+
+def dep_search(models: DepModels, problem: DepProblem, m_a_max: int, mem_cap: int, r1_cap: int,
+               r2_max: int) -> Optional[DepConfig]:
+    """moe_ep_dep_search (Algorithm 1); None when no (m_a, r_1) pair fits the memory rule."""
+    best = DepConfig()
+    rc = load_library().moe_ep_dep_search(ctypes.byref(models), ctypes.byref(problem), m_a_max, mem_cap,
+                                          r1_cap, r2_max, ctypes.byref(best))
+    if rc == -4:
+        return None
+    if rc != 0:
+        raise MoeEpError(rc, "moe_ep_dep_search: bad arguments")
+    return best
 
 
 class MoeEp:
