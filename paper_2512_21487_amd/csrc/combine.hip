@@ -23,13 +23,18 @@ __global__ __launch_bounds__(256) void combine_kernel(
     for (int t = gw; t < Tn; t += nw) {
         const int my_pos = (lane < k) ? pos[(size_t)t * k + lane] : -1;
         const float my_w = (lane < k) ? w[(size_t)t * k + lane] : 0.f;
-        for (int c = lane; c < M8; c += 64) {
+        // the column loop runs the same number of times in every lane: the slot broadcasts below
+        // read lanes 0..k-1, which must not have left the loop when a row is shorter than 64 chunks
+        for (int c0 = 0; c0 < M8; c0 += 64) {
+            const int c = c0 + lane;
+            const bool in_row = c < M8;
             float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
             for (int s = 0; s < k; ++s) {
                 const int p = __shfl(my_pos, s, 64);  // uniform over the wavefront
                 const float ws = __shfl(my_w, s, 64);
-                if (p >= 0) fma8(acc, ws, y[(size_t)p * M8 + c]);
+                if (p >= 0 && in_row) fma8(acc, ws, y[(size_t)p * M8 + c]);
             }
+            if (!in_row) continue;
             if (ysh != nullptr) fma8(acc, 1.0f, ysh[(size_t)t * M8 + c]);
             uint4 o;
             o.x = pack_bf16x2(acc[0], acc[1]); o.y = pack_bf16x2(acc[2], acc[3]);

@@ -155,6 +155,39 @@ def test_single_token_and_empty_call():
     ctx.destroy()
 
 
+def test_more_chunks_than_tokens():
+    wl = tiny_workload(name="r_gt_T", n_tokens=5, hidden=64, inter=64, n_experts=8, n_local=8,
+                       top_k=2, n_shared=1, shared_inter=64)
+    _full_parity(wl, seed=27, r=8)
+
+
+def test_maximum_expert_count_and_top_k():
+    """The limits of the boundary: 512 experts, all local, 64 experts per token."""
+    wl = tiny_workload(name="E512k64", n_tokens=96, hidden=64, inter=64, n_experts=512, n_local=512,
+                       top_k=64)
+    _full_parity(wl, seed=28)
+
+
+@pytest.mark.parametrize("variant", [0, 1, 2, 3, 4, 5, 6])
+@pytest.mark.parametrize("hidden", [64, 128, 192])
+def test_every_tile_variant_matches_oracle(variant, hidden):
+    """Each instantiated tile shape / ring depth of the grouped GEMM, for the routed and the shared
+    experts, on K extents of one, two and three 64-wide steps (shortest pipelines) with ragged row
+    and column tails."""
+    wl = tiny_workload(name=f"v{variant}_M{hidden}", n_tokens=333, hidden=hidden, inter=320, n_experts=6,
+                       n_local=6, top_k=2, n_shared=1, shared_inter=192)
+    old = {k: os.environ.get(k) for k in ("MOE_EP_GEMM_VARIANT", "MOE_EP_SHARED_VARIANT")}
+    os.environ["MOE_EP_GEMM_VARIANT"] = os.environ["MOE_EP_SHARED_VARIANT"] = str(variant)
+    try:
+        _full_parity(wl, seed=29)
+    finally:
+        for k, v in old.items():
+            if v is None:
+                os.environ.pop(k, None)
+            else:
+                os.environ[k] = v
+
+
 # ------------------------------------------------------------------ invariants on the GPU
 def test_chunking_and_order_do_not_change_a_bit():
     g = _gpu()
