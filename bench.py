@@ -159,8 +159,11 @@ def main() -> int:
         "routed_down_gemm": gemm_line(2.0 * kept * M * H, stages["routed_down_gemm"]),
         "shared_gate_up_gemm": gemm_line(4.0 * T * Ns * M * Hs, stages["shared_gate_up_gemm"]),
         "shared_down_gemm": gemm_line(2.0 * T * Ns * M * Hs, stages["shared_down_gemm"]),
-        # partition: per kept row 2M bytes read + 2M written, plus the routing arrays
-        "partition": hbm_line(kept * 4.0 * M + T * k * 16.0, stages["partition"]),
+        # partition: the routing arrays (masks, offsets, positions, row map); the token rows are
+        # gathered by the gate/up projection's own tile loads unless MOE_EP_FUSED_GATHER=0, in which
+        # case a grouped copy adds 2M bytes read + 2M written per kept row
+        "partition": hbm_line((kept * 4.0 * M if os.environ.get("MOE_EP_FUSED_GATHER") == "0" else 0.0)
+                              + T * k * 16.0, stages["partition"]),
         # aggregation: per kept row 2M bytes read, per token 2M written (+2M shared read)
         "aggregation": hbm_line(kept * 2.0 * M + T * 2.0 * M * (2 if Ns else 1), stages["aggregation"]),
         "router": hbm_line(T * (4.0 * wl.n_experts + 8.0 * k), stages["router"]),

@@ -143,7 +143,8 @@ __global__ __launch_bounds__(WGM* WGN* KG * 64) void grouped_gemm_kernel(GemmArg
         nrows = __builtin_amdgcn_readfirstlane(nrows);
         const int n0 = __builtin_amdgcn_readfirstlane(ni * BN_OUT);
         const uint16_t* Wg = a.W + (size_t)g * a.w_group_stride;
-        const uint16_t* Xg = a.A + (size_t)row0 * a.lda;
+        const bool mapped = RAGGED && a.a_row_map != nullptr;   // token rows gathered by the tile loads
+        const uint16_t* Xg = mapped ? a.A : a.A + (size_t)row0 * a.lda;
 
         // per region this wavefront loads: the lane's global source (row, swizzled chunk) as a byte
         // offset from the tile's activation rows Xg or the group's weights Wg (one group's matrices
@@ -155,7 +156,8 @@ __global__ __launch_bounds__(WGM* WGN* KG * 64) void grouped_gemm_kernel(GemmArg
             const int r = j * RPR + ld_row;              // row in the stacked [activations; weights] tile
             const int c = ld_p ^ ((r / RP) % CPR);       // logical chunk stored at physical slot ld_p
             if (i < XRPW) {
-                const int rr = min(r, nrows - 1);        // rows past the end re-read the last valid row
+                int rr = min(r, nrows - 1);              // rows past the end re-read the last valid row
+                if (mapped) rr = a.a_row_map[row0 + rr] / a.a_row_div;
                 goff[i] = ((uint32_t)rr * (uint32_t)a.lda + c * 8) * 2u;
             } else {
                 const int jw = r - BM;                   // row of the weight tile
@@ -377,7 +379,8 @@ static hipError_t launch_one(const GemmArgs& a, int n_cu, int max_row_tiles, hip
     if (max_tiles <= 0) return hipSuccess;
     // lanes address with 32-bit byte offsets inside one group's weights and one activation panel
     const long long w_span = ((SWIGLU ? a.w_up_offset : 0) + (long long)a.N * a.ldw) * 2;
-    const long long x_span = (long long)BM * a.lda * 2;
+    const long long x_span = (long long)(a.a_row_map ? a.a_src_rows : BM) * a.lda * 2;
+    if (a.a_row_map && (!RAGGED || a.a_row_div < 1 || a.a_src_rows < 1)) return hipErrorInvalidValue;
     if (w_span >= (1ll << 32) || x_span >= (1ll << 32) || w_span < 0) return hipErrorInvalidValue;
     // workgroups per CU: LDS (160 KB minus the kernel's small static tables) and 8 wavefront slots
     int occ = (156 * 1024) / Cfg::LDS_BYTES;

@@ -46,6 +46,12 @@ struct GemmArgs {
     int kseg_len;              // K is split into segments of this length ...
     long long w_kseg_stride;   // ... whose weight blocks are this many elements apart
     int c_group_col_stride;    // dense mode: group g writes columns starting at g * this
+    // ragged mode, optional: grouped row p is not row p of A but row a_row_map[p] / a_row_div of A
+    // (the partition's row -> assignment map with a_row_div = top_k: the token rows are then
+    // gathered by the tile loads themselves); a_src_rows = rows A holds.  NULL = rows are in place.
+    const int32_t* a_row_map;
+    int a_row_div;
+    int a_src_rows;
 };
 // variant: index into the tile-shape table of grouped_gemm.hip (0 = default)
 hipError_t launch_grouped_gemm(const GemmArgs& a, bool swiglu, int variant, int n_cu,

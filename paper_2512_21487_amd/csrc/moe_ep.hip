@@ -31,6 +31,7 @@ struct moe_ep_ctx {
     int gemm_variant = 1;    // routed experts: 128-row tiles keep the padding of ragged groups small
     int shared_variant = 2;  // shared experts: dense rows, 256-row tiles
     int BM = 128;
+    bool fused_gather = true;  // the gate/up projection gathers the token rows itself (no grouped copy)
     // device workspaces
     void* d_tokens = nullptr; float* d_logits = nullptr; void* d_out = nullptr;  // pinned-host mode staging
     int32_t* idx = nullptr; float* w = nullptr; int32_t* pos = nullptr; int32_t* perm = nullptr;
@@ -212,6 +213,7 @@ int moe_ep_create(const moe_ep_config* cfg, moe_ep_ctx** out_ctx)
     // tile-shape overrides for tuning (indices into the variant table of grouped_gemm.hip)
     if (const char* v = getenv("MOE_EP_GEMM_VARIANT")) ctx->gemm_variant = atoi(v);
     if (const char* v = getenv("MOE_EP_SHARED_VARIANT")) ctx->shared_variant = atoi(v);
+    if (const char* v = getenv("MOE_EP_FUSED_GATHER")) ctx->fused_gather = atoi(v) != 0;
     ctx->BM = grouped_gemm_row_tile(ctx->gemm_variant);
     if (grouped_gemm_init() != hipSuccess) { delete ctx; return MOE_EP_EHIP; }
 
@@ -444,7 +446,8 @@ int moe_ep_forward(moe_ep_ctx* ctx, const void* tokens, const float* gate_logits
         HIP_TRY(ctx, launch_dispatch_scan(ctx->blk_mask, nblk, El, ctx->BM, ctx->blk_off, count, offset, mt_prefix, s_comp));
         if (Tn > 0) {
             HIP_TRY(ctx, launch_dispatch_permute(idx, ctx->blk_mask, ctx->blk_off, offset, Tn, k, e0, El, pos, perm, s_comp));
-            HIP_TRY(ctx, launch_gather_rows(tok_dev + (size_t)t0 * M, perm, offset + El, k, M, ctx->xp, bw_grid, s_comp));
+            if (!ctx->fused_gather)
+                HIP_TRY(ctx, launch_gather_rows(tok_dev + (size_t)t0 * M, perm, offset + El, k, M, ctx->xp, bw_grid, s_comp));
         }
         prof_end(ctx, sp, s_comp);
         if (Tn == 0) {
@@ -461,6 +464,9 @@ int moe_ep_forward(moe_ep_ctx* ctx, const void* tokens, const float* gate_logits
         g1.G = El; g1.dense_rows = 0; g1.K = M; g1.N = H; g1.lda = M; g1.ldc = H; g1.ldw = M;
         g1.w_group_stride = (long long)3 * H * M; g1.w_up_offset = (long long)H * M;
         g1.kseg_len = M; g1.w_kseg_stride = 0; g1.c_group_col_stride = 0;
+        if (ctx->fused_gather) {  // the projection reads the token rows through the row -> assignment map
+            g1.A = tok_dev + (size_t)t0 * M; g1.a_row_map = perm; g1.a_row_div = k; g1.a_src_rows = Tn;
+        }
         sp = prof_begin(ctx, prof, ST_GEMM1, s_comp);
         HIP_TRY(ctx, launch_grouped_gemm(g1, true, ctx->gemm_variant, ctx->n_cu, max_row_tiles, s_comp));
         prof_end(ctx, sp, s_comp);

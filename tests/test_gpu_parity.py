@@ -233,6 +233,22 @@ def test_pinned_host_pipeline_matches_device_mode():
     pctx.destroy()
 
 
+def test_pinned_host_chunks_that_start_off_16_byte_boundaries():
+    """7 experts and 15-token chunks: a chunk's gate scores start 420 bytes into the buffer, so the
+    inbound copy takes its 4-byte path; the result must still match the oracle."""
+    g = _gpu()
+    wl = tiny_workload(name="pinned_odd", n_tokens=75, hidden=64, inter=64, n_experts=7, n_local=7,
+                       top_k=3, n_shared=1, shared_inter=64)
+    inp = make_inputs(wl, seed=31)
+    ref = _oracle_full(inp, wl, 5)
+    pctx = g.make_ctx(wl, pinned=True)
+    pd = g.DeviceInputs(wl, inp, pinned=True)
+    out = g.run_forward(pctx, wl, pd, r=5, order=1)
+    _check_routing(pctx, ref, 5, wl.n_tokens, wl.top_k)
+    assert rel_err(bf16_bits_to_f32(out), ref["out"]) <= TOL
+    pctx.destroy()
+
+
 def test_auto_chunks_from_timing_model():
     """r_chunks = 0 takes r_2 from the context's timing model (Sec. 4.2) and changes no output bit."""
     g = _gpu()
