@@ -135,7 +135,9 @@ def main() -> int:
         stages = ctx.get_stage_ms()
         ctx.set_profiling(0)
 
-    kept = sum(int(ctx.get_routing(c)["offset"][-1]) for c in range(args.r))
+    routing = [ctx.get_routing(c) for c in range(args.r)]
+    kept = sum(int(rt["offset"][-1]) for rt in routing)
+    tokens_with_kept = sum(int((rt["pos"] >= 0).any(axis=1).sum()) for rt in routing)
     ms_per_step = dt / args.steps * 1e3
     value = T * args.steps / dt
 
@@ -164,8 +166,10 @@ def main() -> int:
         # case a grouped copy adds 2M bytes read + 2M written per kept row
         "partition": hbm_line((kept * 4.0 * M if os.environ.get("MOE_EP_FUSED_GATHER") == "0" else 0.0)
                               + T * k * 16.0, stages["partition"]),
-        # aggregation: per kept row 2M bytes read, per token 2M written (+2M shared read)
-        "aggregation": hbm_line(kept * 2.0 * M + T * 2.0 * M * (2 if Ns else 1), stages["aggregation"]),
+        # aggregation: per kept row 2M bytes read; without shared experts every output row is written
+        # (2M), with them only the rows of tokens that kept a slot are read and rewritten (4M)
+        "aggregation": hbm_line(kept * 2.0 * M + (tokens_with_kept * 4.0 * M if Ns else T * 2.0 * M),
+                                stages["aggregation"]),
         "router": hbm_line(T * (4.0 * wl.n_experts + 8.0 * k), stages["router"]),
     }
     routed_ms = stages["routed_gate_up_gemm"] + stages["routed_down_gemm"]

@@ -108,7 +108,7 @@ int moe_ep_create(const moe_ep_config *cfg, moe_ep_ctx **out_ctx);
  *               n_shared == 0).
  *   out         bf16 [n_tokens, M]: sum over kept slots of weight * expert(token) plus the
  *               sum of the shared experts; tokens with nothing kept and no shared expert
- *               get zeros.  Accumulation is fp32; the activation between the up and down
+ *               get zeros.  Must not overlap tokens or gate_logits.  Accumulation is fp32; the activation between the up and down
  *               projections and each expert's output are rounded to bf16 once.
  *   stream      hipStream_t (NULL = the default stream).  The call only enqueues work:
  *               it starts after everything already on `stream` and `stream` is made to

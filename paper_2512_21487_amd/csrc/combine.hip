@@ -1,5 +1,5 @@
-// Weighted aggregation of the selected experts' outputs, plus the shared experts' output
-// (Sec. 2.1).  Token-major gather-reduce: a wavefront owns an output row, walks the row's
+// Weighted aggregation of the selected experts' outputs (Sec. 2.1), added to the shared experts'
+// output that the shared down projection has already written into the output rows.  Token-major gather-reduce: a wavefront owns an output row, walks the row's
 // kept slots in slot order, and accumulates in fp32; every load and store is 16 bytes per
 // lane and contiguous over the wavefront.  No atomics, so the result is deterministic.
 #include "common.h"
@@ -15,14 +15,17 @@ __device__ __forceinline__ void fma8(float* acc, float ws, const uint4& v) {
 }
 
 __global__ __launch_bounds__(256) void combine_kernel(
-    const uint4* __restrict__ y, const uint4* __restrict__ ysh, const int32_t* __restrict__ pos,
-    const float* __restrict__ w, int Tn, int k, int M8, uint4* __restrict__ out)
+    const uint4* __restrict__ y, const int32_t* __restrict__ pos, const float* __restrict__ w, int Tn,
+    int k, int M8, bool accumulate, uint4* out)
 {
     const int lane = threadIdx.x & 63;
     const int gw = (blockIdx.x * 256 + threadIdx.x) >> 6, nw = gridDim.x * 4;
     for (int t = gw; t < Tn; t += nw) {
         const int my_pos = (lane < k) ? pos[(size_t)t * k + lane] : -1;
         const float my_w = (lane < k) ? w[(size_t)t * k + lane] : 0.f;
+        // accumulate: the row already holds the shared experts' output; a token with no kept
+        // slot keeps it as it is
+        if (accumulate && __ballot(my_pos >= 0) == 0ull) continue;
         // the column loop runs the same number of times in every lane: the slot broadcasts below
         // read lanes 0..k-1, which must not have left the loop when a row is shorter than 64 chunks
         for (int c0 = 0; c0 < M8; c0 += 64) {
@@ -35,7 +38,7 @@ __global__ __launch_bounds__(256) void combine_kernel(
                 if (p >= 0 && in_row) fma8(acc, ws, y[(size_t)p * M8 + c]);
             }
             if (!in_row) continue;
-            if (ysh != nullptr) fma8(acc, 1.0f, ysh[(size_t)t * M8 + c]);
+            if (accumulate) fma8(acc, 1.0f, out[(size_t)t * M8 + c]);
             uint4 o;
             o.x = pack_bf16x2(acc[0], acc[1]); o.y = pack_bf16x2(acc[2], acc[3]);
             o.z = pack_bf16x2(acc[4], acc[5]); o.w = pack_bf16x2(acc[6], acc[7]);
@@ -44,13 +47,12 @@ __global__ __launch_bounds__(256) void combine_kernel(
     }
 }
 
-hipError_t launch_combine(const void* y, const void* ysh, const int32_t* pos, const float* w, int Tn,
-                          int k, int M, void* out, int grid, hipStream_t s)
+hipError_t launch_combine(const void* y, const int32_t* pos, const float* w, int Tn, int k, int M,
+                          bool accumulate, void* out, int grid, hipStream_t s)
 {
     if (Tn <= 0) return hipSuccess;
-    hipLaunchKernelGGL(combine_kernel, dim3(grid), dim3(256), 0, s, static_cast<const uint4*>(y),
-                       static_cast<const uint4*>(ysh), pos, w, Tn, k, M / 8,
-                       static_cast<uint4*>(out));
+    hipLaunchKernelGGL(combine_kernel, dim3(grid), dim3(256), 0, s, static_cast<const uint4*>(y), pos, w, Tn, k,
+                       M / 8, accumulate, static_cast<uint4*>(out));
     return hipGetLastError();
 }
 

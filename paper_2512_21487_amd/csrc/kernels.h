@@ -23,8 +23,8 @@ hipError_t launch_gather_rows(const void* tokens, const int32_t* perm, const int
                               int k, int M, void* xp, int grid, hipStream_t s);
 
 // ---- weighted aggregation (Sec. 2.1)
-hipError_t launch_combine(const void* y, const void* ysh, const int32_t* pos, const float* w, int Tn,
-                          int k, int M, void* out, int grid, hipStream_t s);
+hipError_t launch_combine(const void* y, const int32_t* pos, const float* w, int Tn, int k, int M,
+                          bool accumulate, void* out, int grid, hipStream_t s);
 
 // ---- chunk transfers over the host link (pinned-host mode); bytes must be a multiple of 4
 hipError_t launch_copy(void* dst, const void* src, size_t bytes, int grid, hipStream_t s);

@@ -38,7 +38,7 @@ struct moe_ep_ctx {
     unsigned long long* blk_mask = nullptr; int32_t* blk_off = nullptr;
     int32_t* count = nullptr; int32_t* offset = nullptr; int32_t* mt_prefix = nullptr;
     uint16_t* xp = nullptr; uint16_t* h = nullptr; uint16_t* y = nullptr;
-    uint16_t* hs = nullptr; uint16_t* ysh = nullptr;
+    uint16_t* hs = nullptr;
     // streams and events
     hipStream_t s_in = nullptr, s_comp = nullptr, s_out = nullptr;
     hipEvent_t ev_start = nullptr, ev_done = nullptr, ev_comp_done = nullptr;
@@ -62,7 +62,7 @@ const char* set_why(const char** why, const char* msg) { if (why) *why = msg; re
 size_t align256(size_t b) { return (b + 255) & ~(size_t)255; }
 
 struct WsLayout {
-    size_t tokens, logits, out, idx, w, pos, perm, blk_mask, blk_off, count, offset, mt_prefix, xp, h, y, hs, ysh, total;
+    size_t tokens, logits, out, idx, w, pos, perm, blk_mask, blk_off, count, offset, mt_prefix, xp, h, y, hs, total;
 };
 
 WsLayout ws_layout(const moe_ep_config& c)
@@ -82,7 +82,6 @@ WsLayout ws_layout(const moe_ep_config& c)
     L.count = take(R * El * 4); L.offset = take(R * (El + 1) * 4); L.mt_prefix = take(R * (El + 1) * 4);
     L.xp = take(A * M * 2); L.h = take(A * H * 2); L.y = take(A * M * 2);
     L.hs = take(c.n_shared > 0 ? T * (size_t)c.n_shared * (size_t)c.shared_inter * 2 : 0);
-    L.ysh = take(c.n_shared > 0 ? T * M * 2 : 0);
     L.total = o;
     return L;
 }
@@ -236,7 +235,6 @@ int moe_ep_create(const moe_ep_config* cfg, moe_ep_ctx** out_ctx)
     ctx->h = reinterpret_cast<uint16_t*>(slab + L.h);
     ctx->y = reinterpret_cast<uint16_t*>(slab + L.y);
     ctx->hs = reinterpret_cast<uint16_t*>(slab + L.hs);
-    ctx->ysh = reinterpret_cast<uint16_t*>(slab + L.ysh);
 
     // the chunk events order GPU work against GPU work only, so they skip the system-scope cache
     // write-back a default event record implies (it stalled the other streams' kernels)
@@ -378,7 +376,7 @@ int moe_ep_forward(moe_ep_ctx* ctx, const void* tokens, const float* gate_logits
     const int Tc = (T + r - 1) / r;
     const int bw_grid = ctx->n_cu * 8;  // bandwidth kernels: 8 workgroups of 4 wavefronts per CU
 
-    // shared experts of token range [t0, t0+Tn) -> ysh rows [t0, t0+Tn)
+    // shared experts of token range [t0, t0+Tn) -> output rows [t0, t0+Tn); the aggregation adds to them
     auto run_shared = [&](int t0, int Tn) -> int {
         GemmArgs g1{};
         g1.A = tok_dev + (size_t)t0 * M; g1.W = sw; g1.C = ctx->hs + (size_t)t0 * Ns * Hs;
@@ -392,7 +390,7 @@ int moe_ep_forward(moe_ep_ctx* ctx, const void* tokens, const float* gate_logits
         HIP_TRY(ctx, launch_grouped_gemm(g1, true, ctx->shared_variant, ctx->n_cu, mt * Ns, s_comp));
         prof_end(ctx, sp, s_comp);
         GemmArgs g2{};
-        g2.A = ctx->hs + (size_t)t0 * Ns * Hs; g2.W = sw + (size_t)2 * Hs * M; g2.C = ctx->ysh + (size_t)t0 * M;
+        g2.A = ctx->hs + (size_t)t0 * Ns * Hs; g2.W = sw + (size_t)2 * Hs * M; g2.C = out_dev + (size_t)t0 * M;
         g2.offset = nullptr; g2.mt_prefix = nullptr; g2.G = 1; g2.dense_rows = Tn;
         g2.K = Ns * Hs; g2.N = M; g2.lda = Ns * Hs; g2.ldc = M; g2.ldw = Hs;
         g2.w_group_stride = 0; g2.w_up_offset = 0;
@@ -486,8 +484,7 @@ int moe_ep_forward(moe_ep_ctx* ctx, const void* tokens, const float* gate_logits
         }
 
         sp = prof_begin(ctx, prof, ST_COMBINE, s_comp);
-        HIP_TRY(ctx, launch_combine(ctx->y, Ns > 0 ? ctx->ysh + (size_t)t0 * M : nullptr, pos, w, Tn, k, M,
-                                    out_dev + (size_t)t0 * M, bw_grid, s_comp));
+        HIP_TRY(ctx, launch_combine(ctx->y, pos, w, Tn, k, M, Ns > 0, out_dev + (size_t)t0 * M, bw_grid, s_comp));
         prof_end(ctx, sp, s_comp);
 
         if (pinned) {
