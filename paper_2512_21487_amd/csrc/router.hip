@@ -1,7 +1,8 @@
 // Gate: per token, the top-k of E routing scores and their renormalised softmax weights
-// (Sec. 2.1).  One 64-lane wavefront owns a token at a time (four tokens in turn, their scores
-// all requested up front): lane l holds scores l, l+64, ... in registers, each of the k rounds
-// is a lane-local scan plus a 6-step butterfly arg-max.
+// (Sec. 2.1).  A token is owned by one 16-lane row of a wavefront, so a wavefront advances four
+// tokens at once: lane l of the row holds scores l, l+16, ... in registers, and each of the k
+// selection rounds is a lane-local scan plus a four-step arg-max over the row done with DPP
+// lane exchanges (quad swaps and row mirrors: register moves, no LDS traffic).
 // The same workgroup (64 tokens) also records, per local expert, a 64-bit mask of the
 // tokens that selected it; the partition kernels derive counts and stable ranks from it,
 // so no atomically allocated slot ever decides an order.
@@ -10,90 +11,79 @@
 
 namespace moe_ep {
 
-constexpr int kMaxEpl = 8;  // scores per lane: E <= 512
+constexpr int kRouterThreads = 1024;  // 16 wavefronts x 4 rows = the 64 tokens of a workgroup
 
-constexpr int kRouterThreads = 1024;                                   // 16 wavefronts per 64-token workgroup
-constexpr int kTokPerWave = kTokPerBlock / (kRouterThreads / 64);      // 4 tokens per wavefront
+// the value lane (lane ^ pattern) of the same 16-lane row holds; ctrl is a DPP control:
+// 0xB1 / 0x4E swap neighbours / pairs inside a quad, 0x141 / 0x140 mirror a half row / a row
+template <int CTRL>
+__device__ __forceinline__ int row_exchange(int x) { return __builtin_amdgcn_update_dpp(x, x, CTRL, 0xF, 0xF, false); }
 
+// larger score first, equal scores keep the lower expert index
+__device__ __forceinline__ void keep_better(float& bv, int& bi, float ov, int oi)
+{
+    if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+}
+
+template <int CTRL>
+__device__ __forceinline__ void row_argmax_step(float& bv, int& bi)
+{
+    const float ov = __builtin_bit_cast(float, row_exchange<CTRL>(__builtin_bit_cast(int, bv)));
+    const int oi = row_exchange<CTRL>(bi);
+    keep_better(bv, bi, ov, oi);
+}
+
+template <int EPL>  // scores per lane: E <= 16 * EPL
 __global__ __launch_bounds__(kRouterThreads) void router_topk_kernel(
     const float* __restrict__ logits, int Tn, int E, int k, int e0, int El,
     int32_t* __restrict__ idx, float* __restrict__ w, unsigned long long* __restrict__ blk_mask)
 {
-    extern __shared__ unsigned long long smask[];
+    extern __shared__ unsigned long long smask[];                  // [El] token masks of the local experts
+    int* s_idx = reinterpret_cast<int*>(smask + El);               // [64][k] selected experts
+    float* s_ex = reinterpret_cast<float*>(s_idx + kTokPerBlock * k);  // [64][k] exp(score - best score)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int sub = lane & 15, tl = wave * 4 + (lane >> 4);        // lane inside the row; token inside the block
     for (int i = tid; i < El; i += kRouterThreads) smask[i] = 0ull;
     __syncthreads();
 
-    const int epl = (E + 63) >> 6;
-    // all of this wavefront's scores are requested before the first one is used
-    float v[kTokPerWave][kMaxEpl];
+    const int t = blockIdx.x * kTokPerBlock + tl;
+    const bool live = t < Tn;
+    const float* row = logits + (size_t)min(t, Tn - 1) * E;
+    float v[EPL];
+    unsigned taken = 0;  // bit i: score i of this lane is out of range or already selected
 #pragma unroll
-    for (int j = 0; j < kTokPerWave; ++j) {
-        const int t = blockIdx.x * kTokPerBlock + wave * kTokPerWave + j;
-        const float* row = logits + (size_t)min(t, Tn - 1) * E;
-#pragma unroll
-        for (int i = 0; i < kMaxEpl; ++i) {
-            const int e = lane + 64 * i;
-            v[j][i] = (i < epl && e < E) ? row[e] : 0.f;
-        }
+    for (int i = 0; i < EPL; ++i) {
+        const int e = sub + 16 * i;
+        if (e < E) v[i] = row[e]; else { v[i] = 0.f; taken |= 1u << i; }
     }
-    // the four tokens advance through the k selection rounds together: their arg-max chains are
-    // independent, so the cross-lane exchanges of one token hide behind those of the others
-    unsigned taken[kTokPerWave];
-    int my_idx[kTokPerWave];
-    float my_val[kTokPerWave];
-#pragma unroll
-    for (int j = 0; j < kTokPerWave; ++j) {
-        taken[j] = 0; my_idx[j] = 0; my_val[j] = 0.f;
-#pragma unroll
-        for (int i = 0; i < kMaxEpl; ++i)
-            if (!(i < epl && lane + 64 * i < E)) taken[j] |= 1u << i;
-    }
+    float v0 = 0.f, sum = 0.f;
     for (int s = 0; s < k; ++s) {
-        float bv[kTokPerWave];
-        int bi[kTokPerWave];
+        float bv = -INFINITY;
+        int bi = INT_MAX;
 #pragma unroll
-        for (int j = 0; j < kTokPerWave; ++j) {
-            // lane-local best: larger score first, equal scores keep the lower index
-            bv[j] = -INFINITY; bi[j] = INT_MAX;
-#pragma unroll
-            for (int i = 0; i < kMaxEpl; ++i)
-                if (!((taken[j] >> i) & 1u) && (bi[j] == INT_MAX || v[j][i] > bv[j])) { bv[j] = v[j][i]; bi[j] = lane + 64 * i; }
-        }
-#pragma unroll
-        for (int d = 32; d >= 1; d >>= 1) {
-#pragma unroll
-            for (int j = 0; j < kTokPerWave; ++j) {
-                const float ov = __shfl_xor(bv[j], d, 64);
-                const int oi = __shfl_xor(bi[j], d, 64);
-                if (ov > bv[j] || (ov == bv[j] && oi < bi[j])) { bv[j] = ov; bi[j] = oi; }
-            }
-        }
-#pragma unroll
-        for (int j = 0; j < kTokPerWave; ++j) {
-            if ((bi[j] & 63) == lane) taken[j] |= 1u << (bi[j] >> 6);
-            if (lane == s) { my_idx[j] = bi[j]; my_val[j] = bv[j]; }
-        }
-    }
-#pragma unroll
-    for (int j = 0; j < kTokPerWave; ++j) {
-        const int tl = wave * kTokPerWave + j;
-        const int t = blockIdx.x * kTokPerBlock + tl;
-        if (t >= Tn) break;  // uniform over the wavefront
+        for (int i = 0; i < EPL; ++i)  // ascending index inside a lane: a strict > keeps the lower one
+            if (!((taken >> i) & 1u) && (bi == INT_MAX || v[i] > bv)) { bv = v[i]; bi = sub + 16 * i; }
+        row_argmax_step<0xB1>(bv, bi);
+        row_argmax_step<0x4E>(bv, bi);
+        row_argmax_step<0x141>(bv, bi);
+        row_argmax_step<0x140>(bv, bi);   // every lane of the row now holds the round's winner
+        if ((bi & 15) == sub) taken |= 1u << (bi >> 4);
+        if (s == 0) v0 = bv;
         // softmax restricted to the selection = full softmax renormalised over it
-        const float v0 = __shfl(my_val[j], 0, 64);
-        const float ex = (lane < k) ? expf(my_val[j] - v0) : 0.f;
-        float sum = ex;
-#pragma unroll
-        for (int d = 32; d >= 1; d >>= 1) sum += __shfl_xor(sum, d, 64);
-        if (lane < k) {
-            idx[(size_t)t * k + lane] = my_idx[j];
-            w[(size_t)t * k + lane] = ex / sum;
-            const int el = my_idx[j] - e0;
+        const float ex = expf(bv - v0);
+        sum += ex;
+        if (sub == 0 && live) {
+            s_idx[tl * k + s] = bi;
+            s_ex[tl * k + s] = ex;
+            const int el = bi - e0;
             if (el >= 0 && el < El) atomicOr(&smask[el], 1ull << tl);
         }
     }
     __syncthreads();
+    if (live)
+        for (int s = sub; s < k; s += 16) {
+            idx[(size_t)t * k + s] = s_idx[tl * k + s];
+            w[(size_t)t * k + s] = s_ex[tl * k + s] / sum;
+        }
     unsigned long long* dst = blk_mask + (size_t)blockIdx.x * El;
     for (int i = tid; i < El; i += kRouterThreads) dst[i] = smask[i];
 }
@@ -102,9 +92,20 @@ hipError_t launch_router(const float* logits, int Tn, int E, int k, int e0, int 
                          float* w, unsigned long long* blk_mask, hipStream_t s)
 {
     if (Tn <= 0) return hipSuccess;
+    if (E < 1 || E > 512 || k < 1 || k > 64) return hipErrorInvalidValue;
     const int nblk = (Tn + kTokPerBlock - 1) / kTokPerBlock;
-    hipLaunchKernelGGL(router_topk_kernel, dim3(nblk), dim3(kRouterThreads), El * sizeof(unsigned long long), s,
-                       logits, Tn, E, k, e0, El, idx, w, blk_mask);
+    const size_t lds = El * sizeof(unsigned long long) + (size_t)kTokPerBlock * k * 8;
+#define MOE_EP_ROUTER(EPL)                                                                          \
+    hipLaunchKernelGGL(router_topk_kernel<EPL>, dim3(nblk), dim3(kRouterThreads), lds, s, logits, Tn, E, k, e0, \
+                       El, idx, w, blk_mask)
+    if (E <= 16) MOE_EP_ROUTER(1);
+    else if (E <= 32) MOE_EP_ROUTER(2);
+    else if (E <= 64) MOE_EP_ROUTER(4);
+    else if (E <= 128) MOE_EP_ROUTER(8);
+    else if (E <= 160) MOE_EP_ROUTER(10);
+    else if (E <= 256) MOE_EP_ROUTER(16);
+    else MOE_EP_ROUTER(32);
+#undef MOE_EP_ROUTER
     return hipGetLastError();
 }
 
