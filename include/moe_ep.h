@@ -154,6 +154,10 @@ int moe_ep_get_routing(moe_ep_ctx *ctx, int32_t chunk, int32_t *idx, float *w, i
  * Returns MOE_EP_ESTATE when nothing was recorded.
  */
 int moe_ep_set_profiling(moe_ep_ctx *ctx, int32_t depth);
+/* Restricts the events to the stages whose bit (1 << index into ms[]) is set in `mask`; the default
+ * is every stage.  Events between all stages cost a few percent of a forward (more for small
+ * calls); timing only one stage leaves the rest of the forward undisturbed. */
+int moe_ep_set_profiling_stages(moe_ep_ctx *ctx, uint32_t mask);
 int moe_ep_get_stage_ms(moe_ep_ctx *ctx, float *ms, int32_t n);
 
 /*

@@ -102,6 +102,8 @@ def load_library() -> ctypes.CDLL:
     lib.moe_ep_get_routing.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp]
     lib.moe_ep_set_profiling.restype = ctypes.c_int
     lib.moe_ep_set_profiling.argtypes = [vp, i32]
+    lib.moe_ep_set_profiling_stages.restype = ctypes.c_int
+    lib.moe_ep_set_profiling_stages.argtypes = [vp, ctypes.c_uint32]
     lib.moe_ep_get_stage_ms.restype = ctypes.c_int
     lib.moe_ep_get_stage_ms.argtypes = [vp, vp, i32]
     dp = ctypes.POINTER(ctypes.c_double)
@@ -315,6 +317,13 @@ class MoeEp:
     # -- profiling ------------------------------------------------------------------------
     def set_profiling(self, depth: int) -> None:
         rc = self._lib.moe_ep_set_profiling(self._ctx, depth)
+        if rc != 0:
+            raise MoeEpError(rc, self.last_error())
+
+    def set_profiling_stages(self, names=None) -> None:
+        """Time only the named stages (entries of STAGES); None = every stage."""
+        mask = 0xFFFFFFFF if names is None else sum(1 << STAGES.index(n) for n in names)
+        rc = self._lib.moe_ep_set_profiling_stages(self._ctx, mask)
         if rc != 0:
             raise MoeEpError(rc, self.last_error())
 

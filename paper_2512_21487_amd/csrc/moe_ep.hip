@@ -47,6 +47,7 @@ struct moe_ep_ctx {
     int last_T = -1, last_k = 0, last_r = 0;
     // stage profiling
     int prof_depth = 0, prof_recorded = 0;
+    uint32_t prof_mask = ~0u;
     std::vector<hipEvent_t> prof_pool; size_t prof_next = 0;
     std::vector<ProfSpan> prof_spans;
     // timing model for r_chunks == 0
@@ -110,7 +111,7 @@ hipEvent_t prof_event(moe_ep_ctx* ctx)
 // Marks the start of a timed stage on stream s; returns the span index or -1.
 int prof_begin(moe_ep_ctx* ctx, bool on, int stage, hipStream_t s)
 {
-    if (!on) return -1;
+    if (!on || !((ctx->prof_mask >> stage) & 1u)) return -1;
     hipEvent_t a = prof_event(ctx), b = prof_event(ctx);
     if (!a || !b) return -1;
     if (hipEventRecord(a, s) != hipSuccess) return -1;
@@ -286,6 +287,13 @@ int moe_ep_set_profiling(moe_ep_ctx* ctx, int32_t depth)
     ctx->prof_recorded = 0;
     ctx->prof_next = 0;
     ctx->prof_spans.clear();
+    return MOE_EP_OK;
+}
+
+int moe_ep_set_profiling_stages(moe_ep_ctx* ctx, uint32_t mask)
+{
+    if (!ctx) return MOE_EP_EINVAL;
+    ctx->prof_mask = mask;
     return MOE_EP_OK;
 }
 
