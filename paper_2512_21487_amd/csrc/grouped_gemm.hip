@@ -54,8 +54,6 @@ struct GemmCfg {
     static_assert(STAGES >= 2 && STAGES <= 5 && (STAGES - 2) * RPW <= 63, "ring depth and vmcnt budget");
     static_assert(KG == 1 || (KG == 2 && MB % 2 == 0 && KKW >= 1), "K split over two wavefront groups");
     static_assert(KKW % 2 == 0, "a K step starts and ends on fragment set 0 / 1");
-    static_assert(RPW <= (KKW - 1) * MB * NB, "a K step's loads are issued before it hands over the next ring slot");
-    static_assert(MB + NB <= MB * NB, "one fragment read per MFMA slot");
     static_assert(KG == 1 || LDS_BYTES >= NW * (MB / 2) * NB * 1024, "partial sums are exchanged through the ring's LDS");
 };
 
@@ -242,12 +240,12 @@ __global__ __launch_bounds__(WGM* WGN* KG * 64) void grouped_gemm_kernel(GemmArg
                 _Pragma("unroll") for (int q = 0; q < MB * NB; ++q) {                             \
                     const int nb = q / MB, mb = q % MB;                                           \
                     acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[i & 1][nb], xf[i & 1][mb], acc[mb][nb], 0, 0, 0); \
-                    if (q < MB + NB) {                                                            \
-                        if (i + 1 < KKW) MOE_EP_FRAG1(sT, kg * KKW + i + 1, (i + 1) & 1, MOE_EP_FRAG_ORDER(q)) \
-                        else if (has_next_) MOE_EP_FRAG1(sN, kg * KKW, 0, MOE_EP_FRAG_ORDER(q))   \
+                    _Pragma("unroll") for (int f = q; f < MB + NB; f += MB * NB) {                \
+                        if (i + 1 < KKW) MOE_EP_FRAG1(sT, kg * KKW + i + 1, (i + 1) & 1, MOE_EP_FRAG_ORDER(f)) \
+                        else if (has_next_) MOE_EP_FRAG1(sN, kg * KKW, 0, MOE_EP_FRAG_ORDER(f))   \
                     }                                                                             \
-                    if (issue_) {                                                                 \
-                        _Pragma("unroll") for (int l = i * MB * NB + q; l < RPW; l += KKW * MB * NB) \
+                    if ((issue_) && i + 1 < KKW) {  /* all loads go out before the hand-over */   \
+                        _Pragma("unroll") for (int l = i * MB * NB + q; l < RPW; l += (KKW - 1) * MB * NB) \
                             MOE_EP_ISSUE1((kt_) + STAGES - 1, st2, l)                             \
                     }                                                                             \
                     SB();                                                                         \
@@ -420,6 +418,8 @@ static hipError_t launch_cfg(const GemmArgs& a, bool swiglu, int n_cu, int max_r
 }
 
 // tile variants: id, BM, BN, BK, ring stages, wavefronts in m, in n, K-split groups
+// (7: short row tiles; with exactly 16 rows per expert it streams the weights 13 % faster than the
+// 128-row tiles, with the ragged counts of real routing it does not, so nothing selects it by default)
 #define MOE_EP_VARIANTS(X)         \
     X(0, 128, 256, 64, 3, 1, 2, 2) \
     X(1, 128, 256, 64, 3, 2, 2, 1) \
@@ -427,7 +427,8 @@ static hipError_t launch_cfg(const GemmArgs& a, bool swiglu, int n_cu, int max_r
     X(3, 256, 256, 32, 4, 2, 2, 1) \
     X(4, 128, 128, 64, 2, 2, 2, 1) \
     X(5, 128, 256, 32, 3, 2, 2, 1) \
-    X(6, 128, 256, 32, 2, 2, 2, 1)
+    X(6, 128, 256, 32, 2, 2, 2, 1) \
+    X(7, 64, 128, 64, 3, 1, 2, 1)
 
 hipError_t grouped_gemm_init()
 {

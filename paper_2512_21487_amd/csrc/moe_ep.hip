@@ -30,7 +30,6 @@ struct moe_ep_ctx {
     int n_cu = 0;
     int gemm_variant = 1;    // routed experts: 128-row tiles keep the padding of ragged groups small
     int shared_variant = 2;  // shared experts: dense rows, 256-row tiles
-    int BM = 128;
     bool fused_gather = true;  // the gate/up projection gathers the token rows itself (no grouped copy)
     // device workspaces
     void* d_tokens = nullptr; float* d_logits = nullptr; void* d_out = nullptr;  // pinned-host mode staging
@@ -214,7 +213,6 @@ int moe_ep_create(const moe_ep_config* cfg, moe_ep_ctx** out_ctx)
     if (const char* v = getenv("MOE_EP_GEMM_VARIANT")) ctx->gemm_variant = atoi(v);
     if (const char* v = getenv("MOE_EP_SHARED_VARIANT")) ctx->shared_variant = atoi(v);
     if (const char* v = getenv("MOE_EP_FUSED_GATHER")) ctx->fused_gather = atoi(v) != 0;
-    ctx->BM = grouped_gemm_row_tile(ctx->gemm_variant);
     if (grouped_gemm_init() != hipSuccess) { delete ctx; return MOE_EP_EHIP; }
 
     const WsLayout L = ws_layout(*cfg);
@@ -439,6 +437,8 @@ int moe_ep_forward(moe_ep_ctx* ctx, const void* tokens, const float* gate_logits
         int32_t* mt_prefix = ctx->mt_prefix + (size_t)cidx * (El + 1);
         if (pinned) HIP_TRY(ctx, hipStreamWaitEvent(s_comp, ctx->ev_in[cidx], 0));
         const int nblk = (Tn + kTokPerBlock - 1) / kTokPerBlock;
+        const int variant = ctx->gemm_variant;
+        const int BMv = grouped_gemm_row_tile(variant);
         int32_t* idx = ctx->idx + (size_t)t0 * k;
         float* w = ctx->w + (size_t)t0 * k;
         int32_t* pos = ctx->pos + (size_t)t0 * k;
@@ -449,7 +449,7 @@ int moe_ep_forward(moe_ep_ctx* ctx, const void* tokens, const float* gate_logits
         prof_end(ctx, sp, s_comp);
 
         sp = prof_begin(ctx, prof, ST_PARTITION, s_comp);
-        HIP_TRY(ctx, launch_dispatch_scan(ctx->blk_mask, nblk, El, ctx->BM, ctx->blk_off, count, offset, mt_prefix, s_comp));
+        HIP_TRY(ctx, launch_dispatch_scan(ctx->blk_mask, nblk, El, BMv, ctx->blk_off, count, offset, mt_prefix, s_comp));
         if (Tn > 0) {
             HIP_TRY(ctx, launch_dispatch_permute(idx, ctx->blk_mask, ctx->blk_off, offset, Tn, k, e0, El, pos, perm, s_comp));
             if (!ctx->fused_gather)
@@ -463,7 +463,7 @@ int moe_ep_forward(moe_ep_ctx* ctx, const void* tokens, const float* gate_logits
 
         // an upper bound of the row tiles the device-side prefix sums can describe
         const long long a_max = (long long)Tn * k;
-        const int max_row_tiles = (int)((a_max + ctx->BM - 1) / ctx->BM) + El;
+        const int max_row_tiles = (int)((a_max + BMv - 1) / BMv) + El;
 
         GemmArgs g1{};
         g1.A = ctx->xp; g1.W = rw; g1.C = ctx->h; g1.offset = offset; g1.mt_prefix = mt_prefix;
@@ -474,7 +474,7 @@ int moe_ep_forward(moe_ep_ctx* ctx, const void* tokens, const float* gate_logits
             g1.A = tok_dev + (size_t)t0 * M; g1.a_row_map = perm; g1.a_row_div = k; g1.a_src_rows = Tn;
         }
         sp = prof_begin(ctx, prof, ST_GEMM1, s_comp);
-        HIP_TRY(ctx, launch_grouped_gemm(g1, true, ctx->gemm_variant, ctx->n_cu, max_row_tiles, s_comp));
+        HIP_TRY(ctx, launch_grouped_gemm(g1, true, variant, ctx->n_cu, max_row_tiles, s_comp));
         prof_end(ctx, sp, s_comp);
 
         GemmArgs g2{};
@@ -483,7 +483,7 @@ int moe_ep_forward(moe_ep_ctx* ctx, const void* tokens, const float* gate_logits
         g2.w_group_stride = (long long)3 * H * M; g2.w_up_offset = 0;
         g2.kseg_len = H; g2.w_kseg_stride = 0; g2.c_group_col_stride = 0;
         sp = prof_begin(ctx, prof, ST_GEMM2, s_comp);
-        HIP_TRY(ctx, launch_grouped_gemm(g2, false, ctx->gemm_variant, ctx->n_cu, max_row_tiles, s_comp));
+        HIP_TRY(ctx, launch_grouped_gemm(g2, false, variant, ctx->n_cu, max_row_tiles, s_comp));
         prof_end(ctx, sp, s_comp);
 
         if (Ns > 0 && order == MOE_EP_ORDER_INTERLEAVED) {

@@ -168,7 +168,7 @@ def test_maximum_expert_count_and_top_k():
     _full_parity(wl, seed=28)
 
 
-@pytest.mark.parametrize("variant", [0, 1, 2, 3, 4, 5, 6])
+@pytest.mark.parametrize("variant", [0, 1, 2, 3, 4, 5, 6, 7])
 @pytest.mark.parametrize("hidden", [64, 128, 192])
 def test_every_tile_variant_matches_oracle(variant, hidden):
     """Each instantiated tile shape / ring depth of the grouped GEMM, for the routed and the shared
