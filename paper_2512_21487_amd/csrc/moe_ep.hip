@@ -39,7 +39,7 @@ struct moe_ep_ctx {
     uint16_t* xp = nullptr; uint16_t* h = nullptr; uint16_t* y = nullptr;
     uint16_t* hs = nullptr;
     // streams and events
-    hipStream_t s_in = nullptr, s_comp = nullptr, s_out = nullptr;
+    hipStream_t s_in = nullptr, s_out = nullptr;  // the two link directions (pinned-host mode)
     hipEvent_t ev_start = nullptr, ev_done = nullptr, ev_comp_done = nullptr;
     std::vector<hipEvent_t> ev_in, ev_comp;
     // last forward (for moe_ep_get_routing)
@@ -179,9 +179,7 @@ int moe_ep_destroy(moe_ep_ctx* ctx)
 {
     if (!ctx) return MOE_EP_OK;
     (void)hipSetDevice(ctx->cfg.device);
-    if (ctx->s_in) (void)hipStreamSynchronize(ctx->s_in);
-    if (ctx->s_comp) (void)hipStreamSynchronize(ctx->s_comp);
-    if (ctx->s_out) (void)hipStreamSynchronize(ctx->s_out);
+    (void)hipDeviceSynchronize();  // forwards still in flight on the caller's streams use the workspaces
     for (hipEvent_t e : ctx->ev_in) (void)hipEventDestroy(e);
     for (hipEvent_t e : ctx->ev_comp) (void)hipEventDestroy(e);
     for (hipEvent_t e : ctx->prof_pool) (void)hipEventDestroy(e);
@@ -189,7 +187,6 @@ int moe_ep_destroy(moe_ep_ctx* ctx)
     if (ctx->ev_done) (void)hipEventDestroy(ctx->ev_done);
     if (ctx->ev_comp_done) (void)hipEventDestroy(ctx->ev_comp_done);
     if (ctx->s_in) (void)hipStreamDestroy(ctx->s_in);
-    if (ctx->s_comp) (void)hipStreamDestroy(ctx->s_comp);
     if (ctx->s_out) (void)hipStreamDestroy(ctx->s_out);
     if (ctx->d_tokens) (void)hipFree(ctx->d_tokens);  // one slab holds every workspace
     delete ctx;
@@ -240,7 +237,6 @@ int moe_ep_create(const moe_ep_config* cfg, moe_ep_ctx** out_ctx)
     const unsigned ev_flags = hipEventDisableTiming | hipEventDisableSystemFence;
     bool ok = true;
     ok = ok && hipStreamCreateWithFlags(&ctx->s_in, hipStreamNonBlocking) == hipSuccess;
-    ok = ok && hipStreamCreateWithFlags(&ctx->s_comp, hipStreamNonBlocking) == hipSuccess;
     ok = ok && hipStreamCreateWithFlags(&ctx->s_out, hipStreamNonBlocking) == hipSuccess;
     ok = ok && hipEventCreateWithFlags(&ctx->ev_start, ev_flags) == hipSuccess;
     ok = ok && hipEventCreateWithFlags(&ctx->ev_done, hipEventDisableTiming) == hipSuccess;
@@ -340,7 +336,9 @@ int moe_ep_forward(moe_ep_ctx* ctx, const void* tokens, const float* gate_logits
     hipStream_t user = static_cast<hipStream_t>(stream);
     const bool pinned = c.io_mode == MOE_EP_IO_PINNED_HOST;
     hipStream_t s_in = pinned ? ctx->s_in : user;
-    hipStream_t s_comp = pinned ? ctx->s_comp : user;
+    // compute always runs on the caller's stream; only the two link directions get streams of their
+    // own (a process has four hardware queues here: a fourth private stream would share one)
+    hipStream_t s_comp = user;
     hipStream_t s_out = pinned ? ctx->s_out : user;
     const bool prof = ctx->prof_depth > 0 && ctx->prof_recorded < ctx->prof_depth;
 
@@ -370,13 +368,20 @@ int moe_ep_forward(moe_ep_ctx* ctx, const void* tokens, const float* gate_logits
     }
     // workgroups of a copy kernel: ~128 KB in flight fills the host link; more only queues up in the
     // memory fabric in front of the other streams' kernels (measured: they ran 3-10x slower)
+    // MOE_EP_LINK_MEMCPY: the runtime's asynchronous copies (DMA engines) instead of copy kernels, kept
+    // for comparison: they overlap with compute but move 35 GB/s against 55 and cost 0.3 ms of host
+    // time per call on this system
+    const bool link_memcpy = getenv("MOE_EP_LINK_MEMCPY") != nullptr;
+    auto link_copy = [&](void* dst, const void* src, size_t bytes, int grid, hipStream_t st) -> hipError_t {
+        if (link_memcpy) return bytes ? hipMemcpyAsync(dst, src, bytes, hipMemcpyDefault, st) : hipSuccess;
+        return launch_copy(dst, src, bytes, grid, st);
+    };
     int link_grid = 8;
     if (const char* v = getenv("MOE_EP_LINK_GRID")) link_grid = atoi(v) > 0 ? atoi(v) : 8;
     const int span_total = prof_begin(ctx, prof, ST_TOTAL, user);
     if (pinned) {
         HIP_TRY(ctx, hipEventRecord(ctx->ev_start, user));
         HIP_TRY(ctx, hipStreamWaitEvent(s_in, ctx->ev_start, 0));
-        HIP_TRY(ctx, hipStreamWaitEvent(s_comp, ctx->ev_start, 0));
         HIP_TRY(ctx, hipStreamWaitEvent(s_out, ctx->ev_start, 0));
     }
     const int Tc = (T + r - 1) / r;
@@ -414,9 +419,9 @@ int moe_ep_forward(moe_ep_ctx* ctx, const void* tokens, const float* gate_logits
             const int Tn = t0 >= T ? 0 : (T - t0 < Tc ? T - t0 : Tc);
             const int sp_in = prof_begin(ctx, prof && Tn > 0, ST_COPY_IN, s_in);
             if (Tn > 0) {
-                HIP_TRY(ctx, launch_copy(static_cast<char*>(ctx->d_tokens) + (size_t)t0 * M * 2,
+                HIP_TRY(ctx, link_copy(static_cast<char*>(ctx->d_tokens) + (size_t)t0 * M * 2,
                                          h_tokens + (size_t)t0 * M * 2, (size_t)Tn * M * 2, link_grid, s_in));
-                HIP_TRY(ctx, launch_copy(ctx->d_logits + (size_t)t0 * E, h_logits + (size_t)t0 * E * 4,
+                HIP_TRY(ctx, link_copy(ctx->d_logits + (size_t)t0 * E, h_logits + (size_t)t0 * E * 4,
                                          (size_t)Tn * E * 4, link_grid, s_in));
             }
             prof_end(ctx, sp_in, s_in);
@@ -499,7 +504,7 @@ int moe_ep_forward(moe_ep_ctx* ctx, const void* tokens, const float* gate_logits
             HIP_TRY(ctx, hipEventRecord(ctx->ev_comp[cidx], s_comp));
             HIP_TRY(ctx, hipStreamWaitEvent(s_out, ctx->ev_comp[cidx], 0));
             const int sp_out = prof_begin(ctx, prof, ST_COPY_OUT, s_out);
-            HIP_TRY(ctx, launch_copy(h_out + (size_t)t0 * M * 2,
+            HIP_TRY(ctx, link_copy(h_out + (size_t)t0 * M * 2,
                                      reinterpret_cast<const char*>(out_dev) + (size_t)t0 * M * 2,
                                      (size_t)Tn * M * 2, link_grid, s_out));
             prof_end(ctx, sp_out, s_out);
