@@ -110,9 +110,10 @@ int moe_ep_create(const moe_ep_config *cfg, moe_ep_ctx **out_ctx);
  *               sum of the shared experts; tokens with nothing kept and no shared expert
  *               get zeros.  Must not overlap tokens or gate_logits.  Accumulation is fp32; the activation between the up and down
  *               projections and each expert's output are rounded to bf16 once.
- *   stream      hipStream_t (NULL = the default stream).  The call only enqueues work:
- *               it starts after everything already on `stream` and `stream` is made to
- *               wait for its completion.  Buffers must stay valid until then.
+ *   stream      hipStream_t (NULL = the default stream).  The call only enqueues work: every
+ *               kernel runs on `stream`, after what is already there; in pinned-host mode the
+ *               chunk copies run on two streams of the context and `stream` is made to wait
+ *               for the last of them.  Buffers must stay valid until `stream` reaches that point.
  *
  * tokens / gate_logits / out are device pointers in MOE_EP_IO_DEVICE mode and pinned host
  * pointers in MOE_EP_IO_PINNED_HOST mode.  The caller owns every buffer passed in; the

@@ -3,7 +3,8 @@
 // transfers and expert compute overlap; Sec. 3.2, Eq. limitation: each of the three
 // resources -- inbound transfer, expert compute, outbound transfer -- runs one task at a
 // time, and a chunk's compute waits for its inbound transfer, its outbound transfer for its
-// compute).  The resources are three HIP streams; the precedence rules are HIP events.
+// compute).  The resources are three HIP streams -- the caller's for compute, two of the context's
+// for the link directions -- and the precedence rules are HIP events.
 #include <hip/hip_runtime.h>
 
 #include <cstdio>
