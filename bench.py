@@ -74,6 +74,10 @@ def main() -> int:
     ap.add_argument("--fit-pipeline", action="store_true",
                     help="pinned-host workloads: fit the linear task models of Sec. 4.1 from r=1 forwards at "
                          "several token counts, choose r_2 from them and compare with measured r sweeps")
+    ap.add_argument("--layers", type=int, default=1,
+                    help="steady state over several layers: after the main measurement, time this many "
+                         "forwards back to back per step, each with its own copy of the weights "
+                         "(Sec. 4.2: the per-layer offset of the multi-layer timeline)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one 1 GiB device-to-device copy kernel: the known-size reference "
                          "that rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled by")
@@ -281,6 +285,27 @@ def main() -> int:
             "measured_ms": {str(r): measured[r] for r in r_sweep},
             "chosen_r": ctx.last_chunks(), "measured_best_r": min(measured, key=measured.get),
         }
+    if args.layers > 1:
+        # layer l > 0 uses a rolled copy of layer 0's weights: distinct memory, same distribution, so no
+        # layer finds its weights in a cache the previous one filled
+        L = args.layers
+        routed_l = [routed] + [torch.roll(routed, 4099 * l) for l in range(1, L)]
+        shared_l = [shared] + [None if shared is None else torch.roll(shared, 4099 * l) for l in range(1, L)]
+
+        def layer_step():
+            for l in range(L):
+                ctx.forward(tokens, logits, routed_l[l], shared_l[l], k, args.r, args.order, n_tokens=T, out=out,
+                            stream=stream)
+        for _ in range(3):
+            layer_step()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for _ in range(args.steps):
+            layer_step()
+        torch.cuda.synchronize()
+        per_layer_ms = (time.perf_counter() - t1) / (args.steps * L) * 1e3
+        line["multi_layer"] = {"layers": L, "ms_per_layer": per_layer_ms, "tokens_per_s": T / (per_layer_ms * 1e-3),
+                               "single_layer_ms": ms_per_step}
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(wl, inp)
     if args.copy_probe:
