@@ -58,7 +58,7 @@ typedef enum {
 
 typedef struct {
     int32_t hidden;       /* M; multiple of 64                                              */
-    int32_t inter;        /* H of a routed expert; multiple of 64                           */
+    int32_t inter;        /* H of a routed expert; multiple of 64; hidden * inter < 2^30    */
     int32_t n_experts;    /* E, size of the gate's expert axis; 1..512                      */
     int32_t local_begin;  /* first expert held here; experts [local_begin, +n_local)        */
     int32_t n_local;      /* E/eg experts held here; >= 1                                   */

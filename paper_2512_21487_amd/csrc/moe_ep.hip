@@ -135,12 +135,16 @@ int moe_ep_validate_config(const moe_ep_config* c, const char** why)
     if (!c) { set_why(why, "cfg is NULL"); return MOE_EP_EINVAL; }
     if (c->hidden < 64 || c->hidden % 64) { set_why(why, "hidden must be a positive multiple of 64"); return MOE_EP_EINVAL; }
     if (c->inter < 64 || c->inter % 64) { set_why(why, "inter must be a positive multiple of 64"); return MOE_EP_EINVAL; }
+    // the GEMM's lanes address one expert's W_gate | W_up pair with 32-bit byte offsets
+    if ((long long)c->hidden * c->inter >= (1ll << 30)) { set_why(why, "hidden * inter must be below 2^30"); return MOE_EP_EINVAL; }
     if (c->n_experts < 1 || c->n_experts > 512) { set_why(why, "n_experts must be in 1..512"); return MOE_EP_EINVAL; }
     if (c->n_local < 1 || c->local_begin < 0 || (long long)c->local_begin + c->n_local > c->n_experts) {
         set_why(why, "local experts [local_begin, local_begin+n_local) must lie inside 0..n_experts"); return MOE_EP_EINVAL; }
     if (c->n_shared < 0 || c->n_shared > 64) { set_why(why, "n_shared must be in 0..64"); return MOE_EP_EINVAL; }
     if (c->n_shared > 0 && (c->shared_inter < 64 || c->shared_inter % 64)) {
         set_why(why, "shared_inter must be a positive multiple of 64 when n_shared > 0"); return MOE_EP_EINVAL; }
+    if (c->n_shared > 0 && (long long)c->hidden * c->shared_inter >= (1ll << 30)) {
+        set_why(why, "hidden * shared_inter must be below 2^30"); return MOE_EP_EINVAL; }
     if (c->max_tokens < 1 || c->max_tokens > (1 << 20)) { set_why(why, "max_tokens must be in 1..1048576"); return MOE_EP_EINVAL; }
     if (c->max_top_k < 1 || c->max_top_k > 64 || c->max_top_k > c->n_experts) {
         set_why(why, "max_top_k must be in 1..min(n_experts, 64)"); return MOE_EP_EINVAL; }
@@ -454,11 +458,13 @@ int moe_ep_forward(moe_ep_ctx* ctx, const void* tokens, const float* gate_logits
         HIP_TRY(ctx, launch_router(log_dev + (size_t)t0 * E, Tn, E, k, e0, El, idx, w, ctx->blk_mask, s_comp));
         prof_end(ctx, sp, s_comp);
 
+        // the fused gather addresses a chunk's token rows with 32-bit byte offsets
+        const bool fused = ctx->fused_gather && (unsigned long long)Tn * M * 2 < (1ull << 32);
         sp = prof_begin(ctx, prof, ST_PARTITION, s_comp);
         HIP_TRY(ctx, launch_dispatch_scan(ctx->blk_mask, nblk, El, BMv, ctx->blk_off, count, offset, mt_prefix, s_comp));
         if (Tn > 0) {
             HIP_TRY(ctx, launch_dispatch_permute(idx, ctx->blk_mask, ctx->blk_off, offset, Tn, k, e0, El, pos, perm, s_comp));
-            if (!ctx->fused_gather)
+            if (!fused)
                 HIP_TRY(ctx, launch_gather_rows(tok_dev + (size_t)t0 * M, perm, offset + El, k, M, ctx->xp, bw_grid, s_comp));
         }
         prof_end(ctx, sp, s_comp);
@@ -476,7 +482,7 @@ int moe_ep_forward(moe_ep_ctx* ctx, const void* tokens, const float* gate_logits
         g1.G = El; g1.dense_rows = 0; g1.K = M; g1.N = H; g1.lda = M; g1.ldc = H; g1.ldw = M;
         g1.w_group_stride = (long long)3 * H * M; g1.w_up_offset = (long long)H * M;
         g1.kseg_len = M; g1.w_kseg_stride = 0; g1.c_group_col_stride = 0;
-        if (ctx->fused_gather) {  // the projection reads the token rows through the row -> assignment map
+        if (fused) {  // the projection reads the token rows through the row -> assignment map
             g1.A = tok_dev + (size_t)t0 * M; g1.a_row_map = perm; g1.a_row_div = k; g1.a_src_rows = Tn;
         }
         sp = prof_begin(ctx, prof, ST_GEMM1, s_comp);

@@ -58,6 +58,7 @@ def test_valid_config_and_workspace_size():
     (dict(max_top_k=65, n_experts=128, n_local=8), "max_top_k"),
     (dict(max_chunks=0), "max_chunks"), (dict(max_chunks=65), "max_chunks"),
     (dict(io_mode=2), "io_mode"), (dict(device=-1), "device"),
+    (dict(hidden=32768, inter=32768), "2^30"), (dict(hidden=32768, n_shared=1, shared_inter=32768), "2^30"),
 ])
 def test_bad_config_is_rejected_with_a_reason(kw, word):
     rc, why = pkg.validate_config(_good(**kw))
