@@ -78,6 +78,9 @@ def main() -> int:
                     help="steady state over several layers: after the main measurement, time this many "
                          "forwards back to back per step, each with its own copy of the weights "
                          "(Sec. 4.2: the per-layer offset of the multi-layer timeline)")
+    ap.add_argument("--timeline", action="store_true",
+                    help="after the main measurement, record one forward with events around every stage and "
+                         "add its measured schedule (stage, begin ms, end ms per chunk) to the JSON line")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one 1 GiB device-to-device copy kernel: the known-size reference "
                          "that rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled by")
@@ -285,6 +288,14 @@ def main() -> int:
             "measured_ms": {str(r): measured[r] for r in r_sweep},
             "chosen_r": ctx.last_chunks(), "measured_best_r": min(measured, key=measured.get),
         }
+    if args.timeline:
+        ctx.set_profiling_stages(None)
+        ctx.set_profiling(1)
+        step()
+        line["timeline"] = [{"stage": n, "begin_ms": round(b, 4), "end_ms": round(e, 4)}
+                            for n, _, b, e in ctx.get_timeline() if n != "forward"]
+        ctx.get_stage_ms()
+        ctx.set_profiling(0)
     if args.layers > 1:
         # layer l > 0 uses a rolled copy of layer 0's weights: distinct memory, same distribution, so no
         # layer finds its weights in a cache the previous one filled

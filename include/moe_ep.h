@@ -160,6 +160,16 @@ int moe_ep_set_profiling(moe_ep_ctx *ctx, int32_t depth);
  * calls); timing only one stage leaves the rest of the forward undisturbed. */
 int moe_ep_set_profiling_stages(moe_ep_ctx *ctx, uint32_t mask);
 int moe_ep_get_stage_ms(moe_ep_ctx *ctx, float *ms, int32_t n);
+/*
+ * The measured schedule: for every timed stage instance of the forwards recorded in the current
+ * window (call it before moe_ep_get_stage_ms, which closes the window), in issue order, its stage
+ * (index into ms[] above), the forward it belongs to (0-based inside the window) and its start and
+ * end in milliseconds after that forward's first enqueue.  With r_2 chunks a stage appears r_2 times;
+ * this is the timeline the start times tau of Sec. 3.2 describe.  Arrays (host, any may be NULL) hold
+ * max_spans entries; *n_spans receives the number written.
+ */
+int moe_ep_get_timeline(moe_ep_ctx *ctx, int32_t *stage, int32_t *forward, float *begin_ms, float *end_ms,
+                        int32_t max_spans, int32_t *n_spans);
 
 /*
  * Timing model of the chunk pipeline and the choice of r_2 (Sec. 4.1 linear task models; Sec. 4.2

@@ -104,6 +104,8 @@ def load_library() -> ctypes.CDLL:
     lib.moe_ep_set_profiling.argtypes = [vp, i32]
     lib.moe_ep_set_profiling_stages.restype = ctypes.c_int
     lib.moe_ep_set_profiling_stages.argtypes = [vp, ctypes.c_uint32]
+    lib.moe_ep_get_timeline.restype = ctypes.c_int
+    lib.moe_ep_get_timeline.argtypes = [vp, vp, vp, vp, vp, i32, ctypes.POINTER(i32)]
     lib.moe_ep_get_stage_ms.restype = ctypes.c_int
     lib.moe_ep_get_stage_ms.argtypes = [vp, vp, i32]
     dp = ctypes.POINTER(ctypes.c_double)
@@ -326,6 +328,18 @@ class MoeEp:
         rc = self._lib.moe_ep_set_profiling_stages(self._ctx, mask)
         if rc != 0:
             raise MoeEpError(rc, self.last_error())
+
+    def get_timeline(self, max_spans: int = 4096):
+        """moe_ep_get_timeline: list of (stage name, forward index, begin ms, end ms)."""
+        st = (ctypes.c_int32 * max_spans)(); fw = (ctypes.c_int32 * max_spans)()
+        b = (ctypes.c_float * max_spans)(); e = (ctypes.c_float * max_spans)()
+        n = ctypes.c_int32()
+        rc = self._lib.moe_ep_get_timeline(self._ctx, ctypes.cast(st, ctypes.c_void_p), ctypes.cast(fw, ctypes.c_void_p),
+                                           ctypes.cast(b, ctypes.c_void_p), ctypes.cast(e, ctypes.c_void_p),
+                                           max_spans, ctypes.byref(n))
+        if rc != 0:
+            raise MoeEpError(rc, self.last_error())
+        return [(STAGES[st[i]], int(fw[i]), float(b[i]), float(e[i])) for i in range(n.value)]
 
     def get_stage_ms(self) -> Dict[str, float]:
         ms = (ctypes.c_float * len(STAGES))()

@@ -22,7 +22,7 @@ namespace {
 
 enum Stage { ST_ROUTER = 0, ST_PARTITION, ST_GEMM1, ST_GEMM2, ST_SGEMM1, ST_SGEMM2, ST_COMBINE, ST_TOTAL, ST_COPY_IN, ST_COPY_OUT, ST_COUNT };
 
-struct ProfSpan { hipEvent_t a, b; int stage; };
+struct ProfSpan { hipEvent_t a, b; int stage; int forward; };
 
 }  // namespace
 
@@ -115,7 +115,7 @@ int prof_begin(moe_ep_ctx* ctx, bool on, int stage, hipStream_t s)
     hipEvent_t a = prof_event(ctx), b = prof_event(ctx);
     if (!a || !b) return -1;
     if (hipEventRecord(a, s) != hipSuccess) return -1;
-    ctx->prof_spans.push_back({a, b, stage});
+    ctx->prof_spans.push_back({a, b, stage, ctx->prof_recorded});
     return (int)ctx->prof_spans.size() - 1;
 }
 void prof_end(moe_ep_ctx* ctx, int span, hipStream_t s)
@@ -296,6 +296,33 @@ int moe_ep_set_profiling_stages(moe_ep_ctx* ctx, uint32_t mask)
     return MOE_EP_OK;
 }
 
+int moe_ep_get_timeline(moe_ep_ctx* ctx, int32_t* stage, int32_t* forward, float* begin_ms, float* end_ms,
+                        int32_t max_spans, int32_t* n_spans)
+{
+    if (!ctx || !n_spans || max_spans < 0) return MOE_EP_EINVAL;
+    if (ctx->prof_recorded == 0) return fail(ctx, MOE_EP_ESTATE, "no profiled forward recorded");
+    HIP_TRY(ctx, hipSetDevice(ctx->cfg.device));
+    HIP_TRY(ctx, hipDeviceSynchronize());
+    // time zero of a forward = the start of its whole-forward span (or of its first span)
+    std::vector<hipEvent_t> zero(ctx->prof_recorded, nullptr);
+    for (const ProfSpan& sp : ctx->prof_spans)
+        if (sp.forward < ctx->prof_recorded && (sp.stage == ST_TOTAL || !zero[sp.forward])) zero[sp.forward] = sp.a;
+    int n = 0;
+    for (const ProfSpan& sp : ctx->prof_spans) {
+        if (sp.forward >= ctx->prof_recorded || n >= max_spans) continue;
+        float t0 = 0.f, t1 = 0.f;
+        HIP_TRY(ctx, hipEventElapsedTime(&t0, zero[sp.forward], sp.a));
+        HIP_TRY(ctx, hipEventElapsedTime(&t1, zero[sp.forward], sp.b));
+        if (stage) stage[n] = sp.stage;
+        if (forward) forward[n] = sp.forward;
+        if (begin_ms) begin_ms[n] = t0;
+        if (end_ms) end_ms[n] = t1;
+        ++n;
+    }
+    *n_spans = n;
+    return MOE_EP_OK;
+}
+
 int moe_ep_get_stage_ms(moe_ep_ctx* ctx, float* ms, int32_t n)
 {
     if (!ctx || !ms || n < 1) return MOE_EP_EINVAL;
@@ -341,9 +368,9 @@ int moe_ep_forward(moe_ep_ctx* ctx, const void* tokens, const float* gate_logits
     hipStream_t user = static_cast<hipStream_t>(stream);
     const bool pinned = c.io_mode == MOE_EP_IO_PINNED_HOST;
     hipStream_t s_in = pinned ? ctx->s_in : user;
-    // compute always runs on the caller's stream; only the two link directions get streams of their
-    // own (a process has four hardware queues here: a fourth private stream would share one)
+    // compute always runs on the caller's stream; only the two link directions get streams of their own
     hipStream_t s_comp = user;
+    const int n_cu = ctx->n_cu;
     hipStream_t s_out = pinned ? ctx->s_out : user;
     const bool prof = ctx->prof_depth > 0 && ctx->prof_recorded < ctx->prof_depth;
 
@@ -376,9 +403,11 @@ int moe_ep_forward(moe_ep_ctx* ctx, const void* tokens, const float* gate_logits
     // MOE_EP_LINK_MEMCPY: the runtime's asynchronous copies (DMA engines) instead of copy kernels, kept
     // for comparison: they overlap with compute but move 35 GB/s against 55 and cost 0.3 ms of host
     // time per call on this system
-    const bool link_memcpy = getenv("MOE_EP_LINK_MEMCPY") != nullptr;
+    const char* link_env = getenv("MOE_EP_LINK_MEMCPY");   // "1" both directions, "in" / "out" one
+    const bool memcpy_in = link_env && (link_env[0] == '1' || link_env[0] == 'i');
+    const bool memcpy_out = link_env && (link_env[0] == '1' || link_env[0] == 'o');
     auto link_copy = [&](void* dst, const void* src, size_t bytes, int grid, hipStream_t st) -> hipError_t {
-        if (link_memcpy) return bytes ? hipMemcpyAsync(dst, src, bytes, hipMemcpyDefault, st) : hipSuccess;
+        if (st == s_in ? memcpy_in : memcpy_out) return bytes ? hipMemcpyAsync(dst, src, bytes, hipMemcpyDefault, st) : hipSuccess;
         return launch_copy(dst, src, bytes, grid, st);
     };
     int link_grid = 8;
@@ -390,7 +419,7 @@ int moe_ep_forward(moe_ep_ctx* ctx, const void* tokens, const float* gate_logits
         HIP_TRY(ctx, hipStreamWaitEvent(s_out, ctx->ev_start, 0));
     }
     const int Tc = (T + r - 1) / r;
-    const int bw_grid = ctx->n_cu * 8;  // bandwidth kernels: 8 workgroups of 4 wavefronts per CU
+    const int bw_grid = n_cu * 8;  // bandwidth kernels: 8 workgroups of 4 wavefronts per CU
 
     // shared experts of token range [t0, t0+Tn) -> output rows [t0, t0+Tn); the aggregation adds to them
     auto run_shared = [&](int t0, int Tn) -> int {
@@ -403,7 +432,7 @@ int moe_ep_forward(moe_ep_ctx* ctx, const void* tokens, const float* gate_logits
         const int sbm = grouped_gemm_row_tile(ctx->shared_variant);
         const int mt = (Tn + sbm - 1) / sbm;
         int sp = prof_begin(ctx, prof, ST_SGEMM1, s_comp);
-        HIP_TRY(ctx, launch_grouped_gemm(g1, true, ctx->shared_variant, ctx->n_cu, mt * Ns, s_comp));
+        HIP_TRY(ctx, launch_grouped_gemm(g1, true, ctx->shared_variant, n_cu, mt * Ns, s_comp));
         prof_end(ctx, sp, s_comp);
         GemmArgs g2{};
         g2.A = ctx->hs + (size_t)t0 * Ns * Hs; g2.W = sw + (size_t)2 * Hs * M; g2.C = out_dev + (size_t)t0 * M;
@@ -412,7 +441,7 @@ int moe_ep_forward(moe_ep_ctx* ctx, const void* tokens, const float* gate_logits
         g2.w_group_stride = 0; g2.w_up_offset = 0;
         g2.kseg_len = Hs; g2.w_kseg_stride = (long long)3 * Hs * M; g2.c_group_col_stride = 0;
         sp = prof_begin(ctx, prof, ST_SGEMM2, s_comp);
-        HIP_TRY(ctx, launch_grouped_gemm(g2, false, ctx->shared_variant, ctx->n_cu, mt, s_comp));
+        HIP_TRY(ctx, launch_grouped_gemm(g2, false, ctx->shared_variant, n_cu, mt, s_comp));
         prof_end(ctx, sp, s_comp);
         return MOE_EP_OK;
     };
@@ -486,7 +515,7 @@ int moe_ep_forward(moe_ep_ctx* ctx, const void* tokens, const float* gate_logits
             g1.A = tok_dev + (size_t)t0 * M; g1.a_row_map = perm; g1.a_row_div = k; g1.a_src_rows = Tn;
         }
         sp = prof_begin(ctx, prof, ST_GEMM1, s_comp);
-        HIP_TRY(ctx, launch_grouped_gemm(g1, true, variant, ctx->n_cu, max_row_tiles, s_comp));
+        HIP_TRY(ctx, launch_grouped_gemm(g1, true, variant, n_cu, max_row_tiles, s_comp));
         prof_end(ctx, sp, s_comp);
 
         GemmArgs g2{};
@@ -495,7 +524,7 @@ int moe_ep_forward(moe_ep_ctx* ctx, const void* tokens, const float* gate_logits
         g2.w_group_stride = (long long)3 * H * M; g2.w_up_offset = 0;
         g2.kseg_len = H; g2.w_kseg_stride = 0; g2.c_group_col_stride = 0;
         sp = prof_begin(ctx, prof, ST_GEMM2, s_comp);
-        HIP_TRY(ctx, launch_grouped_gemm(g2, false, variant, ctx->n_cu, max_row_tiles, s_comp));
+        HIP_TRY(ctx, launch_grouped_gemm(g2, false, variant, n_cu, max_row_tiles, s_comp));
         prof_end(ctx, sp, s_comp);
 
         if (Ns > 0 && order == MOE_EP_ORDER_INTERLEAVED) {
@@ -512,8 +541,8 @@ int moe_ep_forward(moe_ep_ctx* ctx, const void* tokens, const float* gate_logits
             HIP_TRY(ctx, hipStreamWaitEvent(s_out, ctx->ev_comp[cidx], 0));
             const int sp_out = prof_begin(ctx, prof, ST_COPY_OUT, s_out);
             HIP_TRY(ctx, link_copy(h_out + (size_t)t0 * M * 2,
-                                     reinterpret_cast<const char*>(out_dev) + (size_t)t0 * M * 2,
-                                     (size_t)Tn * M * 2, link_grid, s_out));
+                                   reinterpret_cast<const char*>(out_dev) + (size_t)t0 * M * 2,
+                                   (size_t)Tn * M * 2, link_grid, s_out));
             prof_end(ctx, sp_out, s_out);
         }
     }

@@ -249,6 +249,38 @@ def test_pinned_host_chunks_that_start_off_16_byte_boundaries():
     pctx.destroy()
 
 
+def test_measured_timeline_obeys_the_precedence_rules():
+    """The measured schedule of a pinned-host forward with r_2 = 3 (moe_ep_get_timeline): every stage
+    appears once per chunk, a chunk's compute starts after its inbound copy ends and its outbound copy
+    after its aggregation ends (Sec. 3.2, Eq. limitation, rules 7-8), each resource runs its tasks in
+    chunk order without overlap (rules 3-5)."""
+    g = _gpu()
+    wl = tiny_workload(name="timeline", n_tokens=600, hidden=256, inter=192, n_experts=16, n_local=16, top_k=2)
+    pctx = g.make_ctx(wl, pinned=True)
+    pd = g.DeviceInputs(wl, make_inputs(wl, seed=33), pinned=True)
+    g.run_forward(pctx, wl, pd, r=3)
+    pctx.set_profiling(1)
+    g.run_forward(pctx, wl, pd, r=3)
+    tl = pctx.get_timeline()
+    pctx.get_stage_ms()
+    pctx.set_profiling(0)
+    by = {}
+    for name, fwd, b, e in tl:
+        assert fwd == 0 and e >= b >= 0.0
+        by.setdefault(name, []).append((b, e))
+    for name in ("copy_in", "router", "partition", "routed_gate_up_gemm", "routed_down_gemm", "aggregation", "copy_out"):
+        assert len(by[name]) == 3, name
+        for (b0, e0), (b1, e1) in zip(by[name], by[name][1:]):
+            assert b1 >= e0 - 1e-3, f"{name}: chunks overlap on one resource"
+    eps = 2e-3  # event timestamps resolve to about a microsecond
+    for c in range(3):
+        assert by["router"][c][0] >= by["copy_in"][c][1] - eps
+        assert by["copy_out"][c][0] >= by["aggregation"][c][1] - eps
+        assert by["routed_down_gemm"][c][0] >= by["routed_gate_up_gemm"][c][1] - eps
+    assert len(by["forward"]) == 1 and by["forward"][0][1] >= by["copy_out"][2][1] - eps
+    pctx.destroy()
+
+
 def test_auto_chunks_from_timing_model():
     """r_chunks = 0 takes r_2 from the context's timing model (Sec. 4.2) and changes no output bit."""
     g = _gpu()
