@@ -78,6 +78,11 @@ def main() -> int:
                     help="steady state over several layers: after the main measurement, time this many "
                          "forwards back to back per step, each with its own copy of the weights "
                          "(Sec. 4.2: the per-layer offset of the multi-layer timeline)")
+    ap.add_argument("--io", choices=["device", "pinned"], default=None,
+                    help="override where the workload keeps tokens / gate scores / output")
+    ap.add_argument("--graph", action="store_true",
+                    help="device I/O only: after the main measurement, capture one forward in a HIP graph and "
+                         "time its replays (launch gaps removed)")
     ap.add_argument("--timeline", action="store_true",
                     help="after the main measurement, record one forward with events around every stage and "
                          "add its measured schedule (stage, begin ms, end ms per chunk) to the JSON line")
@@ -102,7 +107,7 @@ def main() -> int:
     torch.cuda.set_device(0)
     inp = make_inputs(wl)
     T, M, H, k = wl.n_tokens, wl.hidden, wl.inter, wl.top_k
-    pinned = wl.pinned_io
+    pinned = wl.pinned_io if args.io is None else args.io == "pinned"
 
     def put(a, host=False):
         a = a.view(np.int16) if a.dtype == np.uint16 else a
@@ -288,6 +293,22 @@ def main() -> int:
             "measured_ms": {str(r): measured[r] for r in r_sweep},
             "chosen_r": ctx.last_chunks(), "measured_best_r": min(measured, key=measured.get),
         }
+    if args.graph and not pinned:
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            ctx.forward(tokens, logits, routed, shared, k, args.r, args.order, n_tokens=T, out=out,
+                        stream=torch.cuda.current_stream().cuda_stream)
+        for _ in range(3):
+            graph.replay()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        g_ms = (time.perf_counter() - t1) / args.steps * 1e3
+        line["graph_replay"] = {"ms_per_step": g_ms, "tokens_per_s": T / (g_ms * 1e-3), "eager_ms_per_step": ms_per_step}
     if args.timeline:
         ctx.set_profiling_stages(None)
         ctx.set_profiling(1)

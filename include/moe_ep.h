@@ -114,6 +114,8 @@ int moe_ep_create(const moe_ep_config *cfg, moe_ep_ctx **out_ctx);
  *               kernel runs on `stream`, after what is already there; in pinned-host mode the
  *               chunk copies run on two streams of the context and `stream` is made to wait
  *               for the last of them.  Buffers must stay valid until `stream` reaches that point.
+ *               In device mode the call allocates nothing, sets no memory and never waits on the
+ *               host, so it may be recorded into a HIP graph (stream capture) and replayed.
  *
  * tokens / gate_logits / out are device pointers in MOE_EP_IO_DEVICE mode and pinned host
  * pointers in MOE_EP_IO_PINNED_HOST mode.  The caller owns every buffer passed in; the

@@ -249,6 +249,35 @@ def test_pinned_host_chunks_that_start_off_16_byte_boundaries():
     pctx.destroy()
 
 
+def test_device_mode_forward_can_be_captured_in_a_graph():
+    """Device mode enqueues kernels on the caller's stream and nothing else (no allocation, no memset,
+    no host synchronisation), so a forward can be captured once and replayed; every replay, with
+    eager work and synchronisations in between, must reproduce the eager bits."""
+    g = _gpu()
+    wl = tiny_workload(name="graph", n_tokens=300, hidden=128, inter=192, n_experts=12, local_begin=2,
+                       n_local=8, top_k=3, n_shared=1, shared_inter=64)
+    inp = make_inputs(wl, seed=34)
+    ctx = g.make_ctx(wl)
+    d = g.DeviceInputs(wl, inp)
+    eager = g.run_forward(ctx, wl, d, r=2, order=1)
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    d.out.zero_()
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph, stream=side):
+        ctx.forward(d.tokens, d.logits, d.routed, d.shared, wl.top_k, 2, 1, n_tokens=wl.n_tokens, out=d.out,
+                    stream=torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    for rep in range(4):
+        d.out.zero_()
+        scratch = torch.randn(1 << 16, device="cuda").sum().item()  # eager work between replays
+        graph.replay()
+        torch.cuda.synchronize()
+        got = d.out.cpu().numpy().view(np.uint16)
+        assert np.array_equal(got, eager), f"replay {rep} differs from the eager forward"
+    ctx.destroy()
+
+
 def test_measured_timeline_obeys_the_precedence_rules():
     """The measured schedule of a pinned-host forward with r_2 = 3 (moe_ep_get_timeline): every stage
     appears once per chunk, a chunk's compute starts after its inbound copy ends and its outbound copy
