@@ -66,6 +66,13 @@ struct WsLayout {
     size_t tokens, logits, out, idx, w, pos, perm, blk_mask, blk_off, count, offset, mt_prefix, xp, h, y, hs, total;
 };
 
+// MOE_EP_FUSED_GATHER=0 brings back the grouped copy of the token rows (for comparison)
+bool fused_gather_enabled()
+{
+    const char* v = getenv("MOE_EP_FUSED_GATHER");
+    return v == nullptr || atoi(v) != 0;
+}
+
 WsLayout ws_layout(const moe_ep_config& c)
 {
     WsLayout L{};
@@ -81,7 +88,10 @@ WsLayout ws_layout(const moe_ep_config& c)
     L.idx = take(A * 4); L.w = take(A * 4); L.pos = take(A * 4); L.perm = take(A * 4);
     L.blk_mask = take(nblk * El * 8); L.blk_off = take(nblk * El * 4);
     L.count = take(R * El * 4); L.offset = take(R * (El + 1) * 4); L.mt_prefix = take(R * (El + 1) * 4);
-    L.xp = take(A * M * 2); L.h = take(A * H * 2); L.y = take(A * M * 2);
+    // the grouped copy of the token rows exists only when the gate/up projection cannot gather them
+    // itself: switched off, or a chunk of 4 GB and more (its lanes hold 32-bit byte offsets)
+    const bool need_xp = !fused_gather_enabled() || T * M * 2 >= ((size_t)1 << 32);
+    L.xp = take(need_xp ? A * M * 2 : 0); L.h = take(A * H * 2); L.y = take(A * M * 2);
     L.hs = take(c.n_shared > 0 ? T * (size_t)c.n_shared * (size_t)c.shared_inter * 2 : 0);
     L.total = o;
     return L;
@@ -214,7 +224,7 @@ int moe_ep_create(const moe_ep_config* cfg, moe_ep_ctx** out_ctx)
     // tile-shape overrides for tuning (indices into the variant table of grouped_gemm.hip)
     if (const char* v = getenv("MOE_EP_GEMM_VARIANT")) ctx->gemm_variant = atoi(v);
     if (const char* v = getenv("MOE_EP_SHARED_VARIANT")) ctx->shared_variant = atoi(v);
-    if (const char* v = getenv("MOE_EP_FUSED_GATHER")) ctx->fused_gather = atoi(v) != 0;
+    ctx->fused_gather = fused_gather_enabled();
     if (grouped_gemm_init() != hipSuccess) { delete ctx; return MOE_EP_EHIP; }
 
     const WsLayout L = ws_layout(*cfg);
@@ -241,8 +251,10 @@ int moe_ep_create(const moe_ep_config* cfg, moe_ep_ctx** out_ctx)
     // write-back a default event record implies (it stalled the other streams' kernels)
     const unsigned ev_flags = hipEventDisableTiming | hipEventDisableSystemFence;
     bool ok = true;
-    ok = ok && hipStreamCreateWithFlags(&ctx->s_in, hipStreamNonBlocking) == hipSuccess;
-    ok = ok && hipStreamCreateWithFlags(&ctx->s_out, hipStreamNonBlocking) == hipSuccess;
+    if (cfg->io_mode == MOE_EP_IO_PINNED_HOST) {
+        ok = ok && hipStreamCreateWithFlags(&ctx->s_in, hipStreamNonBlocking) == hipSuccess;
+        ok = ok && hipStreamCreateWithFlags(&ctx->s_out, hipStreamNonBlocking) == hipSuccess;
+    }
     ok = ok && hipEventCreateWithFlags(&ctx->ev_start, ev_flags) == hipSuccess;
     ok = ok && hipEventCreateWithFlags(&ctx->ev_done, hipEventDisableTiming) == hipSuccess;
     ok = ok && hipEventCreateWithFlags(&ctx->ev_comp_done, ev_flags) == hipSuccess;
