@@ -188,6 +188,22 @@ def test_every_tile_variant_matches_oracle(variant, hidden):
                 os.environ[k] = v
 
 
+def test_grouped_copy_of_token_rows_matches_too():
+    """MOE_EP_FUSED_GATHER=0: the token rows are first copied into expert-grouped order and the gate/up
+    projection reads that copy (the path kept for comparison and for chunks of 4 GB and more)."""
+    wl = tiny_workload(name="grouped_copy", n_tokens=333, hidden=192, inter=320, n_experts=10, local_begin=2,
+                       n_local=6, top_k=3, n_shared=1, shared_inter=192)
+    old = os.environ.get("MOE_EP_FUSED_GATHER")
+    os.environ["MOE_EP_FUSED_GATHER"] = "0"
+    try:
+        _full_parity(wl, seed=35, r=2)
+    finally:
+        if old is None:
+            os.environ.pop("MOE_EP_FUSED_GATHER", None)
+        else:
+            os.environ["MOE_EP_FUSED_GATHER"] = old
+
+
 # ------------------------------------------------------------------ invariants on the GPU
 def test_chunking_and_order_do_not_change_a_bit():
     g = _gpu()
