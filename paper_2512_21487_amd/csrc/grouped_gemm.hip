@@ -30,15 +30,14 @@
 
 namespace moe_ep {
 
-template <int BM, int BN, int BK_, int STAGES_, int WGM, int WGN, int KG_, bool SWIGLU>
+template <int BM, int BN, int BK_, int STAGES_, int WGM, int WGN, bool SWIGLU>
 struct GemmCfg {
     static constexpr int BK = BK_, STAGES = STAGES_;
     static constexpr int CPR = BK / 8;             // 16-byte chunks per LDS row
     static constexpr int RP = 16 / CPR;            // LDS rows per 256 bytes (one sweep over all banks)
     static constexpr int RPR = 64 / CPR;           // LDS rows per 1 KB region (one wave load instruction)
-    static constexpr int KG = KG_;                 // wavefront groups that split every K step between them
-    static constexpr int KKW = BK / 16 / KG;       // MFMA k16 steps per K step and wavefront
-    static constexpr int NW = WGM * WGN * KG, THREADS = NW * 64;
+    static constexpr int KKW = BK / 16;            // MFMA k16 steps per K step
+    static constexpr int NW = WGM * WGN, THREADS = NW * 64;
     static constexpr int WTM = BM / WGM, WTN = BN / WGN;
     static constexpr int MB = WTM / 32, NB = WTN / 32;
     static constexpr int REGIONS = (BM + BN) / RPR;
@@ -52,9 +51,7 @@ struct GemmCfg {
     static_assert(!SWIGLU || NB % 2 == 0, "gate/up blocks pair up inside a wavefront");
     static_assert((BM / RPR) % NW == 0 && (BN / RPR) % NW == 0, "regions split evenly over wavefronts");
     static_assert(STAGES >= 2 && STAGES <= 5 && (STAGES - 2) * RPW <= 63, "ring depth and vmcnt budget");
-    static_assert(KG == 1 || (KG == 2 && MB % 2 == 0 && KKW >= 1), "K split over two wavefront groups");
     static_assert(KKW % 2 == 0, "a K step starts and ends on fragment set 0 / 1");
-    static_assert(KG == 1 || LDS_BYTES >= NW * (MB / 2) * NB * 1024, "partial sums are exchanged through the ring's LDS");
 };
 
 __device__ __forceinline__ float silu_f(float g) { return g / (1.0f + __expf(-g)); }
@@ -63,10 +60,10 @@ __device__ __forceinline__ float silu_f(float g) { return g / (1.0f + __expf(-g)
 // read has returned (gfx9 encoding: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[5:4] << 14)
 #define MOE_EP_WAIT_VMCNT_LGKM0(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | (((n) >> 4) << 14) | 0x0070)
 
-template <int BM, int BN, int BK, int STAGES, int WGM, int WGN, int KG, bool SWIGLU, bool RAGGED>
-__global__ __launch_bounds__(WGM* WGN* KG * 64) void grouped_gemm_kernel(GemmArgs a)
+template <int BM, int BN, int BK, int STAGES, int WGM, int WGN, bool SWIGLU, bool RAGGED>
+__global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_kernel(GemmArgs a)
 {
-    using Cfg = GemmCfg<BM, BN, BK, STAGES, WGM, WGN, KG, SWIGLU>;
+    using Cfg = GemmCfg<BM, BN, BK, STAGES, WGM, WGN, SWIGLU>;
     constexpr int MB = Cfg::MB, NB = Cfg::NB, RPW = Cfg::RPW, XRPW = Cfg::XRPW, NW = Cfg::NW;
     constexpr int THREADS = Cfg::THREADS, BN_OUT = Cfg::BN_OUT, CPR = Cfg::CPR, RP = Cfg::RP;
     constexpr int RPR = Cfg::RPR, KKW = Cfg::KKW;
@@ -76,7 +73,7 @@ __global__ __launch_bounds__(WGM* WGN* KG * 64) void grouped_gemm_kernel(GemmArg
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform: LDS destinations stay scalar
-    const int wn = wave % WGN, wm = (wave / WGN) % WGM, kg = wave / (WGN * WGM);
+    const int wn = wave % WGN, wm = wave / WGN;
     const int NT = (a.N + BN_OUT - 1) / BN_OUT;
     int mt_total, mt_per = 0;
     if (RAGGED) {  // routed experts: ragged groups described by device prefix sums
@@ -96,9 +93,22 @@ __global__ __launch_bounds__(WGM* WGN* KG * 64) void grouped_gemm_kernel(GemmArg
     // load geometry of this lane: row inside a 1 KB region, physical chunk slot
     const int ld_row = lane / CPR, ld_p = lane % CPR;
 
-    for (int it = 0;; ++it) {
+    // Coordinates of a tile (wavefront-uniform) and, separately, the issue side: where the
+    // direct-to-LDS loads of the tile whose K steps are being fetched come from.  The two differ at
+    // the end of a tile, when the ring already takes in the next tile's first K steps.
+    struct Tile { int g, row0, nrows, n0; };
+    const bool mapped = RAGGED && a.a_row_map != nullptr;   // token rows gathered by the tile loads
+    const uint16_t* Xi = a.A;
+    const uint16_t* Wi = a.W;
+    // per region this wavefront loads: the lane's global source (row, swizzled chunk) as a byte
+    // offset from the tile's activation rows Xi or the group's weights Wi (one group's matrices
+    // and one activation panel are checked by the launcher to span less than 2^32 bytes)
+    uint32_t goff[RPW];
+
+    // tile number it of this workgroup -> coordinates, Xi / Wi / goff; false past the last tile
+    auto setup_tile = [&](int it, Tile& t) __attribute__((always_inline)) -> bool {
         const int L = (it * 8 + xcd) * per_xcd + slot;
-        if (L >= total) break;
+        if (L >= total) return false;
         // tile id -> (group, row tile, column tile): inside a group the row tiles are taken in bands
         // of kBand; inside a band the row tile runs fastest, then the column tile.  A run of 32
         // consecutive ids (one XCD's share) then covers about kBand row panels x 32/kBand
@@ -134,214 +144,173 @@ __global__ __launch_bounds__(WGM* WGN* KG * 64) void grouped_gemm_kernel(GemmArg
             row0 = mi * BM;
             nrows = min(BM, a.dense_rows - row0);
         }
-        // the tile's coordinates came through LDS; telling the compiler they are wavefront-uniform
-        // keeps base addresses in scalar registers and leaves the lanes 32-bit offsets only
-        g = __builtin_amdgcn_readfirstlane(g);
-        row0 = __builtin_amdgcn_readfirstlane(row0);
-        nrows = __builtin_amdgcn_readfirstlane(nrows);
-        const int n0 = __builtin_amdgcn_readfirstlane(ni * BN_OUT);
-        const uint16_t* Wg = a.W + (size_t)g * a.w_group_stride;
-        const bool mapped = RAGGED && a.a_row_map != nullptr;   // token rows gathered by the tile loads
-        const uint16_t* Xg = mapped ? a.A : a.A + (size_t)row0 * a.lda;
-
-        // per region this wavefront loads: the lane's global source (row, swizzled chunk) as a byte
-        // offset from the tile's activation rows Xg or the group's weights Wg (one group's matrices
-        // and one activation panel are checked by the launcher to span less than 2^32 bytes)
-        uint32_t goff[RPW];
+        // the coordinates came through LDS; telling the compiler they are wavefront-uniform keeps
+        // base addresses in scalar registers and leaves the lanes 32-bit offsets only
+        t.g = __builtin_amdgcn_readfirstlane(g);
+        t.row0 = __builtin_amdgcn_readfirstlane(row0);
+        t.nrows = __builtin_amdgcn_readfirstlane(nrows);
+        t.n0 = __builtin_amdgcn_readfirstlane(ni * BN_OUT);
+        Wi = a.W + (size_t)t.g * a.w_group_stride;
+        Xi = mapped ? a.A : a.A + (size_t)t.row0 * a.lda;
 #pragma unroll
         for (int i = 0; i < RPW; ++i) {
             const int j = wave + NW * i;                 // region index inside a stage
             const int r = j * RPR + ld_row;              // row in the stacked [activations; weights] tile
             const int c = ld_p ^ ((r / RP) % CPR);       // logical chunk stored at physical slot ld_p
             if (i < XRPW) {
-                int rr = min(r, nrows - 1);              // rows past the end re-read the last valid row
-                if (mapped) rr = a.a_row_map[row0 + rr] / a.a_row_div;
+                int rr = min(r, t.nrows - 1);            // rows past the end re-read the last valid row
+                if (mapped) rr = a.a_row_map[t.row0 + rr] / a.a_row_div;
                 goff[i] = ((uint32_t)rr * (uint32_t)a.lda + c * 8) * 2u;
             } else {
                 const int jw = r - BM;                   // row of the weight tile
                 int n;
                 uint32_t base = 0;
                 if (SWIGLU) {
-                    if (jw < BN / 2) n = n0 + jw; else { n = n0 + jw - BN / 2; base = (uint32_t)a.w_up_offset; }
+                    if (jw < BN / 2) n = t.n0 + jw; else { n = t.n0 + jw - BN / 2; base = (uint32_t)a.w_up_offset; }
                 } else {
-                    n = n0 + jw;
+                    n = t.n0 + jw;
                 }
                 n = min(n, a.N - 1);
                 goff[i] = (base + (uint32_t)n * (uint32_t)a.ldw + c * 8) * 2u;
             }
         }
+        return true;
+    };
 
-        f32x16_t acc[MB][NB];
+    // first LDS row of accumulator column block nb of this wavefront (stacked tile coordinates)
+    auto w_row_base = [&](int nb) -> int {
+        if (SWIGLU) return BM + ((nb < NB / 2) ? wn * (Cfg::WTN / 2) + nb * 32
+                                               : BN / 2 + wn * (Cfg::WTN / 2) + (nb - NB / 2) * 32);
+        return BM + wn * Cfg::WTN + nb * 32;
+    };
+    f32x16_t acc[MB][NB];
+    bf16x8_t xf[2][MB], wf[2][NB];
+    // one LDS fragment read from ring slot base sT_: index f < MB is an activation block,
+    // f >= MB a weight block
+#define MOE_EP_FRAG1(sT_, kk_, set_, f_)                                                          \
+    {                                                                                             \
+        const int csw_ = ((kk_) * 2 + fr_kh) ^ fr_sw;                                             \
+        if ((f_) < MB) xf[set_][(f_) < MB ? (f_) : 0] = __builtin_bit_cast(bf16x8_t,              \
+            (sT_)[(wm * Cfg::WTM + (f_) * 32 + fr_row) * CPR + csw_]);                            \
+        else wf[set_][(f_) >= MB ? (f_) - MB : 0] = __builtin_bit_cast(bf16x8_t,                  \
+            (sT_)[(w_row_base((f_) >= MB ? (f_) - MB : 0) + fr_row) * CPR + csw_]);               \
+    }
+    // one direct-to-LDS load of the issue-side tile: region i of this wavefront, K step ks_, ring slot stage_
+#define MOE_EP_ISSUE1(ks_, stage_, i_)                                                            \
+    {                                                                                             \
+        const int k_ = (ks_) * BK;                                                                \
+        const int seg_ = k_ / a.kseg_len;                                                         \
+        const size_t wk_ = (size_t)seg_ * a.w_kseg_stride + (k_ - seg_ * a.kseg_len);             \
+        uint4* dst_ = lds + (stage_) * Cfg::STAGE_CHUNKS + wave * 64 + NW * 64 * (i_);            \
+        __builtin_amdgcn_global_load_lds(                                                         \
+            reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(                         \
+                (i_) < XRPW ? Xi + k_ : Wi + wk_) + goff[i_]),                                    \
+            dst_, 16, 0, 0);                                                                      \
+    }
+#define SB() __builtin_amdgcn_sched_barrier(0)
+    // The hand-over of a ring slot to the MFMAs: this wavefront's loads into it have landed (all
+    // but the newest pending_ loads), its own LDS reads of older slots have returned, and after
+    // the barrier the same holds for every wavefront, so the slot may be read and the slot read
+    // before it may be refilled.
+#define MOE_EP_HANDOVER(pending_)                                                                 \
+    {                                                                                             \
+        MOE_EP_WAIT_VMCNT_LGKM0(pending_);                                                        \
+        __builtin_amdgcn_s_barrier();                                                             \
+        asm volatile("" ::: "memory");                                                            \
+    }
+    // One K step.  The source order below is the issue order: sched_barrier(0) after every MFMA
+    // keeps the compiler from regrouping.  A K step is KKW k16 steps; k16 step i works out of
+    // fragment set i & 1 while the LDS reads
+    // of step i+1 and the global loads of K step ks_ of the issue-side tile (STAGES-1 K steps
+    // ahead in the ring) are slipped between its MFMAs.  The fragments of a K step's first k16
+    // step are read during the LAST k16 step of the K step before it: the hand-over of the next
+    // ring slot sits in front of those MFMAs (next_pending_ = loads that may still be in flight
+    // then; has_next_ = false when nothing follows in the ring), so the LDS latency after a
+    // barrier hides behind MB*NB MFMAs.  Fragment reads are ordered so that the first MFMA needs
+    // only the first two.
+#define MOE_EP_FRAG_ORDER(f_) ((f_) == 0 ? MB : (f_) <= MB ? (f_) - 1 : (f_))
+#define MOE_EP_STEP(ks_, issue_, has_next_, next_pending_) MOE_EP_STEP5(ks_, issue_, has_next_, has_next_, next_pending_)
+#define MOE_EP_STEP5(ks_, issue_, handover_, prefetch_, next_pending_)                            \
+    {                                                                                             \
+        const uint4* sT = lds + stage * Cfg::STAGE_CHUNKS;                                        \
+        const int st_next = stage == STAGES - 1 ? 0 : stage + 1;                                  \
+        const uint4* sN = lds + st_next * Cfg::STAGE_CHUNKS;                                      \
+        const int st2 = stage == 0 ? STAGES - 1 : stage - 1;                                      \
+        _Pragma("unroll") for (int i = 0; i < KKW; ++i) {                                         \
+            if (i == KKW - 1 && (handover_)) MOE_EP_HANDOVER(next_pending_)                       \
+            _Pragma("unroll") for (int q = 0; q < MB * NB; ++q) {                                 \
+                const int nb = q / MB, mb = q % MB;                                               \
+                acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[i & 1][nb], xf[i & 1][mb], acc[mb][nb], 0, 0, 0); \
+                _Pragma("unroll") for (int f = q; f < MB + NB; f += MB * NB) {                    \
+                    if (i + 1 < KKW) MOE_EP_FRAG1(sT, i + 1, (i + 1) & 1, MOE_EP_FRAG_ORDER(f)) \
+                    else if (prefetch_) MOE_EP_FRAG1(sN, 0, 0, MOE_EP_FRAG_ORDER(f))       \
+                }                                                                                 \
+                if ((issue_) && i + 1 < KKW) {  /* all loads go out before the hand-over */       \
+                    _Pragma("unroll") for (int l = i * MB * NB + q; l < RPW; l += (KKW - 1) * MB * NB) \
+                        MOE_EP_ISSUE1(ks_, st2, l)                                                \
+                }                                                                                 \
+                SB();                                                                             \
+            }                                                                                     \
+        }                                                                                         \
+        stage = st_next;                                                                          \
+    }
+    // the first STAGES-1 K steps of the issue-side tile go in flight, K step p into ring slot stage+p
+#define MOE_EP_PROLOGUE()                                                                         \
+    _Pragma("unroll") for (int p = 0; p < STAGES - 1; ++p)                                        \
+        if (p < KT) {                                                                             \
+            const int sp_ = stage + p >= STAGES ? stage + p - STAGES : stage + p;                 \
+            _Pragma("unroll") for (int i = 0; i < RPW; ++i) MOE_EP_ISSUE1(p, sp_, i)              \
+        }
+
+    Tile cur;
+    if (!setup_tile(0, cur)) return;
+    // The ring never drains between tiles: when a tile's own K steps are all in flight, the remaining
+    // STAGES-1 steps of its loop fetch the first K steps of the workgroup's next tile and the last
+    // step hands the first of them over, so the epilogue's stores overlap the next tile's loads.
+    // After the last tile the same steps re-fetch that tile's own first K steps (the issue side simply
+    // stays where it is): a few wasted loads at the very end keep every step of the loop alike.  The
+    // launcher guarantees KT >= STAGES-1.
+    int stage = 0;
+    MOE_EP_PROLOGUE()
+    MOE_EP_HANDOVER((STAGES - 2) * RPW)
+    for (int it = 0;; ++it) {
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[mb][nb][r] = 0.f;
-
-        // first LDS row of accumulator column block nb of this wavefront (stacked tile coordinates)
-        auto w_row_base = [&](int nb) -> int {
-            if (SWIGLU) return BM + ((nb < NB / 2) ? wn * (Cfg::WTN / 2) + nb * 32
-                                                   : BN / 2 + wn * (Cfg::WTN / 2) + (nb - NB / 2) * 32);
-            return BM + wn * Cfg::WTN + nb * 32;
-        };
-        bf16x8_t xf[2][MB], wf[2][NB];
-        // one LDS fragment read from ring slot base sT_: index f < MB is an activation block,
-        // f >= MB a weight block
-#define MOE_EP_FRAG1(sT_, kk_, set_, f_)                                                          \
-        {                                                                                         \
-            const int csw_ = ((kk_) * 2 + fr_kh) ^ fr_sw;                                         \
-            if ((f_) < MB) xf[set_][(f_) < MB ? (f_) : 0] = __builtin_bit_cast(bf16x8_t,          \
-                (sT_)[(wm * Cfg::WTM + (f_) * 32 + fr_row) * CPR + csw_]);                        \
-            else wf[set_][(f_) >= MB ? (f_) - MB : 0] = __builtin_bit_cast(bf16x8_t,              \
-                (sT_)[(w_row_base((f_) >= MB ? (f_) - MB : 0) + fr_row) * CPR + csw_]);           \
-        }
-        // one direct-to-LDS load: region i of this wavefront, K step kt_, ring slot stage_
-#define MOE_EP_ISSUE1(kt_, stage_, i_)                                                            \
-        {                                                                                         \
-            const int k_ = (kt_) * BK;                                                            \
-            const int seg_ = k_ / a.kseg_len;                                                     \
-            const size_t wk_ = (size_t)seg_ * a.w_kseg_stride + (k_ - seg_ * a.kseg_len);         \
-            uint4* dst_ = lds + (stage_) * Cfg::STAGE_CHUNKS + wave * 64 + NW * 64 * (i_);        \
-            __builtin_amdgcn_global_load_lds(                                                     \
-                reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(                     \
-                    (i_) < XRPW ? Xg + k_ : Wg + wk_) + goff[i_]),                                \
-                dst_, 16, 0, 0);                                                                  \
-        }
-#define SB() __builtin_amdgcn_sched_barrier(0)
-        // The hand-over of ring slot `slot_` to the MFMAs: this wavefront's loads into it have landed
-        // (all but the newest pending_ loads), its own LDS reads of older slots have returned, and
-        // after the barrier the same holds for every wavefront, so the slot may be read and the
-        // slot read before it may be refilled.
-#define MOE_EP_HANDOVER(pending_)                                                                 \
-        {                                                                                         \
-            MOE_EP_WAIT_VMCNT_LGKM0(pending_);                                                    \
-            __builtin_amdgcn_s_barrier();                                                         \
-            asm volatile("" ::: "memory");                                                        \
-        }
-        // One K step.  The source order below is the issue order: sched_barrier(0) after every
-        // MFMA keeps the compiler from regrouping.  This wavefront multiplies k16 steps
-        // kg*KKW .. kg*KKW+KKW-1 of the K step; k16 step i works out of fragment set i & 1 while
-        // the LDS reads of step i+1 and the global loads STAGES-1 K steps ahead are slipped between
-        // its MFMAs.  The fragments of a K step's first k16 step are read during the LAST k16
-        // step of the K step before it: the hand-over of the next ring slot sits in front of those
-        // MFMAs (next_pending_ = loads that may still be in flight then; has_next_ = false for the
-        // tile's last K step), so the LDS latency after a barrier hides behind MB*NB MFMAs.
-        // Fragment reads are ordered so that the first MFMA needs only the first two.
-#define MOE_EP_FRAG_ORDER(f_) ((f_) == 0 ? MB : (f_) <= MB ? (f_) - 1 : (f_))
-#define MOE_EP_STEP(kt_, issue_, has_next_, next_pending_)                                        \
-        {                                                                                         \
-            const uint4* sT = lds + stage * Cfg::STAGE_CHUNKS;                                    \
-            const int st_next = stage == STAGES - 1 ? 0 : stage + 1;                              \
-            const uint4* sN = lds + st_next * Cfg::STAGE_CHUNKS;                                  \
-            const int st2 = stage == 0 ? STAGES - 1 : stage - 1;                                  \
-            _Pragma("unroll") for (int i = 0; i < KKW; ++i) {                                     \
-                if (i == KKW - 1 && (has_next_)) MOE_EP_HANDOVER(next_pending_)                   \
-                _Pragma("unroll") for (int q = 0; q < MB * NB; ++q) {                             \
-                    const int nb = q / MB, mb = q % MB;                                           \
-                    acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[i & 1][nb], xf[i & 1][mb], acc[mb][nb], 0, 0, 0); \
-                    _Pragma("unroll") for (int f = q; f < MB + NB; f += MB * NB) {                \
-                        if (i + 1 < KKW) MOE_EP_FRAG1(sT, kg * KKW + i + 1, (i + 1) & 1, MOE_EP_FRAG_ORDER(f)) \
-                        else if (has_next_) MOE_EP_FRAG1(sN, kg * KKW, 0, MOE_EP_FRAG_ORDER(f))   \
-                    }                                                                             \
-                    if ((issue_) && i + 1 < KKW) {  /* all loads go out before the hand-over */   \
-                        _Pragma("unroll") for (int l = i * MB * NB + q; l < RPW; l += (KKW - 1) * MB * NB) \
-                            MOE_EP_ISSUE1((kt_) + STAGES - 1, st2, l)                             \
-                    }                                                                             \
-                    SB();                                                                         \
-                }                                                                                 \
-            }                                                                                     \
-            stage = st_next;                                                                      \
-        }
-
-        // prologue: the first STAGES-1 K steps go in flight, the first one is handed over and its
-        // first fragments are read
+        {   // the tile's first K step has been handed over: its first fragments
+            const uint4* s0 = lds + stage * Cfg::STAGE_CHUNKS;
 #pragma unroll
-        for (int p = 0; p < STAGES - 1; ++p)
-            if (p < KT) {
-#pragma unroll
-                for (int i = 0; i < RPW; ++i) MOE_EP_ISSUE1(p, p, i)
-            }
-        {
-            const int ahead = min(STAGES - 2, KT - 1);  // K steps in flight behind the first
-            if (STAGES >= 5 && ahead == 3) MOE_EP_HANDOVER(3 * RPW)
-            else if (STAGES >= 4 && ahead == 2) MOE_EP_HANDOVER(2 * RPW)
-            else if (STAGES >= 3 && ahead == 1) MOE_EP_HANDOVER(1 * RPW)
-            else MOE_EP_HANDOVER(0)
-#pragma unroll
-            for (int f = 0; f < MB + NB; ++f) MOE_EP_FRAG1(lds, kg * KKW, 0, MOE_EP_FRAG_ORDER(f))
+            for (int f = 0; f < MB + NB; ++f) MOE_EP_FRAG1(s0, 0, 0, MOE_EP_FRAG_ORDER(f))
             SB();
         }
-        int stage = 0;
         int kt = 0;
         // K step kt hands over K step kt+1, behind which STAGES-2 more are in flight
-        for (; kt + STAGES - 1 < KT; ++kt) MOE_EP_STEP(kt, true, true, (STAGES - 2) * RPW)
-        // tail: no more loads to issue; the step that leaves p K steps to go runs if KT > p
-        if constexpr (STAGES >= 5) { if (KT >= 4) MOE_EP_STEP(kt, false, true, 2 * RPW) }
-        if constexpr (STAGES >= 4) { if (KT >= 3) MOE_EP_STEP(kt, false, true, 1 * RPW) }
-        if constexpr (STAGES >= 3) { if (KT >= 2) MOE_EP_STEP(kt, false, true, 0) }
-        MOE_EP_STEP(kt, false, false, 0)
-#undef MOE_EP_HANDOVER
-#undef MOE_EP_STEP
-#undef MOE_EP_FRAG_ORDER
-#undef SB
-#undef MOE_EP_ISSUE1
-#undef MOE_EP_FRAG1
-        asm volatile("" ::: "memory");
-        __builtin_amdgcn_s_barrier();  // every wavefront is done reading the ring
-        // K split: the two wavefronts that share an output block swap halves of their partial
-        // sums through LDS (lane-major, so both sides index identically) and each finishes one half.
-        int mb_lo = 0, mb_hi = MB;
-        if constexpr (KG == 2) {
-            constexpr int HB = (MB / 2) * NB;                 // blocks given away
-            const int give_lo = kg == 0 ? MB / 2 : 0;         // first row block given away
-            mb_lo = kg == 0 ? 0 : MB / 2; mb_hi = mb_lo + MB / 2;
-            f32x4_t* ex = reinterpret_cast<f32x4_t*>(lds);
-#pragma unroll
-            for (int mbb = 0; mbb < MB / 2; ++mbb)
-#pragma unroll
-                for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        f32x4_t v;
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) v[i] = kg == 0 ? acc[MB / 2 + mbb][nb][q * 4 + i] : acc[mbb][nb][q * 4 + i];
-                        ex[((wave * HB + mbb * NB + nb) * 4 + q) * 64 + lane] = v;
-                    }
-            (void)give_lo;
-            __syncthreads();
-            const int partner = wave < WGN * WGM ? wave + WGN * WGM : wave - WGN * WGM;
-#pragma unroll
-            for (int mbb = 0; mbb < MB / 2; ++mbb)
-#pragma unroll
-                for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        const f32x4_t v = ex[((partner * HB + mbb * NB + nb) * 4 + q) * 64 + lane];
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) {
-                            if (kg == 0) acc[mbb][nb][q * 4 + i] += v[i];
-                            else acc[MB / 2 + mbb][nb][q * 4 + i] += v[i];
-                        }
-                    }
-            __syncthreads();  // the next tile's first loads overwrite the exchange area
-        }
+        for (; kt + STAGES - 1 < KT; ++kt) MOE_EP_STEP(kt + STAGES - 1, true, true, (STAGES - 2) * RPW)
+        // the tile's own loads are all out: the issue side moves on to the next tile
+        Tile nxt;
+        const bool has_nxt = setup_tile(it + 1, nxt);
+        for (; kt + 1 < KT; ++kt) MOE_EP_STEP(kt + STAGES - 1 - KT, true, true, (STAGES - 2) * RPW)
+        // the last step hands the next tile's first K step over (no store is in flight yet, so the
+        // load count is exact); its fragments are read after the epilogue
+        MOE_EP_STEP5(kt + STAGES - 1 - KT, true, true, false, (STAGES - 2) * RPW)
 
         // epilogue: lane holds token row (lane & 31) of each block and, per register quad q,
         // output columns 8q + 4*(lane >> 5) + {0..3} of the block
-        uint16_t* Cg = a.C + (size_t)g * a.c_group_col_stride;
+        uint16_t* Cg = a.C + (size_t)cur.g * a.c_group_col_stride;
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) {
-            if (mb < mb_lo || mb >= mb_hi) continue;
             const int m = wm * Cfg::WTM + mb * 32 + fr_row;
-            if (m >= nrows) continue;
-            uint16_t* crow = Cg + (size_t)(row0 + m) * a.ldc;
+            if (m >= cur.nrows) continue;
+            uint16_t* crow = Cg + (size_t)(cur.row0 + m) * a.ldc;
             if (SWIGLU) {
 #pragma unroll
                 for (int nb = 0; nb < NB / 2; ++nb)
 #pragma unroll
                     for (int q = 0; q < 4; ++q) {
-                        const int n = n0 + wn * (Cfg::WTN / 2) + nb * 32 + q * 8 + fr_kh * 4;
+                        const int n = cur.n0 + wn * (Cfg::WTN / 2) + nb * 32 + q * 8 + fr_kh * 4;
                         if (n >= a.N) continue;
                         float h[4];
 #pragma unroll
@@ -356,7 +325,7 @@ __global__ __launch_bounds__(WGM* WGN* KG * 64) void grouped_gemm_kernel(GemmArg
                 for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
                     for (int q = 0; q < 4; ++q) {
-                        const int n = n0 + wn * Cfg::WTN + nb * 32 + q * 8 + fr_kh * 4;
+                        const int n = cur.n0 + wn * Cfg::WTN + nb * 32 + q * 8 + fr_kh * 4;
                         if (n >= a.N) continue;
                         uint2 o;
                         o.x = pack_bf16x2(acc[mb][nb][q * 4 + 0], acc[mb][nb][q * 4 + 1]);
@@ -365,13 +334,25 @@ __global__ __launch_bounds__(WGM* WGN* KG * 64) void grouped_gemm_kernel(GemmArg
                     }
             }
         }
+        if (!has_nxt) break;
+        cur = nxt;
     }
+    // loads still on their way write into this workgroup's LDS: they must land before it is given up
+    MOE_EP_WAIT_VMCNT_LGKM0(0);
+#undef MOE_EP_PROLOGUE
+#undef MOE_EP_HANDOVER
+#undef MOE_EP_STEP5
+#undef MOE_EP_STEP
+#undef MOE_EP_FRAG_ORDER
+#undef SB
+#undef MOE_EP_ISSUE1
+#undef MOE_EP_FRAG1
 }
 
-template <int BM, int BN, int BK, int STAGES, int WGM, int WGN, int KG, bool SWIGLU, bool RAGGED>
+template <int BM, int BN, int BK, int STAGES, int WGM, int WGN, bool SWIGLU, bool RAGGED>
 static hipError_t launch_one(const GemmArgs& a, int n_cu, int max_row_tiles, hipStream_t s)
 {
-    using Cfg = GemmCfg<BM, BN, BK, STAGES, WGM, WGN, KG, SWIGLU>;
+    using Cfg = GemmCfg<BM, BN, BK, STAGES, WGM, WGN, SWIGLU>;
     const int NT = (a.N + Cfg::BN_OUT - 1) / Cfg::BN_OUT;
     const long long max_tiles = (long long)max_row_tiles * NT;
     if (max_tiles <= 0) return hipSuccess;
@@ -388,52 +369,54 @@ static hipError_t launch_one(const GemmArgs& a, int n_cu, int max_row_tiles, hip
     long long grid = (long long)n_cu * occ;
     if (grid > max_tiles) grid = max_tiles;
     grid = (grid + 7) / 8 * 8;
-    hipLaunchKernelGGL((grouped_gemm_kernel<BM, BN, BK, STAGES, WGM, WGN, KG, SWIGLU, RAGGED>),
+    hipLaunchKernelGGL((grouped_gemm_kernel<BM, BN, BK, STAGES, WGM, WGN, SWIGLU, RAGGED>),
                        dim3((unsigned)grid), dim3(Cfg::THREADS), Cfg::LDS_BYTES, s, a);
     return hipGetLastError();
 }
 
-template <int BM, int BN, int BK, int STAGES, int WGM, int WGN, int KG>
+template <int BM, int BN, int BK, int STAGES, int WGM, int WGN>
 static hipError_t raise_all()
 {
     hipError_t e;
 #define R(SW, RG)                                                                                       \
     if ((e = hipFuncSetAttribute(                                                                       \
-             reinterpret_cast<const void*>(&grouped_gemm_kernel<BM, BN, BK, STAGES, WGM, WGN, KG, SW, RG>), \
+             reinterpret_cast<const void*>(&grouped_gemm_kernel<BM, BN, BK, STAGES, WGM, WGN, SW, RG>), \
              hipFuncAttributeMaxDynamicSharedMemorySize,                                                \
-             GemmCfg<BM, BN, BK, STAGES, WGM, WGN, KG, SW>::LDS_BYTES)) != hipSuccess) return e;
+             GemmCfg<BM, BN, BK, STAGES, WGM, WGN, SW>::LDS_BYTES)) != hipSuccess) return e;
     R(true, true) R(true, false) R(false, true) R(false, false)
 #undef R
     return hipSuccess;
 }
 
-template <int BM, int BN, int BK, int STAGES, int WGM, int WGN, int KG>
+template <int BM, int BN, int BK, int STAGES, int WGM, int WGN>
 static hipError_t launch_cfg(const GemmArgs& a, bool swiglu, int n_cu, int max_row_tiles, hipStream_t s)
 {
     const bool ragged = a.offset != nullptr;
-    if (swiglu) return ragged ? launch_one<BM, BN, BK, STAGES, WGM, WGN, KG, true, true>(a, n_cu, max_row_tiles, s)
-                              : launch_one<BM, BN, BK, STAGES, WGM, WGN, KG, true, false>(a, n_cu, max_row_tiles, s);
-    return ragged ? launch_one<BM, BN, BK, STAGES, WGM, WGN, KG, false, true>(a, n_cu, max_row_tiles, s)
-                  : launch_one<BM, BN, BK, STAGES, WGM, WGN, KG, false, false>(a, n_cu, max_row_tiles, s);
+    if (swiglu) return ragged ? launch_one<BM, BN, BK, STAGES, WGM, WGN, true, true>(a, n_cu, max_row_tiles, s)
+                              : launch_one<BM, BN, BK, STAGES, WGM, WGN, true, false>(a, n_cu, max_row_tiles, s);
+    return ragged ? launch_one<BM, BN, BK, STAGES, WGM, WGN, false, true>(a, n_cu, max_row_tiles, s)
+                  : launch_one<BM, BN, BK, STAGES, WGM, WGN, false, false>(a, n_cu, max_row_tiles, s);
 }
 
-// tile variants: id, BM, BN, BK, ring stages, wavefronts in m, in n, K-split groups
-// (7: short row tiles; with exactly 16 rows per expert it streams the weights 13 % faster than the
-// 128-row tiles, with the ragged counts of real routing it does not, so nothing selects it by default)
+// tile variants: id, BM, BN, BK, ring slots, wavefronts in m, in n
+// (0 and 7: short row tiles; with exactly 16 rows per expert they stream the weights 13 % faster than
+// the 128-row tiles, with the ragged counts of real routing they do not, so nothing selects them by
+// default).  A ring of S slots needs K >= (S-1) * BK; for a shorter K the launcher takes the
+// two-slot variant with the same row tile, listed in the last column.
 #define MOE_EP_VARIANTS(X)         \
-    X(0, 128, 256, 64, 3, 1, 2, 2) \
-    X(1, 128, 256, 64, 3, 2, 2, 1) \
-    X(2, 256, 256, 64, 2, 2, 2, 1) \
-    X(3, 256, 256, 32, 4, 2, 2, 1) \
-    X(4, 128, 128, 64, 2, 2, 2, 1) \
-    X(5, 128, 256, 32, 3, 2, 2, 1) \
-    X(6, 128, 256, 32, 2, 2, 2, 1) \
-    X(7, 64, 128, 64, 3, 1, 2, 1)
+    X(0, 64, 128, 64, 2, 1, 2, 0)  \
+    X(1, 128, 256, 64, 3, 2, 2, 4) \
+    X(2, 256, 256, 64, 2, 2, 2, 2) \
+    X(3, 256, 256, 32, 4, 2, 2, 2) \
+    X(4, 128, 128, 64, 2, 2, 2, 4) \
+    X(5, 128, 256, 32, 3, 2, 2, 6) \
+    X(6, 128, 256, 32, 2, 2, 2, 6) \
+    X(7, 64, 128, 64, 3, 1, 2, 0)
 
 hipError_t grouped_gemm_init()
 {
     hipError_t e;
-#define X(id, BM, BN, BK, ST, WGM, WGN, KG) if ((e = raise_all<BM, BN, BK, ST, WGM, WGN, KG>()) != hipSuccess) return e;
+#define X(id, BM, BN, BK, ST, WGM, WGN, FB) if ((e = raise_all<BM, BN, BK, ST, WGM, WGN>()) != hipSuccess) return e;
     MOE_EP_VARIANTS(X)
 #undef X
     return hipSuccess;
@@ -442,7 +425,7 @@ hipError_t grouped_gemm_init()
 int grouped_gemm_row_tile(int variant)
 {
     switch (variant) {
-#define X(id, BM, BN, BK, ST, WGM, WGN, KG) case id: return BM;
+#define X(id, BM, BN, BK, ST, WGM, WGN, FB) case id: return BM;
         MOE_EP_VARIANTS(X)
 #undef X
         default: return 128;
@@ -452,11 +435,15 @@ int grouped_gemm_row_tile(int variant)
 hipError_t launch_grouped_gemm(const GemmArgs& a, bool swiglu, int variant, int n_cu,
                                int max_row_tiles, hipStream_t s)
 {
+    if (a.K < 64 || a.K % 64) return hipErrorInvalidValue;
     switch (variant) {
-#define X(id, BM, BN, BK, ST, WGM, WGN, KG) case id: return launch_cfg<BM, BN, BK, ST, WGM, WGN, KG>(a, swiglu, n_cu, max_row_tiles, s);
+#define X(id, BM, BN, BK, ST, WGM, WGN, FB)                                                          \
+        case id:                                                                                    \
+            if (a.K / BK < ST - 1) return launch_grouped_gemm(a, swiglu, FB, n_cu, max_row_tiles, s); \
+            return launch_cfg<BM, BN, BK, ST, WGM, WGN>(a, swiglu, n_cu, max_row_tiles, s);
         MOE_EP_VARIANTS(X)
 #undef X
-        default: return launch_cfg<128, 256, 64, 3, 1, 2, 2>(a, swiglu, n_cu, max_row_tiles, s);
+        default: return hipErrorInvalidValue;
     }
 }
 
