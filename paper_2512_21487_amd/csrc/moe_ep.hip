@@ -32,6 +32,8 @@ struct moe_ep_ctx {
     int gemm_variant = 1;    // routed experts: 128-row tiles keep the padding of ragged groups small
     int shared_variant = 2;  // shared experts: dense rows, 256-row tiles
     bool fused_gather = true;  // the gate/up projection gathers the token rows itself (no grouped copy)
+    int link_grid = 8;         // workgroups of a host-link copy kernel
+    bool memcpy_in = false, memcpy_out = false;  // host-link copies through the runtime instead of kernels
     // device workspaces
     void* d_tokens = nullptr; float* d_logits = nullptr; void* d_out = nullptr;  // pinned-host mode staging
     int32_t* idx = nullptr; float* w = nullptr; int32_t* pos = nullptr; int32_t* perm = nullptr;
@@ -224,6 +226,16 @@ int moe_ep_create(const moe_ep_config* cfg, moe_ep_ctx** out_ctx)
     // tile-shape overrides for tuning (indices into the variant table of grouped_gemm.hip)
     if (const char* v = getenv("MOE_EP_GEMM_VARIANT")) ctx->gemm_variant = atoi(v);
     if (const char* v = getenv("MOE_EP_SHARED_VARIANT")) ctx->shared_variant = atoi(v);
+    // workgroups of a copy kernel: ~128 KB in flight fills the host link; more only queues up in the
+    // memory fabric in front of the compute kernels
+    if (const char* v = getenv("MOE_EP_LINK_GRID")) ctx->link_grid = atoi(v) > 0 ? atoi(v) : 8;
+    // MOE_EP_LINK_MEMCPY = 1 | in | out: the runtime's asynchronous copies (DMA engines) instead of copy
+    // kernels in both / one direction, kept for comparison: inbound they overlap cleanly with compute,
+    // but each call costs the host thread 0.2-0.3 ms on this system
+    if (const char* v = getenv("MOE_EP_LINK_MEMCPY")) {
+        ctx->memcpy_in = v[0] == '1' || v[0] == 'i';
+        ctx->memcpy_out = v[0] == '1' || v[0] == 'o';
+    }
     ctx->fused_gather = fused_gather_enabled();
     if (grouped_gemm_init() != hipSuccess) { delete ctx; return MOE_EP_EHIP; }
 
@@ -410,20 +422,12 @@ int moe_ep_forward(moe_ep_ctx* ctx, const void* tokens, const float* gate_logits
         h_tokens = static_cast<const char*>(dev[0]); h_logits = static_cast<const char*>(dev[1]);
         h_out = static_cast<char*>(dev[2]);
     }
-    // workgroups of a copy kernel: ~128 KB in flight fills the host link; more only queues up in the
-    // memory fabric in front of the other streams' kernels (measured: they ran 3-10x slower)
-    // MOE_EP_LINK_MEMCPY: the runtime's asynchronous copies (DMA engines) instead of copy kernels, kept
-    // for comparison: they overlap with compute but move 35 GB/s against 55 and cost 0.3 ms of host
-    // time per call on this system
-    const char* link_env = getenv("MOE_EP_LINK_MEMCPY");   // "1" both directions, "in" / "out" one
-    const bool memcpy_in = link_env && (link_env[0] == '1' || link_env[0] == 'i');
-    const bool memcpy_out = link_env && (link_env[0] == '1' || link_env[0] == 'o');
     auto link_copy = [&](void* dst, const void* src, size_t bytes, int grid, hipStream_t st) -> hipError_t {
-        if (st == s_in ? memcpy_in : memcpy_out) return bytes ? hipMemcpyAsync(dst, src, bytes, hipMemcpyDefault, st) : hipSuccess;
+        if (st == s_in ? ctx->memcpy_in : ctx->memcpy_out)
+            return bytes ? hipMemcpyAsync(dst, src, bytes, hipMemcpyDefault, st) : hipSuccess;
         return launch_copy(dst, src, bytes, grid, st);
     };
-    int link_grid = 8;
-    if (const char* v = getenv("MOE_EP_LINK_GRID")) link_grid = atoi(v) > 0 ? atoi(v) : 8;
+    const int link_grid = ctx->link_grid;
     const int span_total = prof_begin(ctx, prof, ST_TOTAL, user);
     if (pinned) {
         HIP_TRY(ctx, hipEventRecord(ctx->ev_start, user));
