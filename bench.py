@@ -175,6 +175,7 @@ def main() -> int:
     routing = [ctx.get_routing(c) for c in range(args.r)]
     kept = sum(int(rt["offset"][-1]) for rt in routing)
     tokens_with_kept = sum(int((rt["pos"] >= 0).any(axis=1).sum()) for rt in routing)
+    load = np.sum([rt["count"] for rt in routing], axis=0)   # realised rows per local expert
     ms_per_step = dt / args.steps * 1e3
     value = T * args.steps / dt
 
@@ -225,7 +226,9 @@ def main() -> int:
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{wl.name}: T={T} M={M} H={H} E={wl.n_experts} local={wl.n_local} "
                                f"top_k={k} shared={Ns}x{Hs} io={'pinned_host' if pinned else 'device'}",
-                   "r_chunks": args.r, "order": args.order, "kept_assignments": kept},
+                   "r_chunks": args.r, "order": args.order, "kept_assignments": kept,
+                   "expert_load": {"max": int(load.max()), "mean": float(load.mean()), "min": int(load.min()),
+                                   "empty": int((load == 0).sum())}},
         "grouped_gemm_pct_of_bf16_mfma_peak": None if routed_line is None else 100.0 * routed_line["frac"],
         "roofline": roof,
         "kernels": kernels,

@@ -294,6 +294,42 @@ def test_device_mode_forward_can_be_captured_in_a_graph():
     ctx.destroy()
 
 
+_DIGEST_SCRIPT = r"""
+import hashlib, sys
+sys.path.insert(0, {tests!r}); sys.path.insert(0, {root!r})
+import gpu_util as g
+from workloads import make_inputs, tiny_workload
+wl = tiny_workload(name="serial", n_tokens=700, hidden=256, inter=192, n_experts=16, local_begin=4, n_local=8,
+                   top_k=4, n_shared=1, shared_inter=128)
+inp = make_inputs(wl, seed=36)
+for pinned in (False, True):
+    ctx = g.make_ctx(wl, pinned=pinned)
+    d = g.DeviceInputs(wl, inp, pinned=pinned)
+    for r, order in ((1, 0), (4, 1)):
+        out = g.run_forward(ctx, wl, d, r=r, order=order)
+        print(hashlib.sha256(out.tobytes()).hexdigest())
+    ctx.destroy()
+"""
+
+
+def test_serialised_launches_give_the_same_bits():
+    """The event graph between the three streams is the race surface: with every launch made
+    blocking (HIP_LAUNCH_BLOCKING=1, AMD_SERIALIZE_KERNEL=3) the outputs must be the bits of the
+    asynchronous run, in device and pinned-host mode, chunked and not."""
+    import subprocess
+    import sys
+    here = os.path.dirname(os.path.abspath(__file__))
+    script = _DIGEST_SCRIPT.format(tests=here, root=os.path.dirname(here))
+    digests = []
+    for extra in ({}, {"HIP_LAUNCH_BLOCKING": "1", "AMD_SERIALIZE_KERNEL": "3"}):
+        env = dict(os.environ, **extra)
+        p = subprocess.run([sys.executable, "-c", script], capture_output=True, text=True, env=env, timeout=300)
+        assert p.returncode == 0, p.stderr[-2000:]
+        digests.append([l for l in p.stdout.split() if len(l) == 64])
+    assert len(digests[0]) == 4 and digests[0] == digests[1]
+    assert len(set(digests[0])) == 1  # and chunking, order and I/O mode change nothing either
+
+
 def test_measured_timeline_obeys_the_precedence_rules():
     """The measured schedule of a pinned-host forward with r_2 = 3 (moe_ep_get_timeline): every stage
     appears once per chunk, a chunk's compute starts after its inbound copy ends and its outbound copy
