@@ -27,22 +27,38 @@ __global__ __launch_bounds__(256) void combine_kernel(
         // slot keeps it as it is
         if (accumulate && __ballot(my_pos >= 0) == 0ull) continue;
         // the column loop runs the same number of times in every lane: the slot broadcasts below
-        // read lanes 0..k-1, which must not have left the loop when a row is shorter than 64 chunks
-        for (int c0 = 0; c0 < M8; c0 += 64) {
-            const int c = c0 + lane;
-            const bool in_row = c < M8;
-            float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        // read lanes 0..k-1, which must not have left the loop when a row is shorter than a trip
+        for (int c0 = 0; c0 < M8; c0 += 128) {
+            // two 16-byte column chunks per lane and trip: twice the loads in flight
+            const int ca = c0 + lane, cb = c0 + 64 + lane;
+            const bool in_a = ca < M8, in_b = cb < M8;
+            float acc_a[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+            float acc_b[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
             for (int s = 0; s < k; ++s) {
                 const int p = __shfl(my_pos, s, 64);  // uniform over the wavefront
                 const float ws = __shfl(my_w, s, 64);
-                if (p >= 0 && in_row) fma8(acc, ws, y[(size_t)p * M8 + c]);
+                if (p >= 0) {
+                    uint4 va, vb;
+                    if (in_a) va = y[(size_t)p * M8 + ca];
+                    if (in_b) vb = y[(size_t)p * M8 + cb];
+                    if (in_a) fma8(acc_a, ws, va);
+                    if (in_b) fma8(acc_b, ws, vb);
+                }
             }
-            if (!in_row) continue;
-            if (accumulate) fma8(acc, 1.0f, out[(size_t)t * M8 + c]);
-            uint4 o;
-            o.x = pack_bf16x2(acc[0], acc[1]); o.y = pack_bf16x2(acc[2], acc[3]);
-            o.z = pack_bf16x2(acc[4], acc[5]); o.w = pack_bf16x2(acc[6], acc[7]);
-            out[(size_t)t * M8 + c] = o;
+            if (in_a) {
+                if (accumulate) fma8(acc_a, 1.0f, out[(size_t)t * M8 + ca]);
+                uint4 o;
+                o.x = pack_bf16x2(acc_a[0], acc_a[1]); o.y = pack_bf16x2(acc_a[2], acc_a[3]);
+                o.z = pack_bf16x2(acc_a[4], acc_a[5]); o.w = pack_bf16x2(acc_a[6], acc_a[7]);
+                out[(size_t)t * M8 + ca] = o;
+            }
+            if (in_b) {
+                if (accumulate) fma8(acc_b, 1.0f, out[(size_t)t * M8 + cb]);
+                uint4 o;
+                o.x = pack_bf16x2(acc_b[0], acc_b[1]); o.y = pack_bf16x2(acc_b[2], acc_b[3]);
+                o.z = pack_bf16x2(acc_b[4], acc_b[5]); o.w = pack_bf16x2(acc_b[6], acc_b[7]);
+                out[(size_t)t * M8 + cb] = o;
+            }
         }
     }
 }
