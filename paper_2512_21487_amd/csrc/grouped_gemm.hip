@@ -25,6 +25,8 @@
 // SwiGLU: the weight tile holds BN/2 rows of W_gate and the matching BN/2 rows of W_up; a
 // wavefront's accumulator blocks pair a gate block with the up block of the same columns,
 // so act = silu(z_gate) * z_up is formed in registers and only act is written.
+#include <type_traits>
+
 #include "common.h"
 #include "kernels.h"
 
@@ -52,9 +54,34 @@ struct GemmCfg {
     static_assert((BM / RPR) % NW == 0 && (BN / RPR) % NW == 0, "regions split evenly over wavefronts");
     static_assert(STAGES >= 2 && STAGES <= 5 && (STAGES - 2) * RPW <= 63, "ring depth and vmcnt budget");
     static_assert(KKW % 2 == 0, "a K step starts and ends on fragment set 0 / 1");
+    // MFMAs between two hand-overs, and over how many of them (counted from the hand-over that
+    // frees the slot) a wavefront spreads the RPW loads of one K step: a load blocks the
+    // wavefront's instruction stream until the CU's memory pipeline takes it, so loads issued
+    // faster than that pipeline drains stall the MFMAs queued behind them.  A two-slot ring keeps
+    // the last k16 step before the next hand-over free, so that the last load has time to land.
+#ifndef MOE_EP_ISSUE_WINDOW_2
+#define MOE_EP_ISSUE_WINDOW_2 (KKW * MB * NB - MB * NB > RPW ? KKW * MB * NB - MB * NB : RPW)
+#endif
+#ifndef MOE_EP_ISSUE_WINDOW_N
+#define MOE_EP_ISSUE_WINDOW_N (KKW * MB * NB)
+#endif
+    static constexpr int SLOTS = KKW * MB * NB;
+    static constexpr int WINDOW = STAGES == 2 ? (MOE_EP_ISSUE_WINDOW_2) : (MOE_EP_ISSUE_WINDOW_N);
+    static_assert(WINDOW >= RPW && WINDOW <= SLOTS, "at most one load per MFMA between two hand-overs");
+    // the load issued behind MFMA number p after a hand-over, or -1
+    static constexpr int load_at(int p)
+    {
+        const int l = (p * RPW + WINDOW - 1) / WINDOW;
+        return (l < RPW && (l * WINDOW) / RPW == p) ? l : -1;
+    }
 };
 
-__device__ __forceinline__ float silu_f(float g) { return g / (1.0f + __expf(-g)); }
+// g * sigmoid(g) from the hardware's exp2 and reciprocal (about 1 ulp each: far below the bf16
+// rounding of the result); exp2 saturates to +inf / 0 at the ends, which give -0 and g
+__device__ __forceinline__ float silu_f(float g)
+{
+    return g * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(g * -1.4426950408889634f));
+}
 
 // s_waitcnt vmcnt(n) lgkmcnt(0): all but the newest n vector-memory loads have landed and every LDS
 // read has returned (gfx9 encoding: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[5:4] << 14)
@@ -218,62 +245,78 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_kernel(GemmArgs a)
         __builtin_amdgcn_s_barrier();                                                             \
         asm volatile("" ::: "memory");                                                            \
     }
-    // One K step.  The source order below is the issue order: sched_barrier(0) after every MFMA
-    // keeps the compiler from regrouping.  A K step is KKW k16 steps; k16 step i works out of
-    // fragment set i & 1 while the LDS reads
-    // of step i+1 and the global loads of K step ks_ of the issue-side tile (STAGES-1 K steps
-    // ahead in the ring) are slipped between its MFMAs.  The fragments of a K step's first k16
-    // step are read during the LAST k16 step of the K step before it: the hand-over of the next
-    // ring slot sits in front of those MFMAs (next_pending_ = loads that may still be in flight
-    // then; has_next_ = false when nothing follows in the ring), so the LDS latency after a
-    // barrier hides behind MB*NB MFMAs.  Fragment reads are ordered so that the first MFMA needs
-    // only the first two.
+    // One K step of the tile being computed.  The source order below is the issue order:
+    // sched_barrier(0) after every MFMA keeps the compiler from regrouping.  A K step is KKW k16
+    // steps; k16 step i works out of fragment set i & 1 while the LDS reads of step i+1 are slipped
+    // between its MFMAs.  The hand-over of the next ring slot sits in front of the LAST k16 step:
+    // the fragments of the next K step's first k16 step are read during that step (prefetch_; not
+    // at the end of a tile, whose epilogue would have to keep them alive), so the LDS latency after
+    // a barrier hides behind MB*NB MFMAs.  The same barrier frees the slot this K step has been
+    // reading - every wavefront's last reads of it have returned - and the loads of the K step
+    // STAGES ahead (ki on the issue side) start into it at once and carry on through the first
+    // k16 steps of the following K step, spread evenly behind the MFMAs (GemmCfg::load_at).  When the issue side has used up its
+    // tile it moves to the workgroup's next one just before that.  Fragment reads are ordered so
+    // that the first MFMA needs only the first two.
 #define MOE_EP_FRAG_ORDER(f_) ((f_) == 0 ? MB : (f_) <= MB ? (f_) - 1 : (f_))
-#define MOE_EP_STEP(ks_, issue_, has_next_, next_pending_) MOE_EP_STEP5(ks_, issue_, has_next_, has_next_, next_pending_)
-#define MOE_EP_STEP5(ks_, issue_, handover_, prefetch_, next_pending_)                            \
+#define MOE_EP_STEP(prefetch_)                                                                    \
     {                                                                                             \
         const uint4* sT = lds + stage * Cfg::STAGE_CHUNKS;                                        \
         const int st_next = stage == STAGES - 1 ? 0 : stage + 1;                                  \
         const uint4* sN = lds + st_next * Cfg::STAGE_CHUNKS;                                      \
-        const int st2 = stage == 0 ? STAGES - 1 : stage - 1;                                      \
+        const int st_prev = stage == 0 ? STAGES - 1 : stage - 1;                                  \
         _Pragma("unroll") for (int i = 0; i < KKW; ++i) {                                         \
-            if (i == KKW - 1 && (handover_)) MOE_EP_HANDOVER(next_pending_)                       \
+            if (i == KKW - 1) {                                                                   \
+                if (ki == KT) {                                                                   \
+                    if (!issue_end) {                                                             \
+                        has_nxt = setup_tile(it_issue + 1, nxt);                                  \
+                        if (has_nxt) ++it_issue; else issue_end = true;                           \
+                    }                                                                             \
+                    ki = 0;                                                                       \
+                }                                                                                 \
+                MOE_EP_HANDOVER((STAGES - 2) * RPW)                                               \
+            }                                                                                     \
             _Pragma("unroll") for (int q = 0; q < MB * NB; ++q) {                                 \
                 const int nb = q / MB, mb = q % MB;                                               \
                 acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[i & 1][nb], xf[i & 1][mb], acc[mb][nb], 0, 0, 0); \
                 _Pragma("unroll") for (int f = q; f < MB + NB; f += MB * NB) {                    \
-                    if (i + 1 < KKW) MOE_EP_FRAG1(sT, i + 1, (i + 1) & 1, MOE_EP_FRAG_ORDER(f)) \
-                    else if (prefetch_) MOE_EP_FRAG1(sN, 0, 0, MOE_EP_FRAG_ORDER(f))       \
+                    if (i + 1 < KKW) MOE_EP_FRAG1(sT, i + 1, (i + 1) & 1, MOE_EP_FRAG_ORDER(f))   \
+                    else if (prefetch_) MOE_EP_FRAG1(sN, 0, 0, MOE_EP_FRAG_ORDER(f))              \
                 }                                                                                 \
-                if ((issue_) && i + 1 < KKW) {  /* all loads go out before the hand-over */       \
-                    _Pragma("unroll") for (int l = i * MB * NB + q; l < RPW; l += (KKW - 1) * MB * NB) \
-                        MOE_EP_ISSUE1(ks_, st2, l)                                                \
+                if (i + 1 < KKW) {  /* the rest of the load group that started a K step ago */    \
+                    const int l_ = Cfg::load_at((i + 1) * MB * NB + q);                           \
+                    if (l_ >= 0) MOE_EP_ISSUE1(ki - 1, st_prev, l_ < 0 ? 0 : l_)                  \
+                } else {                                                                          \
+                    const int l_ = Cfg::load_at(q);                                               \
+                    if (l_ >= 0) MOE_EP_ISSUE1(ki, stage, l_ < 0 ? 0 : l_)                        \
                 }                                                                                 \
                 SB();                                                                             \
             }                                                                                     \
         }                                                                                         \
+        ++ki;                                                                                     \
         stage = st_next;                                                                          \
     }
-    // the first STAGES-1 K steps of the issue-side tile go in flight, K step p into ring slot stage+p
-#define MOE_EP_PROLOGUE()                                                                         \
-    _Pragma("unroll") for (int p = 0; p < STAGES - 1; ++p)                                        \
-        if (p < KT) {                                                                             \
-            const int sp_ = stage + p >= STAGES ? stage + p - STAGES : stage + p;                 \
-            _Pragma("unroll") for (int i = 0; i < RPW; ++i) MOE_EP_ISSUE1(p, sp_, i)              \
-        }
 
-    Tile cur;
+    Tile cur, nxt;
     if (!setup_tile(0, cur)) return;
-    // The ring never drains between tiles: when a tile's own K steps are all in flight, the remaining
-    // STAGES-1 steps of its loop fetch the first K steps of the workgroup's next tile and the last
-    // step hands the first of them over, so the epilogue's stores overlap the next tile's loads.
-    // After the last tile the same steps re-fetch that tile's own first K steps (the issue side simply
-    // stays where it is): a few wasted loads at the very end keep every step of the loop alike.  The
-    // launcher guarantees KT >= STAGES-1.
-    int stage = 0;
-    MOE_EP_PROLOGUE()
+    // The ring never drains between tiles: the issue side runs STAGES K steps ahead of the MFMAs and
+    // simply crosses into the workgroup's next tile (the launcher guarantees KT >= STAGES, so it is
+    // never more than one tile ahead), and the epilogue's stores overlap the next tile's loads.
+    // After the last tile it wraps around to that tile's own first K steps: a few wasted loads at
+    // the very end keep every step of the loop alike.
+    int stage = 0, it_issue = 0;
+    bool has_nxt = false, issue_end = false;
+    // K steps 0 .. STAGES-2 go in flight, the first is handed over, and K step STAGES-1 starts
+    // the way every later one does: behind a hand-over
+#pragma unroll
+    for (int p = 0; p < STAGES - 1; ++p)
+#pragma unroll
+        for (int i = 0; i < RPW; ++i) MOE_EP_ISSUE1(p, p, i)
     MOE_EP_HANDOVER((STAGES - 2) * RPW)
-    for (int it = 0;; ++it) {
+#pragma unroll
+    for (int p = 0; p < MB * NB; ++p)
+        if (Cfg::load_at(p) >= 0) MOE_EP_ISSUE1(STAGES - 1, STAGES - 1, Cfg::load_at(p) < 0 ? 0 : Cfg::load_at(p))
+    int ki = STAGES;  // K step of the issue-side tile whose loads start at the next hand-over
+    for (;;) {
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
@@ -286,62 +329,63 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_kernel(GemmArgs a)
             for (int f = 0; f < MB + NB; ++f) MOE_EP_FRAG1(s0, 0, 0, MOE_EP_FRAG_ORDER(f))
             SB();
         }
-        int kt = 0;
-        // K step kt hands over K step kt+1, behind which STAGES-2 more are in flight
-        for (; kt + STAGES - 1 < KT; ++kt) MOE_EP_STEP(kt + STAGES - 1, true, true, (STAGES - 2) * RPW)
-        // the tile's own loads are all out: the issue side moves on to the next tile
-        Tile nxt;
-        const bool has_nxt = setup_tile(it + 1, nxt);
-        for (; kt + 1 < KT; ++kt) MOE_EP_STEP(kt + STAGES - 1 - KT, true, true, (STAGES - 2) * RPW)
-        // the last step hands the next tile's first K step over (no store is in flight yet, so the
-        // load count is exact); its fragments are read after the epilogue
-        MOE_EP_STEP5(kt + STAGES - 1 - KT, true, true, false, (STAGES - 2) * RPW)
+        for (int kt = 0; kt + 1 < KT; ++kt) MOE_EP_STEP(true)
+        // the last step hands the next tile's first K step over; its fragments are read after the
+        // epilogue
+        MOE_EP_STEP(false)
 
-        // epilogue: lane holds token row (lane & 31) of each block and, per register quad q,
-        // output columns 8q + 4*(lane >> 5) + {0..3} of the block
-        uint16_t* Cg = a.C + (size_t)cur.g * a.c_group_col_stride;
+        // epilogue: a lane holds token row (lane & 31) of each block and, per register quad q,
+        // output columns 8q + 4*(lane >> 5) + {0..3} of the block.  Two quads are exchanged between
+        // the half-wavefronts (v_permlane32_swap) so that a lane stores 8 consecutive columns with
+        // one 16-byte store: every store instruction then carries 32 bytes per token row instead of
+        // 16, and the store path of the CU, which is what the epilogue waits for, sees half the
+        // requests.  A tile whose columns all lie inside N (the usual case, decided once per tile)
+        // stores without per-store column tests.
+        {
+            const int n_lane = cur.n0 + wn * (SWIGLU ? Cfg::WTN / 2 : Cfg::WTN) + fr_kh * 8;
+            uint16_t* Cg = a.C + (size_t)cur.g * a.c_group_col_stride + n_lane;
+            auto store_tile = [&](auto guard_n) {
+                constexpr bool GUARD_N = decltype(guard_n)::value;
 #pragma unroll
-        for (int mb = 0; mb < MB; ++mb) {
-            const int m = wm * Cfg::WTM + mb * 32 + fr_row;
-            if (m >= cur.nrows) continue;
-            uint16_t* crow = Cg + (size_t)(cur.row0 + m) * a.ldc;
-            if (SWIGLU) {
+                for (int mb = 0; mb < MB; ++mb) {
+                    const int m = wm * Cfg::WTM + mb * 32 + fr_row;
+                    if (m >= cur.nrows) continue;  // the same for both lanes of an exchange
+                    uint16_t* crow = Cg + (size_t)(cur.row0 + m) * a.ldc;
 #pragma unroll
-                for (int nb = 0; nb < NB / 2; ++nb)
+                    for (int nb = 0; nb < (SWIGLU ? NB / 2 : NB); ++nb)
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        const int n = cur.n0 + wn * (Cfg::WTN / 2) + nb * 32 + q * 8 + fr_kh * 4;
-                        if (n >= a.N) continue;
-                        float h[4];
+                        for (int q = 0; q < 4; q += 2) {
+                            uint32_t pk[2][2];  // [quad q, q+1][column pair]
 #pragma unroll
-                        for (int i = 0; i < 4; ++i)
-                            h[i] = silu_f(acc[mb][nb][q * 4 + i]) * acc[mb][nb + NB / 2][q * 4 + i];
-                        uint2 o;
-                        o.x = pack_bf16x2(h[0], h[1]); o.y = pack_bf16x2(h[2], h[3]);
-                        *reinterpret_cast<uint2*>(crow + n) = o;
-                    }
-            } else {
+                            for (int j = 0; j < 2; ++j) {
+                                float h[4];
 #pragma unroll
-                for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        const int n = cur.n0 + wn * Cfg::WTN + nb * 32 + q * 8 + fr_kh * 4;
-                        if (n >= a.N) continue;
-                        uint2 o;
-                        o.x = pack_bf16x2(acc[mb][nb][q * 4 + 0], acc[mb][nb][q * 4 + 1]);
-                        o.y = pack_bf16x2(acc[mb][nb][q * 4 + 2], acc[mb][nb][q * 4 + 3]);
-                        *reinterpret_cast<uint2*>(crow + n) = o;
-                    }
-            }
+                                for (int i = 0; i < 4; ++i)
+                                    h[i] = SWIGLU ? silu_f(acc[mb][nb][(q + j) * 4 + i]) * acc[mb][nb + NB / 2][(q + j) * 4 + i]
+                                                  : acc[mb][nb][(q + j) * 4 + i];
+                                pk[j][0] = pack_bf16x2(h[0], h[1]);
+                                pk[j][1] = pack_bf16x2(h[2], h[3]);
+                            }
+                            // lanes 32..63 of quad q  <->  lanes 0..31 of quad q+1
+                            const auto s0 = __builtin_amdgcn_permlane32_swap(pk[0][0], pk[1][0], false, false);
+                            const auto s1 = __builtin_amdgcn_permlane32_swap(pk[0][1], pk[1][1], false, false);
+                            if (GUARD_N && n_lane + nb * 32 + q * 8 >= a.N) continue;
+                            uint4 o;
+                            o.x = s0[0]; o.y = s1[0]; o.z = s0[1]; o.w = s1[1];
+                            *reinterpret_cast<uint4*>(crow + nb * 32 + q * 8) = o;
+                        }
+                }
+            };
+            if (cur.n0 + Cfg::BN_OUT <= a.N) store_tile(std::false_type{});
+            else store_tile(std::true_type{});
         }
         if (!has_nxt) break;
         cur = nxt;
+        has_nxt = false;
     }
     // loads still on their way write into this workgroup's LDS: they must land before it is given up
     MOE_EP_WAIT_VMCNT_LGKM0(0);
-#undef MOE_EP_PROLOGUE
 #undef MOE_EP_HANDOVER
-#undef MOE_EP_STEP5
 #undef MOE_EP_STEP
 #undef MOE_EP_FRAG_ORDER
 #undef SB
@@ -361,6 +405,8 @@ static hipError_t launch_one(const GemmArgs& a, int n_cu, int max_row_tiles, hip
     const long long x_span = (long long)(a.a_row_map ? a.a_src_rows : BM) * a.lda * 2;
     if (a.a_row_map && (!RAGGED || a.a_row_div < 1 || a.a_src_rows < 1)) return hipErrorInvalidValue;
     if (w_span >= (1ll << 32) || x_span >= (1ll << 32) || w_span < 0) return hipErrorInvalidValue;
+    // the epilogue stores 8 output columns (16 bytes) per lane
+    if (a.N % 8 || a.ldc % 8 || a.c_group_col_stride % 8 || (reinterpret_cast<uintptr_t>(a.C) & 15)) return hipErrorInvalidValue;
     // workgroups per CU: LDS (160 KB minus the kernel's small static tables) and 8 wavefront slots
     int occ = (156 * 1024) / Cfg::LDS_BYTES;
     const int by_waves = 8 / Cfg::NW;
@@ -401,17 +447,20 @@ static hipError_t launch_cfg(const GemmArgs& a, bool swiglu, int n_cu, int max_r
 // tile variants: id, BM, BN, BK, ring slots, wavefronts in m, in n
 // (0 and 7: short row tiles; with exactly 16 rows per expert they stream the weights 13 % faster than
 // the 128-row tiles, with the ragged counts of real routing they do not, so nothing selects them by
-// default).  A ring of S slots needs K >= (S-1) * BK; for a shorter K the launcher takes the
-// two-slot variant with the same row tile, listed in the last column.
+// default).  A ring of S slots needs K >= S * BK; for a shorter K the launcher takes the two-slot
+// variant with the same row tile and 32-wide K steps (K is a multiple of 64), listed in the last
+// column.
 #define MOE_EP_VARIANTS(X)         \
-    X(0, 64, 128, 64, 2, 1, 2, 0)  \
-    X(1, 128, 256, 64, 3, 2, 2, 4) \
-    X(2, 256, 256, 64, 2, 2, 2, 2) \
-    X(3, 256, 256, 32, 4, 2, 2, 2) \
-    X(4, 128, 128, 64, 2, 2, 2, 4) \
+    X(0, 64, 128, 64, 2, 1, 2, 8)  \
+    X(1, 128, 256, 64, 3, 2, 2, 6) \
+    X(2, 256, 256, 64, 2, 2, 2, 9) \
+    X(3, 256, 256, 32, 4, 2, 2, 9) \
+    X(4, 128, 128, 64, 2, 2, 2, 6) \
     X(5, 128, 256, 32, 3, 2, 2, 6) \
     X(6, 128, 256, 32, 2, 2, 2, 6) \
-    X(7, 64, 128, 64, 3, 1, 2, 0)
+    X(7, 64, 128, 64, 3, 1, 2, 8)  \
+    X(8, 64, 128, 32, 2, 1, 2, 8)  \
+    X(9, 256, 256, 32, 2, 2, 2, 9)
 
 hipError_t grouped_gemm_init()
 {
@@ -439,7 +488,10 @@ hipError_t launch_grouped_gemm(const GemmArgs& a, bool swiglu, int variant, int 
     switch (variant) {
 #define X(id, BM, BN, BK, ST, WGM, WGN, FB)                                                          \
         case id:                                                                                    \
-            if (a.K / BK < ST - 1) return launch_grouped_gemm(a, swiglu, FB, n_cu, max_row_tiles, s); \
+            if (a.K / BK < ST) {                                                                    \
+                if (FB == id) return hipErrorInvalidValue;                                          \
+                return launch_grouped_gemm(a, swiglu, FB, n_cu, max_row_tiles, s);                  \
+            }                                                                                       \
             return launch_cfg<BM, BN, BK, ST, WGM, WGN>(a, swiglu, n_cu, max_row_tiles, s);
         MOE_EP_VARIANTS(X)
 #undef X
