@@ -352,7 +352,12 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_kernel(GemmArgs a)
                     if (m >= cur.nrows) continue;  // the same for both lanes of an exchange
                     uint16_t* crow = Cg + (size_t)(cur.row0 + m) * a.ldc;
 #pragma unroll
-                    for (int nb = 0; nb < (SWIGLU ? NB / 2 : NB); ++nb)
+                    for (int nb = 0; nb < (SWIGLU ? NB / 2 : NB); ++nb) {
+                        // the block stays in its accumulator registers until here: without the
+                        // pin the compiler copies all accumulators out during the last K step,
+                        // spills, and every spill reload waits for all stores before it
+                        asm volatile("; accumulator block %1" : "+a"(acc[mb][nb]) : "n"(mb * NB + nb));
+                        if (SWIGLU) asm volatile("; accumulator block %1" : "+a"(acc[mb][nb + NB / 2]) : "n"(mb * NB + nb + NB / 2));
 #pragma unroll
                         for (int q = 0; q < 4; q += 2) {
                             uint32_t pk[2][2];  // [quad q, q+1][column pair]
@@ -374,6 +379,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_kernel(GemmArgs a)
                             o.x = s0[0]; o.y = s1[0]; o.z = s0[1]; o.w = s1[1];
                             *reinterpret_cast<uint4*>(crow + nb * 32 + q * 8) = o;
                         }
+                    }
                 }
             };
             if (cur.n0 + Cfg::BN_OUT <= a.N) store_tile(std::false_type{});
