@@ -87,25 +87,23 @@ __device__ __forceinline__ float silu_f(float g)
 // read has returned (gfx9 encoding: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[5:4] << 14)
 #define MOE_EP_WAIT_VMCNT_LGKM0(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | (((n) >> 4) << 14) | 0x0070)
 
+// All tiles of one shape that a workgroup owns.  Ragged mode reads the groups from LDS tables the
+// caller has filled: s_pref[g] = row tiles of this shape before group g (s_pref[G] = all of them),
+// s_row0[g] / s_rowend[g] = the rows of group g this shape covers.
 template <int BM, int BN, int BK, int STAGES, int WGM, int WGN, bool SWIGLU, bool RAGGED>
-__global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_kernel(GemmArgs a)
+__device__ __forceinline__ void gemm_tiles(const GemmArgs& a, uint4* lds, const int* s_pref, const int* s_row0,
+                                           const int* s_rowend)
 {
     using Cfg = GemmCfg<BM, BN, BK, STAGES, WGM, WGN, SWIGLU>;
     constexpr int MB = Cfg::MB, NB = Cfg::NB, RPW = Cfg::RPW, XRPW = Cfg::XRPW, NW = Cfg::NW;
     constexpr int THREADS = Cfg::THREADS, BN_OUT = Cfg::BN_OUT, CPR = Cfg::CPR, RP = Cfg::RP;
     constexpr int RPR = Cfg::RPR, KKW = Cfg::KKW;
-    extern __shared__ uint4 lds[];
-    __shared__ int s_pref[513];
-    __shared__ int s_off[513];
-
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform: LDS destinations stay scalar
     const int wn = wave % WGN, wm = wave / WGN;
     const int NT = (a.N + BN_OUT - 1) / BN_OUT;
     int mt_total, mt_per = 0;
-    if (RAGGED) {  // routed experts: ragged groups described by device prefix sums
-        for (int i = tid; i <= a.G; i += THREADS) { s_pref[i] = a.mt_prefix[i]; s_off[i] = a.offset[i]; }
-        __syncthreads();
+    if (RAGGED) {  // routed experts: ragged groups, tables in LDS
         mt_total = s_pref[a.G];
     } else {       // shared experts: every group multiplies the same dense rows
         mt_per = (a.dense_rows + BM - 1) / BM;
@@ -165,8 +163,8 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_kernel(GemmArgs a)
             mi = band * kBand + (lb - ni * band_h);
         }
         if (RAGGED) {
-            row0 = s_off[g] + mi * BM;
-            nrows = min(BM, s_off[g + 1] - row0);
+            row0 = s_row0[g] + mi * BM;
+            nrows = min(BM, s_rowend[g] - row0);
         } else {
             row0 = mi * BM;
             nrows = min(BM, a.dense_rows - row0);
@@ -399,6 +397,92 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_kernel(GemmArgs a)
 #undef MOE_EP_FRAG1
 }
 
+constexpr int kMaxGroups = 512;
+
+// one tile shape for all groups (the ragged groups' row-tile prefix comes from the dispatch scan)
+template <int BM, int BN, int BK, int STAGES, int WGM, int WGN, bool SWIGLU, bool RAGGED>
+__global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_kernel(GemmArgs a)
+{
+    extern __shared__ uint4 lds[];
+    __shared__ int s_pref[kMaxGroups + 1], s_row0[kMaxGroups + 1], s_rowend[kMaxGroups + 1];
+    if (RAGGED) {
+        for (int i = threadIdx.x; i <= a.G; i += WGM * WGN * 64) {
+            s_pref[i] = a.mt_prefix[i];
+            s_row0[i] = a.offset[i];
+            s_rowend[i] = a.offset[i < a.G ? i + 1 : i];
+        }
+        __syncthreads();
+    }
+    gemm_tiles<BM, BN, BK, STAGES, WGM, WGN, SWIGLU, RAGGED>(a, lds, s_pref, s_row0, s_rowend);
+}
+
+// Two tile shapes in one launch, ragged groups only: the rows of a group are covered by tall tiles
+// (BMA rows, fewer operand bytes per flop) as far as they fill them to more than BMB rows, and
+// what is left at the end of the group by short tiles of BMB rows, which waste fewer MFMAs on a
+// short tail.  Every workgroup first works through its share of the tall tiles, then, once its
+// ring has drained, through its share of the short ones; the tables of both passes are derived
+// here from the group offsets alone.
+template <int BMA, int BKA, int STA, int BMB, int BKB, int STB, int BN, int WGM, int WGN, bool SWIGLU>
+__global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_two_shape_kernel(GemmArgs a)
+{
+    static_assert(WGM * WGN * 64 >= 64 && BMA > BMB, "tall tiles first");
+    extern __shared__ uint4 lds[];
+    __shared__ int s_pref[kMaxGroups + 1], s_row0[kMaxGroups + 1], s_rowend[kMaxGroups + 1];
+    const int tid = threadIdx.x;
+    // exclusive prefix sum of per-group tile counts by the first wavefront: 8 groups per lane,
+    // then a scan over the lanes
+    auto fill = [&](bool tall) {
+        __syncthreads();
+        if (tid < 64) {
+            int cnt[9], sum = 0;
+#pragma unroll
+            for (int j = 0; j < 9; ++j) {
+                const int g = tid * 9 + j;
+                int c = 0;
+                if (g < a.G) {
+                    const int lo = a.offset[g], hi = a.offset[g + 1], r = hi - lo;
+                    const int n_tall = r / BMA + ((r % BMA) > BMB ? 1 : 0);
+                    const int split = min(hi, lo + n_tall * BMA);
+                    if (tall) { s_row0[g] = lo; s_rowend[g] = split; c = n_tall; }
+                    else { s_row0[g] = split; s_rowend[g] = hi; c = (hi - split + BMB - 1) / BMB; }
+                }
+                cnt[j] = sum;
+                sum += c;
+            }
+            int incl = sum;
+#pragma unroll
+            for (int d = 1; d < 64; d <<= 1) {
+                const int up = __shfl_up(incl, d, 64);
+                if (tid >= d) incl += up;
+            }
+            const int base = incl - sum;
+#pragma unroll
+            for (int j = 0; j < 9; ++j) {
+                const int g = tid * 9 + j;
+                if (g <= a.G) s_pref[g] = base + cnt[j];
+            }
+        }
+        __syncthreads();
+    };
+    fill(true);
+    gemm_tiles<BMA, BN, BKA, STA, WGM, WGN, SWIGLU, true>(a, lds, s_pref, s_row0, s_rowend);
+    fill(false);  // its first barrier also separates the two passes' use of the ring
+    gemm_tiles<BMB, BN, BKB, STB, WGM, WGN, SWIGLU, true>(a, lds, s_pref, s_row0, s_rowend);
+}
+
+// what every kernel here assumes of its arguments beyond the shapes the caller has checked
+static bool args_fit(const GemmArgs& a, bool swiglu, bool ragged, int bm)
+{
+    // lanes address with 32-bit byte offsets inside one group's weights and one activation panel
+    const long long w_span = ((swiglu ? a.w_up_offset : 0) + (long long)a.N * a.ldw) * 2;
+    const long long x_span = (long long)(a.a_row_map ? a.a_src_rows : bm) * a.lda * 2;
+    if (a.a_row_map && (!ragged || a.a_row_div < 1 || a.a_src_rows < 1)) return false;
+    if (w_span >= (1ll << 32) || x_span >= (1ll << 32) || w_span < 0) return false;
+    if (a.G < 1 || a.G > kMaxGroups) return false;
+    // the epilogue stores 8 output columns (16 bytes) per lane
+    return !(a.N % 8 || a.ldc % 8 || a.c_group_col_stride % 8 || (reinterpret_cast<uintptr_t>(a.C) & 15));
+}
+
 template <int BM, int BN, int BK, int STAGES, int WGM, int WGN, bool SWIGLU, bool RAGGED>
 static hipError_t launch_one(const GemmArgs& a, int n_cu, int max_row_tiles, hipStream_t s)
 {
@@ -406,13 +490,7 @@ static hipError_t launch_one(const GemmArgs& a, int n_cu, int max_row_tiles, hip
     const int NT = (a.N + Cfg::BN_OUT - 1) / Cfg::BN_OUT;
     const long long max_tiles = (long long)max_row_tiles * NT;
     if (max_tiles <= 0) return hipSuccess;
-    // lanes address with 32-bit byte offsets inside one group's weights and one activation panel
-    const long long w_span = ((SWIGLU ? a.w_up_offset : 0) + (long long)a.N * a.ldw) * 2;
-    const long long x_span = (long long)(a.a_row_map ? a.a_src_rows : BM) * a.lda * 2;
-    if (a.a_row_map && (!RAGGED || a.a_row_div < 1 || a.a_src_rows < 1)) return hipErrorInvalidValue;
-    if (w_span >= (1ll << 32) || x_span >= (1ll << 32) || w_span < 0) return hipErrorInvalidValue;
-    // the epilogue stores 8 output columns (16 bytes) per lane
-    if (a.N % 8 || a.ldc % 8 || a.c_group_col_stride % 8 || (reinterpret_cast<uintptr_t>(a.C) & 15)) return hipErrorInvalidValue;
+    if (!args_fit(a, SWIGLU, RAGGED, BM)) return hipErrorInvalidValue;
     // workgroups per CU: LDS (160 KB minus the kernel's small static tables) and 8 wavefront slots
     int occ = (156 * 1024) / Cfg::LDS_BYTES;
     const int by_waves = 8 / Cfg::NW;
@@ -468,9 +546,30 @@ static hipError_t launch_cfg(const GemmArgs& a, bool swiglu, int n_cu, int max_r
     X(8, 64, 128, 32, 2, 1, 2, 8)  \
     X(9, 256, 256, 32, 2, 2, 2, 9)
 
+// the two-shape kernel of the routed experts: 256-row tiles on a two-slot ring, 128-row tiles on a
+// three-slot ring, 256 output columns, 64-wide K steps, 2 x 2 wavefronts
+constexpr int kTwoShapeVariant = 10;
+#define MOE_EP_TWO_SHAPE(SW) grouped_gemm_two_shape_kernel<256, 64, 2, 128, 64, 3, 256, 2, 2, SW>
+constexpr int kTwoShapeLds = GemmCfg<128, 256, 64, 3, 2, 2, false>::LDS_BYTES > GemmCfg<256, 256, 64, 2, 2, 2, false>::LDS_BYTES
+                                 ? GemmCfg<128, 256, 64, 3, 2, 2, false>::LDS_BYTES
+                                 : GemmCfg<256, 256, 64, 2, 2, 2, false>::LDS_BYTES;
+
+static hipError_t launch_two_shape(const GemmArgs& a, bool swiglu, int n_cu, hipStream_t s)
+{
+    if (!a.offset || !args_fit(a, swiglu, true, 256)) return hipErrorInvalidValue;
+    const unsigned grid = (unsigned)((n_cu + 7) / 8 * 8);
+    if (swiglu) hipLaunchKernelGGL((MOE_EP_TWO_SHAPE(true)), dim3(grid), dim3(256), kTwoShapeLds, s, a);
+    else hipLaunchKernelGGL((MOE_EP_TWO_SHAPE(false)), dim3(grid), dim3(256), kTwoShapeLds, s, a);
+    return hipGetLastError();
+}
+
 hipError_t grouped_gemm_init()
 {
     hipError_t e;
+    if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(&MOE_EP_TWO_SHAPE(true)),
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, kTwoShapeLds)) != hipSuccess) return e;
+    if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(&MOE_EP_TWO_SHAPE(false)),
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, kTwoShapeLds)) != hipSuccess) return e;
 #define X(id, BM, BN, BK, ST, WGM, WGN, FB) if ((e = raise_all<BM, BN, BK, ST, WGM, WGN>()) != hipSuccess) return e;
     MOE_EP_VARIANTS(X)
 #undef X
@@ -491,6 +590,13 @@ hipError_t launch_grouped_gemm(const GemmArgs& a, bool swiglu, int variant, int 
                                int max_row_tiles, hipStream_t s)
 {
     if (a.K < 64 || a.K % 64) return hipErrorInvalidValue;
+    if (variant == kTwoShapeVariant) {
+        // dense rows have no ragged tails: 256-row tiles; a K too short for the three-slot ring:
+        // the 128-row shape alone, which falls back further by itself
+        if (!a.offset) return launch_grouped_gemm(a, swiglu, 2, n_cu, max_row_tiles, s);
+        if (a.K / 64 < 3) return launch_grouped_gemm(a, swiglu, 1, n_cu, max_row_tiles, s);
+        return launch_two_shape(a, swiglu, n_cu, s);
+    }
     switch (variant) {
 #define X(id, BM, BN, BK, ST, WGM, WGN, FB)                                                          \
         case id:                                                                                    \

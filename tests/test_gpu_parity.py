@@ -168,12 +168,13 @@ def test_maximum_expert_count_and_top_k():
     _full_parity(wl, seed=28)
 
 
-@pytest.mark.parametrize("variant", [0, 1, 2, 3, 4, 5, 6, 7])
-@pytest.mark.parametrize("hidden", [64, 128, 192])
+@pytest.mark.parametrize("variant", [0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10])
+@pytest.mark.parametrize("hidden", [64, 128, 192, 320])
 def test_every_tile_variant_matches_oracle(variant, hidden):
-    """Each instantiated tile shape / ring depth of the grouped GEMM, for the routed and the shared
-    experts, on K extents of one, two and three 64-wide steps (shortest pipelines) with ragged row
-    and column tails."""
+    """Each instantiated tile shape / ring depth of the grouped GEMM (10: tall and short tiles in one
+    launch), for the routed and the shared experts, on K extents of one, two, three and five 64-wide
+    steps (shortest pipelines, fallbacks to the 32-wide variants included) with ragged row and column
+    tails."""
     wl = tiny_workload(name=f"v{variant}_M{hidden}", n_tokens=333, hidden=hidden, inter=320, n_experts=6,
                        n_local=6, top_k=2, n_shared=1, shared_inter=192)
     old = {k: os.environ.get(k) for k in ("MOE_EP_GEMM_VARIANT", "MOE_EP_SHARED_VARIANT")}
@@ -186,6 +187,31 @@ def test_every_tile_variant_matches_oracle(variant, hidden):
                 os.environ.pop(k, None)
             else:
                 os.environ[k] = v
+
+
+def test_tall_and_short_tiles_in_one_launch():
+    """Tile variant 10 on expert loads that need every case of its row split: experts with several
+    256-row tiles, tails longer than 128 rows (one more tall tile), tails of at most 128 rows (a
+    short tile) and an expert without tokens."""
+    wl = tiny_workload(name="two_shapes", n_tokens=1400, hidden=192, inter=320, n_experts=7, n_local=7,
+                       top_k=2, n_shared=1, shared_inter=192, zipf_s=1.0)
+
+    def no_tokens_for_expert_3(inp):
+        inp["gate_logits"][:, 3] = -1e9
+
+    old = os.environ.get("MOE_EP_GEMM_VARIANT")
+    os.environ["MOE_EP_GEMM_VARIANT"] = "10"
+    try:
+        _, ref = _full_parity(wl, seed=41, mutate=no_tokens_for_expert_3)
+    finally:
+        if old is None:
+            os.environ.pop("MOE_EP_GEMM_VARIANT", None)
+        else:
+            os.environ["MOE_EP_GEMM_VARIANT"] = old
+    counts = ref["count"][0].tolist()
+    tails = [c % 256 for c in counts]
+    assert max(counts) >= 512 and min(counts) == 0
+    assert any(t > 128 for t in tails) and any(0 < t <= 128 for t in tails)
 
 
 def test_grouped_copy_of_token_rows_matches_too():
