@@ -314,6 +314,13 @@ __device__ __forceinline__ void gemm_tiles(const GemmArgs& a, uint4* lds, const 
     for (int p = 0; p < MB * NB; ++p)
         if (Cfg::load_at(p) >= 0) MOE_EP_ISSUE1(STAGES - 1, STAGES - 1, Cfg::load_at(p) < 0 ? 0 : Cfg::load_at(p))
     int ki = STAGES;  // K step of the issue-side tile whose loads start at the next hand-over
+    {   // the first tile's first K step has been handed over: its first fragments.  Every later K
+        // step, the first of a following tile included, gets them from the step before it.
+        const uint4* s0 = lds + stage * Cfg::STAGE_CHUNKS;
+#pragma unroll
+        for (int f = 0; f < MB + NB; ++f) MOE_EP_FRAG1(s0, 0, 0, MOE_EP_FRAG_ORDER(f))
+        SB();
+    }
     for (;;) {
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb)
@@ -321,16 +328,9 @@ __device__ __forceinline__ void gemm_tiles(const GemmArgs& a, uint4* lds, const 
             for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[mb][nb][r] = 0.f;
-        {   // the tile's first K step has been handed over: its first fragments
-            const uint4* s0 = lds + stage * Cfg::STAGE_CHUNKS;
-#pragma unroll
-            for (int f = 0; f < MB + NB; ++f) MOE_EP_FRAG1(s0, 0, 0, MOE_EP_FRAG_ORDER(f))
-            SB();
-        }
-        for (int kt = 0; kt + 1 < KT; ++kt) MOE_EP_STEP(true)
-        // the last step hands the next tile's first K step over; its fragments are read after the
-        // epilogue
-        MOE_EP_STEP(false)
+        // one loop shape for every K step: the last one of a tile hands the next tile's first K
+        // step over and reads its first fragments, which wait in registers through the epilogue
+        for (int kt = 0; kt < KT; ++kt) MOE_EP_STEP(true)
 
         // epilogue: a lane holds token row (lane & 31) of each block and, per register quad q,
         // output columns 8q + 4*(lane >> 5) + {0..3} of the block.  Two quads are exchanged between
@@ -346,6 +346,9 @@ __device__ __forceinline__ void gemm_tiles(const GemmArgs& a, uint4* lds, const 
                 constexpr bool GUARD_N = decltype(guard_n)::value;
 #pragma unroll
                 for (int mb = 0; mb < MB; ++mb) {
+                    // a row of blocks is pinned in its accumulator registers right before its turn
+                    if (NB == 4) asm volatile("; accumulator row %4" : "+a"(acc[mb][0]), "+a"(acc[mb][1]), "+a"(acc[mb][NB > 2 ? 2 : 0]), "+a"(acc[mb][NB > 3 ? 3 : 1]) : "n"(mb));
+                    else if (NB == 2) asm volatile("; accumulator row %2" : "+a"(acc[mb][0]), "+a"(acc[mb][1]) : "n"(mb));
                     const int m = wm * Cfg::WTM + mb * 32 + fr_row;
                     if (m >= cur.nrows) continue;  // the same for both lanes of an exchange
                     uint16_t* crow = Cg + (size_t)(cur.row0 + m) * a.ldc;
@@ -354,8 +357,6 @@ __device__ __forceinline__ void gemm_tiles(const GemmArgs& a, uint4* lds, const 
                         // the block stays in its accumulator registers until here: without the
                         // pin the compiler copies all accumulators out during the last K step,
                         // spills, and every spill reload waits for all stores before it
-                        asm volatile("; accumulator block %1" : "+a"(acc[mb][nb]) : "n"(mb * NB + nb));
-                        if (SWIGLU) asm volatile("; accumulator block %1" : "+a"(acc[mb][nb + NB / 2]) : "n"(mb * NB + nb + NB / 2));
 #pragma unroll
                         for (int q = 0; q < 4; q += 2) {
                             uint32_t pk[2][2];  // [quad q, q+1][column pair]
