@@ -86,6 +86,9 @@ def main() -> int:
     ap.add_argument("--timeline", action="store_true",
                     help="after the main measurement, record one forward with events around every stage and "
                          "add its measured schedule (stage, begin ms, end ms per chunk) to the JSON line")
+    ap.add_argument("--dep", default=None, metavar="R1,R2,ATTN_US",
+                    help="also run the layer as the disaggregated schedule (moe_ep_forward_dep): r_1 micro-batches of "
+                         "r_2 chunks, attention stand-ins of ATTN_US microseconds, both orders, against the replay model")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one 1 GiB device-to-device copy kernel: the known-size reference "
                          "that rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled by")
@@ -125,9 +128,14 @@ def main() -> int:
         out = torch.zeros((T, M), dtype=torch.int16, pin_memory=True)
     else:
         out = torch.zeros((T, M), dtype=torch.int16, device="cuda")
+    dep = None
+    if args.dep:
+        f = args.dep.split(",")
+        dep = (int(f[0]), int(f[1]), float(f[2]))
+    dep_chunks = dep[0] * dep[1] if dep else 1
     ctx = pkg.MoeEp(hidden=M, inter=H, n_experts=wl.n_experts, local_begin=wl.local_begin,
                     n_local=wl.n_local, n_shared=wl.n_shared, shared_inter=wl.shared_inter,
-                    max_tokens=T, max_top_k=k, max_chunks=max(args.r, 8 if pinned else 1),
+                    max_tokens=T, max_top_k=k, max_chunks=max(args.r, 8 if pinned else 1, dep_chunks),
                     io_mode=pkg.IO_PINNED_HOST if pinned else pkg.IO_DEVICE)
     stream = torch.cuda.current_stream().cuda_stream
 
@@ -320,6 +328,43 @@ def main() -> int:
                             for n, _, b, e in ctx.get_timeline() if n != "forward"]
         ctx.get_stage_ms()
         ctx.set_profiling(0)
+    if dep:
+        # Sec. 2.3 on one GPU: measured makespan of both attention-group orders, the task durations the
+        # timeline shows, and what the earliest-start replay of Eq. limitation predicts from them
+        r_1, r_2, attn_us = dep
+        res = {"r_1": r_1, "r_2": r_2, "attn_us": attn_us, "io": "pinned" if pinned else "device",
+               "measured_ms": {}, "model_ms": {}, "tasks_ms": {}}
+        for name, order in (("ASAS", 0), ("AASS", 1)):
+            def dep_step():
+                ctx.forward_dep(tokens, logits, routed, shared, k, r_1, r_2, order, attn_us, n_tokens=T, out=out,
+                                stream=stream)
+            for _ in range(3):
+                dep_step()
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            for _ in range(args.steps):
+                dep_step()
+            torch.cuda.synchronize()
+            res["measured_ms"][name] = (time.perf_counter() - t1) / args.steps * 1e3
+            ctx.set_profiling_stages(None)
+            ctx.set_profiling(1)
+            dep_step()
+            by = {}
+            for n, _, b, e in ctx.get_timeline():
+                by.setdefault(n, []).append((b, e))
+            ctx.get_stage_ms()
+            ctx.set_profiling(0)
+            mean = lambda xs: float(np.mean(xs)) if len(xs) else 0.0
+            t_a = mean([e - b for b, e in by.get("attention", [])])
+            t_s = mean([e2 - b1 for (b1, _), (_, e2) in zip(by.get("shared_gate_up_gemm", []), by.get("shared_down_gemm", []))])
+            t_e = mean([e2 - b1 for (b1, _), (_, e2) in zip(by["router"], by["routed_down_gemm"])]) + \
+                mean([e - b for b, e in by["aggregation"]])
+            t_c = mean([e - b for b, e in by.get("copy_in", []) + by.get("copy_out", [])])
+            res["tasks_ms"][name] = {"attention": t_a, "shared": t_s, "experts_per_chunk": t_e, "link_per_chunk": t_c}
+            mod = pkg.DepModels(t_a, 0.0, t_s, 0.0, t_e, 0.0, t_c, 0.0)
+            prob = pkg.DepProblem(ag=1, n_experts=wl.n_experts, top_k=k, seq_len=1, n_layers=1)
+            res["model_ms"][name] = pkg.dep_replay(mod, prob, 1, r_1, r_2, order)[0]
+        line["dep_layer"] = res
     if args.layers > 1:
         # layer l > 0 uses a rolled copy of layer 0's weights: distinct memory, same distribution, so no
         # layer finds its weights in a cache the previous one filled

@@ -129,8 +129,8 @@ int moe_ep_forward(moe_ep_ctx *ctx, const void *tokens, const float *gate_logits
 
 /*
  * Test / inspection surface: host copies of what the last forward computed for chunk
- * `chunk` (synchronises the context's streams).  Any pointer may be NULL.  With
- * Tc = ceil(n_tokens / r_chunks) and Tn the tokens of this chunk:
+ * `chunk` (synchronises the context's streams; after moe_ep_forward_dep chunk = i * r_2 + j for
+ * chunk j of micro-batch i).  Any pointer may be NULL.  With Tn the tokens of this chunk:
  *   idx    int32 [Tn, top_k] selected global expert ids, best first
  *   w      fp32  [Tn, top_k] routing weights
  *   pos    int32 [Tn, top_k] row of the assignment in the grouped input, -1 if dropped
@@ -153,7 +153,8 @@ int moe_ep_get_routing(moe_ep_ctx *ctx, int32_t chunk, int32_t *idx, float *w, i
  *   ms[3] routed down GEMM  ms[4] shared gate/up GEMM  ms[5] shared down GEMM
  *   ms[6] aggregation  ms[7] whole forward (first enqueue to last completion)
  *   ms[8] inbound copies  ms[9] outbound copies (MOE_EP_IO_PINNED_HOST only, else 0)
- * each summed over the chunks of a forward.  n = floats the caller provides (<= 10 written).
+ *   ms[10] attention stand-ins (moe_ep_forward_dep only, else 0)
+ * each summed over the chunks of a forward.  n = floats the caller provides (<= 11 written).
  * Returns MOE_EP_ESTATE when nothing was recorded.
  */
 int moe_ep_set_profiling(moe_ep_ctx *ctx, int32_t depth);
@@ -232,6 +233,29 @@ typedef struct {
 /* Order in which the attention group takes a layer's tasks (Sec. 4.2): a_0 s_0 a_1 s_1 ... or
  * a_0 a_1 ... s_0 s_1 ... */
 typedef enum { MOE_EP_DEP_ASAS = 0, MOE_EP_DEP_AASS = 1 } moe_ep_dep_order;
+
+/*
+ * One MoE layer as the disaggregated schedule of Sec. 2.3 runs it, on one GPU (Fig. as, Eq.
+ * limitation): the n_tokens are r_1 micro-batches of ceil(n_tokens / r_1) tokens, each cut into r_2
+ * chunks of ceil(micro-batch / r_2) tokens.  The attention group is a stream of the context's own:
+ * per micro-batch a stand-in for its attention - a kernel that occupies one wavefront for about
+ * attn_us microseconds (0 = none) - and the micro-batch's shared experts, in the order
+ * a_0 s_0 a_1 s_1 ... (MOE_EP_DEP_ASAS) or a_0 a_1 ... s_0 s_1 ... (MOE_EP_DEP_AASS).  A
+ * micro-batch's chunks start after its attention (rule 6): in MOE_EP_IO_PINNED_HOST mode their
+ * inbound copies (A2E), in device mode their gate; gate, partition and the routed experts of every
+ * chunk run on `stream` (rules 7, 8), the aggregation of a chunk after the micro-batch's shared
+ * experts have written its output rows, and in pinned-host mode the outbound copy (E2A) follows.
+ * r_1 * r_2 <= max_chunks.  Everything else - arguments, layouts, ownership, errors, determinism -
+ * is as for moe_ep_forward, and the output bits are the same as moe_ep_forward's for every r_1, r_2,
+ * order and attn_us.  On one GPU the shared experts and the routed experts share the compute units,
+ * which the paper's two groups of GPUs do not: the measured schedule (moe_ep_get_timeline) obeys the
+ * rules, its makespan is not the paper's.  Not for stream capture (the first call creates the
+ * attention-group stream).
+ */
+int moe_ep_forward_dep(moe_ep_ctx *ctx, const void *tokens, const float *gate_logits,
+                       const void *routed_w, const void *shared_w, int32_t top_k, int32_t r_1,
+                       int32_t r_2, int32_t dep_order, double attn_us, int32_t n_tokens, void *out,
+                       void *stream);
 
 typedef struct {
     int32_t m_a, r_1, r_2, order;

@@ -17,9 +17,23 @@ IO_DEVICE = 0
 IO_PINNED_HOST = 1
 STAGES = ("router", "partition", "routed_gate_up_gemm", "routed_down_gemm",
           "shared_gate_up_gemm", "shared_down_gemm", "aggregation", "forward", "copy_in",
-          "copy_out")
+          "copy_out", "attention")
 
 _STATUS = {0: "OK", -1: "EINVAL", -2: "ENOMEM", -3: "EHIP", -4: "ESTATE"}
+
+
+def chunk_range(T: int, r_1: int, r_2: int, c: int):
+    """(first token, tokens) of chunk c = i * r_2 + j: r_1 micro-batches of ceil(T / r_1) tokens, each
+    cut into r_2 chunks of ceil(micro-batch / r_2) tokens (argument marshalling for get_routing)."""
+    Tm = (T + r_1 - 1) // r_1
+    i, j = divmod(c, r_2)
+    mb0 = i * Tm
+    if mb0 >= T:
+        return T, 0
+    mb1 = min(T, mb0 + Tm)
+    Tc = (Tm + r_2 - 1) // r_2
+    a = min(mb0 + j * Tc, mb1)
+    return a, min(a + Tc, mb1) - a
 
 
 class MoeEpError(RuntimeError):
@@ -98,6 +112,8 @@ def load_library() -> ctypes.CDLL:
     lib.moe_ep_create.argtypes = [cfgp, ctypes.POINTER(vp)]
     lib.moe_ep_forward.restype = ctypes.c_int
     lib.moe_ep_forward.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, vp, vp]
+    lib.moe_ep_forward_dep.restype = ctypes.c_int
+    lib.moe_ep_forward_dep.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, ctypes.c_double, i32, vp, vp]
     lib.moe_ep_get_routing.restype = ctypes.c_int
     lib.moe_ep_get_routing.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp]
     lib.moe_ep_set_profiling.restype = ctypes.c_int
@@ -268,7 +284,7 @@ class MoeEp:
         if rc != 0:
             self._ctx = ctypes.c_void_p()
             raise MoeEpError(rc, "moe_ep_create failed (no usable HIP device or out of memory)")
-        self._last = (0, 0, 0)
+        self._last = (0, 0, 0, 1)
 
     # -- moe_ep_forward -------------------------------------------------------------------
     def forward(self, tokens, gate_logits, routed_w, shared_w, top_k: int, r_chunks: int = 1,
@@ -284,15 +300,30 @@ class MoeEp:
                                       stream)
         if rc != 0:
             raise MoeEpError(rc, self.last_error())
-        self._last = (n_tokens, top_k, int(self._lib.moe_ep_last_chunks(self._ctx)))
+        self._last = (n_tokens, top_k, int(self._lib.moe_ep_last_chunks(self._ctx)), 1)
+        return rc
+
+    # -- moe_ep_forward_dep ---------------------------------------------------------------
+    def forward_dep(self, tokens, gate_logits, routed_w, shared_w, top_k: int, r_1: int = 1, r_2: int = 1,
+                    dep_order: int = 0, attn_us: float = 0.0, n_tokens: Optional[int] = None, out=None,
+                    stream: Optional[int] = None) -> int:
+        if n_tokens is None:
+            n_tokens = int(tokens.shape[0])
+        if stream is None:
+            import torch
+            stream = torch.cuda.current_stream().cuda_stream
+        rc = self._lib.moe_ep_forward_dep(self._ctx, _ptr(tokens), _ptr(gate_logits), _ptr(routed_w),
+                                          _ptr(shared_w), top_k, r_1, r_2, dep_order, float(attn_us),
+                                          n_tokens, _ptr(out), stream)
+        if rc != 0:
+            raise MoeEpError(rc, self.last_error())
+        self._last = (n_tokens, top_k, r_1 * r_2, r_1)
         return rc
 
     # -- moe_ep_get_routing ---------------------------------------------------------------
     def get_routing(self, chunk: int = 0) -> Dict[str, np.ndarray]:
-        T, k, r = self._last
-        Tc = (T + r - 1) // r if r else 0
-        t0 = chunk * Tc
-        Tn = 0 if t0 >= T else min(Tc, T - t0)
+        T, k, r, r_1 = self._last
+        t0, Tn = chunk_range(T, r_1, r // r_1 if r_1 else 1, chunk) if r else (0, 0)
         El = self.cfg.n_local
         idx = np.zeros((Tn, k), dtype=np.int32)
         w = np.zeros((Tn, k), dtype=np.float32)

@@ -28,6 +28,9 @@ hipError_t launch_combine(const void* y, const int32_t* pos, const float* w, int
 
 // ---- chunk transfers over the host link (pinned-host mode); bytes must be a multiple of 4
 hipError_t launch_copy(void* dst, const void* src, size_t bytes, int grid, hipStream_t s);
+// a one-wavefront kernel that lasts about `microseconds` (at most 1 s): stand-in for a task that
+// runs on other hardware
+hipError_t launch_busy(double microseconds, hipStream_t s);
 
 // ---- expert projections as one grouped GEMM launch (Sec. 3.1, Eq. moe_detail / shared_detail)
 struct GemmArgs {

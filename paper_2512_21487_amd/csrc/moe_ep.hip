@@ -20,7 +20,7 @@ using namespace moe_ep;
 
 namespace {
 
-enum Stage { ST_ROUTER = 0, ST_PARTITION, ST_GEMM1, ST_GEMM2, ST_SGEMM1, ST_SGEMM2, ST_COMBINE, ST_TOTAL, ST_COPY_IN, ST_COPY_OUT, ST_COUNT };
+enum Stage { ST_ROUTER = 0, ST_PARTITION, ST_GEMM1, ST_GEMM2, ST_SGEMM1, ST_SGEMM2, ST_COMBINE, ST_TOTAL, ST_COPY_IN, ST_COPY_OUT, ST_ATTN, ST_COUNT };
 
 struct ProfSpan { hipEvent_t a, b; int stage; int forward; };
 
@@ -45,8 +45,13 @@ struct moe_ep_ctx {
     hipStream_t s_in = nullptr, s_out = nullptr;  // the two link directions (pinned-host mode)
     hipEvent_t ev_start = nullptr, ev_done = nullptr, ev_comp_done = nullptr;
     std::vector<hipEvent_t> ev_in, ev_comp;
-    // last forward (for moe_ep_get_routing)
-    int last_T = -1, last_k = 0, last_r = 0;
+    // attention-group side of moe_ep_forward_dep, created at its first call: the stream the attention
+    // stand-ins and the shared experts run on, and per micro-batch "attention done" / "shared done"
+    hipStream_t s_ag = nullptr;
+    hipEvent_t ev_ag_done = nullptr;
+    std::vector<hipEvent_t> ev_attn, ev_shared;
+    // last forward (for moe_ep_get_routing): tokens, top_k, chunks = micro-batches x chunks of each
+    int last_T = -1, last_k = 0, last_r = 0, last_r1 = 1;
     // stage profiling
     int prof_depth = 0, prof_recorded = 0;
     uint32_t prof_mask = ~0u;
@@ -199,6 +204,10 @@ int moe_ep_destroy(moe_ep_ctx* ctx)
     (void)hipDeviceSynchronize();  // forwards still in flight on the caller's streams use the workspaces
     for (hipEvent_t e : ctx->ev_in) (void)hipEventDestroy(e);
     for (hipEvent_t e : ctx->ev_comp) (void)hipEventDestroy(e);
+    for (hipEvent_t e : ctx->ev_attn) (void)hipEventDestroy(e);
+    for (hipEvent_t e : ctx->ev_shared) (void)hipEventDestroy(e);
+    if (ctx->ev_ag_done) (void)hipEventDestroy(ctx->ev_ag_done);
+    if (ctx->s_ag) (void)hipStreamDestroy(ctx->s_ag);
     for (hipEvent_t e : ctx->prof_pool) (void)hipEventDestroy(e);
     if (ctx->ev_start) (void)hipEventDestroy(ctx->ev_start);
     if (ctx->ev_done) (void)hipEventDestroy(ctx->ev_done);
@@ -299,7 +308,7 @@ int moe_ep_set_profiling(moe_ep_ctx* ctx, int32_t depth)
     if (!ctx || depth < 0 || depth > 256) return MOE_EP_EINVAL;
     HIP_TRY(ctx, hipSetDevice(ctx->cfg.device));
     HIP_TRY(ctx, hipDeviceSynchronize());
-    const size_t per_forward = 2 * ((size_t)ctx->cfg.max_chunks * 10 + 4);
+    const size_t per_forward = 2 * ((size_t)ctx->cfg.max_chunks * 12 + 4);
     const size_t want = (size_t)depth * per_forward;
     while (ctx->prof_pool.size() < want) {
         hipEvent_t e = nullptr;
@@ -367,25 +376,36 @@ int moe_ep_get_stage_ms(moe_ep_ctx* ctx, float* ms, int32_t n)
     return MOE_EP_OK;
 }
 
-int moe_ep_forward(moe_ep_ctx* ctx, const void* tokens, const float* gate_logits,
-                   const void* routed_w, const void* shared_w, int32_t top_k, int32_t r_chunks,
-                   int32_t order, int32_t n_tokens, void* out, void* stream)
+}  // extern "C"
+
+namespace {
+
+// The tokens of a forward are cut into r_1 micro-batches of ceil(T / r_1) tokens and every
+// micro-batch into r_2 chunks of ceil(micro-batch / r_2) tokens (Sec. 2.3); chunk c = i * r_2 + j.
+void chunk_range(int T, int r_1, int r_2, int c, int* t0, int* Tn)
 {
-    if (!ctx) return MOE_EP_EINVAL;
-    const char* why = nullptr;
-    if (moe_ep_validate_forward(&ctx->cfg, tokens, gate_logits, routed_w, shared_w, top_k, r_chunks,
-                                order, n_tokens, out, &why) != MOE_EP_OK)
-        return fail(ctx, MOE_EP_EINVAL, why);
-    ctx->err[0] = 0;
-    if (r_chunks == 0) {
-        if (!ctx->has_model) return fail(ctx, MOE_EP_ESTATE, "r_chunks == 0 needs moe_ep_set_pipeline_model first");
-        r_chunks = moe_ep_choose_chunks(&ctx->model, n_tokens, ctx->cfg.max_chunks);
-    }
+    const int Tm = (T + r_1 - 1) / r_1, i = c / r_2, j = c % r_2;
+    const int mb0 = i * Tm, mb1 = mb0 + Tm < T ? mb0 + Tm : T;
+    const int Tc = (Tm + r_2 - 1) / r_2;
+    int a = mb0 + j * Tc, b = a + Tc;
+    if (b > mb1) b = mb1;
+    if (a > b) a = b;
+    if (a < 0 || mb0 >= T) { a = T; b = T; }
+    *t0 = a;
+    *Tn = b - a;
+}
+
+// dep = false: moe_ep_forward (r_1 = 1, `order` is a moe_ep_order).  dep = true: moe_ep_forward_dep
+// (`order` is a moe_ep_dep_order, attention stand-ins of attn_us microseconds per micro-batch).
+int forward_impl(moe_ep_ctx* ctx, const void* tokens, const float* gate_logits, const void* routed_w,
+                 const void* shared_w, int32_t top_k, int32_t r_1, int32_t r_2, int32_t order, bool dep,
+                 double attn_us, int32_t n_tokens, void* out, void* stream)
+{
     const moe_ep_config& c = ctx->cfg;
-    const int T = n_tokens, k = top_k, r = r_chunks;
+    const int T = n_tokens, k = top_k, r = r_1 * r_2;
     const int M = c.hidden, H = c.inter, E = c.n_experts, El = c.n_local, e0 = c.local_begin;
     const int Ns = c.n_shared, Hs = c.shared_inter;
-    ctx->last_T = T; ctx->last_k = k; ctx->last_r = r;
+    ctx->last_T = T; ctx->last_k = k; ctx->last_r = r; ctx->last_r1 = r_1;
     if (T == 0) return MOE_EP_OK;
     HIP_TRY(ctx, hipSetDevice(c.device));
 
@@ -429,16 +449,18 @@ int moe_ep_forward(moe_ep_ctx* ctx, const void* tokens, const float* gate_logits
     };
     const int link_grid = ctx->link_grid;
     const int span_total = prof_begin(ctx, prof, ST_TOTAL, user);
+    hipStream_t s_ag = dep ? ctx->s_ag : user;  // attention stand-ins and, in dep mode, the shared experts
+    if (pinned || dep) HIP_TRY(ctx, hipEventRecord(ctx->ev_start, user));
     if (pinned) {
-        HIP_TRY(ctx, hipEventRecord(ctx->ev_start, user));
         HIP_TRY(ctx, hipStreamWaitEvent(s_in, ctx->ev_start, 0));
         HIP_TRY(ctx, hipStreamWaitEvent(s_out, ctx->ev_start, 0));
     }
-    const int Tc = (T + r - 1) / r;
+    if (dep) HIP_TRY(ctx, hipStreamWaitEvent(s_ag, ctx->ev_start, 0));
     const int bw_grid = n_cu * 8;  // bandwidth kernels: 8 workgroups of 4 wavefronts per CU
 
     // shared experts of token range [t0, t0+Tn) -> output rows [t0, t0+Tn); the aggregation adds to them
-    auto run_shared = [&](int t0, int Tn) -> int {
+    auto run_shared = [&](int t0, int Tn, hipStream_t st) -> int {
+        if (Tn <= 0) return MOE_EP_OK;
         GemmArgs g1{};
         g1.A = tok_dev + (size_t)t0 * M; g1.W = sw; g1.C = ctx->hs + (size_t)t0 * Ns * Hs;
         g1.offset = nullptr; g1.mt_prefix = nullptr; g1.G = Ns; g1.dense_rows = Tn;
@@ -447,50 +469,103 @@ int moe_ep_forward(moe_ep_ctx* ctx, const void* tokens, const float* gate_logits
         g1.kseg_len = M; g1.w_kseg_stride = 0; g1.c_group_col_stride = Hs;
         const int sbm = grouped_gemm_row_tile(ctx->shared_variant);
         const int mt = (Tn + sbm - 1) / sbm;
-        int sp = prof_begin(ctx, prof, ST_SGEMM1, s_comp);
-        HIP_TRY(ctx, launch_grouped_gemm(g1, true, ctx->shared_variant, n_cu, mt * Ns, s_comp));
-        prof_end(ctx, sp, s_comp);
+        int sp = prof_begin(ctx, prof, ST_SGEMM1, st);
+        HIP_TRY(ctx, launch_grouped_gemm(g1, true, ctx->shared_variant, n_cu, mt * Ns, st));
+        prof_end(ctx, sp, st);
         GemmArgs g2{};
         g2.A = ctx->hs + (size_t)t0 * Ns * Hs; g2.W = sw + (size_t)2 * Hs * M; g2.C = out_dev + (size_t)t0 * M;
         g2.offset = nullptr; g2.mt_prefix = nullptr; g2.G = 1; g2.dense_rows = Tn;
         g2.K = Ns * Hs; g2.N = M; g2.lda = Ns * Hs; g2.ldc = M; g2.ldw = Hs;
         g2.w_group_stride = 0; g2.w_up_offset = 0;
         g2.kseg_len = Hs; g2.w_kseg_stride = (long long)3 * Hs * M; g2.c_group_col_stride = 0;
-        sp = prof_begin(ctx, prof, ST_SGEMM2, s_comp);
-        HIP_TRY(ctx, launch_grouped_gemm(g2, false, ctx->shared_variant, n_cu, mt, s_comp));
-        prof_end(ctx, sp, s_comp);
+        sp = prof_begin(ctx, prof, ST_SGEMM2, st);
+        HIP_TRY(ctx, launch_grouped_gemm(g2, false, ctx->shared_variant, n_cu, mt, st));
+        prof_end(ctx, sp, st);
         return MOE_EP_OK;
     };
+    auto micro_batch_range = [&](int i, int* t0, int* Tn) {
+        int a, n, b, m;
+        chunk_range(T, r_1, r_2, i * r_2, &a, &n);
+        chunk_range(T, r_1, r_2, i * r_2 + r_2 - 1, &b, &m);
+        *t0 = a;
+        *Tn = b + m - a;
+    };
 
-    // inbound transfers: all chunks are queued at once on their own stream
-    if (pinned) {
-        for (int cidx = 0; cidx < r; ++cidx) {
-            const int t0 = cidx * Tc;
-            const int Tn = t0 >= T ? 0 : (T - t0 < Tc ? T - t0 : Tc);
-            const int sp_in = prof_begin(ctx, prof && Tn > 0, ST_COPY_IN, s_in);
-            if (Tn > 0) {
-                HIP_TRY(ctx, link_copy(static_cast<char*>(ctx->d_tokens) + (size_t)t0 * M * 2,
-                                         h_tokens + (size_t)t0 * M * 2, (size_t)Tn * M * 2, link_grid, s_in));
-                HIP_TRY(ctx, link_copy(ctx->d_logits + (size_t)t0 * E, h_logits + (size_t)t0 * E * 4,
-                                         (size_t)Tn * E * 4, link_grid, s_in));
+    // inbound transfer of chunk cidx on the inbound link stream
+    auto enqueue_inbound = [&](int cidx) -> int {
+        int t0, Tn;
+        chunk_range(T, r_1, r_2, cidx, &t0, &Tn);
+        const int sp_in = prof_begin(ctx, prof && Tn > 0, ST_COPY_IN, s_in);
+        if (Tn > 0) {
+            HIP_TRY(ctx, link_copy(static_cast<char*>(ctx->d_tokens) + (size_t)t0 * M * 2,
+                                     h_tokens + (size_t)t0 * M * 2, (size_t)Tn * M * 2, link_grid, s_in));
+            HIP_TRY(ctx, link_copy(ctx->d_logits + (size_t)t0 * E, h_logits + (size_t)t0 * E * 4,
+                                     (size_t)Tn * E * 4, link_grid, s_in));
+        }
+        prof_end(ctx, sp_in, s_in);
+        HIP_TRY(ctx, hipEventRecord(ctx->ev_in[cidx], s_in));
+        return MOE_EP_OK;
+    };
+    if (dep) {
+        // Attention-group side (Sec. 2.3, Fig. as): per micro-batch an attention stand-in, then its
+        // tokens may leave for the experts (rule 6), and its shared experts run on the same stream
+        // either right behind its attention (ASAS) or behind the last attention (AASS).  Every
+        // event is recorded, in host order, before anything is told to wait for it.
+        auto shared_of_micro_batch = [&](int i) -> int {
+            if (Ns > 0) {
+                int t0, Tn;
+                micro_batch_range(i, &t0, &Tn);
+                // in the stand-in the token rows reach the GPU through the inbound link
+                if (pinned) HIP_TRY(ctx, hipStreamWaitEvent(s_ag, ctx->ev_in[i * r_2 + r_2 - 1], 0));
+                const int rc = run_shared(t0, Tn, s_ag);
+                if (rc != MOE_EP_OK) return rc;
             }
-            prof_end(ctx, sp_in, s_in);
-            HIP_TRY(ctx, hipEventRecord(ctx->ev_in[cidx], s_in));
+            HIP_TRY(ctx, hipEventRecord(ctx->ev_shared[i], s_ag));
+            return MOE_EP_OK;
+        };
+        for (int i = 0; i < r_1; ++i) {
+            const int sp_at = prof_begin(ctx, prof && attn_us > 0.0, ST_ATTN, s_ag);
+            HIP_TRY(ctx, launch_busy(attn_us, s_ag));
+            prof_end(ctx, sp_at, s_ag);
+            HIP_TRY(ctx, hipEventRecord(ctx->ev_attn[i], s_ag));
+            if (pinned) {
+                HIP_TRY(ctx, hipStreamWaitEvent(s_in, ctx->ev_attn[i], 0));
+                for (int j = 0; j < r_2; ++j) {
+                    const int rc = enqueue_inbound(i * r_2 + j);
+                    if (rc != MOE_EP_OK) return rc;
+                }
+            }
+            if (order == MOE_EP_DEP_ASAS) {
+                const int rc = shared_of_micro_batch(i);
+                if (rc != MOE_EP_OK) return rc;
+            }
+        }
+        if (order == MOE_EP_DEP_AASS)
+            for (int i = 0; i < r_1; ++i) {
+                const int rc = shared_of_micro_batch(i);
+                if (rc != MOE_EP_OK) return rc;
+            }
+    } else if (pinned) {
+        // all chunks are queued at once on their own stream
+        for (int cidx = 0; cidx < r; ++cidx) {
+            const int rc = enqueue_inbound(cidx);
+            if (rc != MOE_EP_OK) return rc;
         }
     }
-    if (Ns > 0 && order == MOE_EP_ORDER_SHARED_FIRST) {
+    if (!dep && Ns > 0 && order == MOE_EP_ORDER_SHARED_FIRST) {
         if (pinned) HIP_TRY(ctx, hipStreamWaitEvent(s_comp, ctx->ev_in[r - 1], 0));
-        int rc = run_shared(0, T);
+        int rc = run_shared(0, T, s_comp);
         if (rc != MOE_EP_OK) return rc;
     }
 
     for (int cidx = 0; cidx < r; ++cidx) {
-        const int t0 = cidx * Tc;
-        const int Tn = t0 >= T ? 0 : (T - t0 < Tc ? T - t0 : Tc);
+        int t0, Tn;
+        chunk_range(T, r_1, r_2, cidx, &t0, &Tn);
         int32_t* count = ctx->count + (size_t)cidx * El;
         int32_t* offset = ctx->offset + (size_t)cidx * (El + 1);
         int32_t* mt_prefix = ctx->mt_prefix + (size_t)cidx * (El + 1);
         if (pinned) HIP_TRY(ctx, hipStreamWaitEvent(s_comp, ctx->ev_in[cidx], 0));
+        else if (dep && cidx % r_2 == 0) HIP_TRY(ctx, hipStreamWaitEvent(s_comp, ctx->ev_attn[cidx / r_2], 0));
         const int nblk = (Tn + kTokPerBlock - 1) / kTokPerBlock;
         const int variant = ctx->gemm_variant;
         const int BMv = grouped_gemm_row_tile(variant);
@@ -543,10 +618,12 @@ int moe_ep_forward(moe_ep_ctx* ctx, const void* tokens, const float* gate_logits
         HIP_TRY(ctx, launch_grouped_gemm(g2, false, variant, n_cu, max_row_tiles, s_comp));
         prof_end(ctx, sp, s_comp);
 
-        if (Ns > 0 && order == MOE_EP_ORDER_INTERLEAVED) {
-            int rc = run_shared(t0, Tn);
+        if (!dep && Ns > 0 && order == MOE_EP_ORDER_INTERLEAVED) {
+            int rc = run_shared(t0, Tn, s_comp);
             if (rc != MOE_EP_OK) return rc;
         }
+        // the aggregation adds to what the micro-batch's shared experts have written (attention-group stream)
+        if (dep && Ns > 0) HIP_TRY(ctx, hipStreamWaitEvent(s_comp, ctx->ev_shared[cidx / r_2], 0));
 
         sp = prof_begin(ctx, prof, ST_COMBINE, s_comp);
         HIP_TRY(ctx, launch_combine(ctx->y, pos, w, Tn, k, M, Ns > 0, out_dev + (size_t)t0 * M, bw_grid, s_comp));
@@ -568,9 +645,66 @@ int moe_ep_forward(moe_ep_ctx* ctx, const void* tokens, const float* gate_logits
         HIP_TRY(ctx, hipEventRecord(ctx->ev_done, s_out));
         HIP_TRY(ctx, hipStreamWaitEvent(user, ctx->ev_done, 0));
     }
+    if (dep) {
+        HIP_TRY(ctx, hipEventRecord(ctx->ev_ag_done, s_ag));
+        HIP_TRY(ctx, hipStreamWaitEvent(user, ctx->ev_ag_done, 0));
+    }
     prof_end(ctx, span_total, user);
     if (prof) ctx->prof_recorded++;
     return MOE_EP_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int moe_ep_forward(moe_ep_ctx* ctx, const void* tokens, const float* gate_logits,
+                   const void* routed_w, const void* shared_w, int32_t top_k, int32_t r_chunks,
+                   int32_t order, int32_t n_tokens, void* out, void* stream)
+{
+    if (!ctx) return MOE_EP_EINVAL;
+    const char* why = nullptr;
+    if (moe_ep_validate_forward(&ctx->cfg, tokens, gate_logits, routed_w, shared_w, top_k, r_chunks,
+                                order, n_tokens, out, &why) != MOE_EP_OK)
+        return fail(ctx, MOE_EP_EINVAL, why);
+    ctx->err[0] = 0;
+    if (r_chunks == 0) {
+        if (!ctx->has_model) return fail(ctx, MOE_EP_ESTATE, "r_chunks == 0 needs moe_ep_set_pipeline_model first");
+        r_chunks = moe_ep_choose_chunks(&ctx->model, n_tokens, ctx->cfg.max_chunks);
+    }
+    return forward_impl(ctx, tokens, gate_logits, routed_w, shared_w, top_k, 1, r_chunks, order, false, 0.0,
+                        n_tokens, out, stream);
+}
+
+int moe_ep_forward_dep(moe_ep_ctx* ctx, const void* tokens, const float* gate_logits,
+                       const void* routed_w, const void* shared_w, int32_t top_k, int32_t r_1, int32_t r_2,
+                       int32_t dep_order, double attn_us, int32_t n_tokens, void* out, void* stream)
+{
+    if (!ctx) return MOE_EP_EINVAL;
+    const char* why = nullptr;
+    if (r_1 < 1 || r_2 < 1 || (long long)r_1 * r_2 > ctx->cfg.max_chunks)
+        return fail(ctx, MOE_EP_EINVAL, "r_1 and r_2 must be at least 1 and r_1 * r_2 at most max_chunks");
+    if (dep_order != MOE_EP_DEP_ASAS && dep_order != MOE_EP_DEP_AASS) return fail(ctx, MOE_EP_EINVAL, "dep_order must be MOE_EP_DEP_ASAS or MOE_EP_DEP_AASS");
+    if (!(attn_us >= 0.0) || attn_us > 1e6) return fail(ctx, MOE_EP_EINVAL, "attn_us must be in 0..1e6");
+    if (moe_ep_validate_forward(&ctx->cfg, tokens, gate_logits, routed_w, shared_w, top_k, r_1 * r_2,
+                                MOE_EP_ORDER_INTERLEAVED, n_tokens, out, &why) != MOE_EP_OK)
+        return fail(ctx, MOE_EP_EINVAL, why);
+    ctx->err[0] = 0;
+    HIP_TRY(ctx, hipSetDevice(ctx->cfg.device));
+    if (!ctx->s_ag) {  // first call: the attention-group stream and its events
+        const unsigned ev_flags = hipEventDisableTiming;
+        HIP_TRY(ctx, hipStreamCreateWithFlags(&ctx->s_ag, hipStreamNonBlocking));
+        HIP_TRY(ctx, hipEventCreateWithFlags(&ctx->ev_ag_done, ev_flags));
+        for (int i = 0; i < ctx->cfg.max_chunks; ++i) {
+            hipEvent_t a = nullptr, b = nullptr;
+            HIP_TRY(ctx, hipEventCreateWithFlags(&a, ev_flags));
+            ctx->ev_attn.push_back(a);
+            HIP_TRY(ctx, hipEventCreateWithFlags(&b, ev_flags));
+            ctx->ev_shared.push_back(b);
+        }
+    }
+    return forward_impl(ctx, tokens, gate_logits, routed_w, shared_w, top_k, r_1, r_2, dep_order, true, attn_us,
+                        n_tokens, out, stream);
 }
 
 int moe_ep_get_routing(moe_ep_ctx* ctx, int32_t chunk, int32_t* idx, float* w, int32_t* pos,
@@ -580,9 +714,9 @@ int moe_ep_get_routing(moe_ep_ctx* ctx, int32_t chunk, int32_t* idx, float* w, i
     if (ctx->last_T < 0) return fail(ctx, MOE_EP_ESTATE, "no forward has run yet");
     if (chunk < 0 || chunk >= ctx->last_r) return fail(ctx, MOE_EP_EINVAL, "chunk out of range");
     const moe_ep_config& c = ctx->cfg;
-    const int T = ctx->last_T, k = ctx->last_k, r = ctx->last_r, El = c.n_local;
-    const int Tc = (T + r - 1) / r, t0 = chunk * Tc;
-    const int Tn = t0 >= T ? 0 : (T - t0 < Tc ? T - t0 : Tc);
+    const int T = ctx->last_T, k = ctx->last_k, El = c.n_local;
+    int t0 = 0, Tn = 0;
+    if (T > 0) chunk_range(T, ctx->last_r1, ctx->last_r / ctx->last_r1, chunk, &t0, &Tn);
     HIP_TRY(ctx, hipSetDevice(c.device));
     HIP_TRY(ctx, hipDeviceSynchronize());
     if (T == 0) {

@@ -36,4 +36,25 @@ hipError_t launch_copy(void* dst, const void* src, size_t bytes, int grid, hipSt
     return hipGetLastError();
 }
 
+// Stand-in for an attention-group task of a given duration (Sec. 2.3: the attention of a
+// micro-batch runs on other GPUs; here only its place in the schedule matters): one wavefront that
+// sleeps until the constant 100 MHz wall clock has advanced by `ticks`, or until `max_polls` polls
+// have passed, whichever comes first, so that the kernel ends whatever the clock does.
+__global__ __launch_bounds__(64) void busy_kernel(long long ticks, int max_polls)
+{
+    const long long t0 = wall_clock64();
+    for (int i = 0; i < max_polls && wall_clock64() - t0 < ticks; ++i) __builtin_amdgcn_s_sleep(32);
+}
+
+hipError_t launch_busy(double microseconds, hipStream_t s)
+{
+    if (!(microseconds > 0.0)) return hipSuccess;
+    if (microseconds > 1e6) return hipErrorInvalidValue;
+    const long long ticks = (long long)(microseconds * 100.0);
+    // a poll (s_sleep 32 = about 2048 cycles) takes at least half a microsecond at any clock the part runs at
+    const int max_polls = (int)(microseconds * 4.0) + 64;
+    hipLaunchKernelGGL(busy_kernel, dim3(1), dim3(64), 0, s, ticks, max_polls);
+    return hipGetLastError();
+}
+
 }  // namespace moe_ep

@@ -55,3 +55,13 @@ def run_forward(ctx: pkg.MoeEp, wl: MoEWorkload, d: DeviceInputs, r=1, order=0, 
     ctx.forward(d.tokens, d.logits, d.routed, d.shared, wl.top_k, r, order, n_tokens=T, out=d.out)
     torch.cuda.synchronize()
     return d.out.cpu().numpy().view(np.uint16)[:T].copy()
+
+
+def run_forward_dep(ctx: pkg.MoeEp, wl: MoEWorkload, d: DeviceInputs, r_1=1, r_2=1, dep_order=0, attn_us=0.0):
+    """One moe_ep_forward_dep through the C ABI; returns the output as uint16 bf16 bits (host)."""
+    d.out.zero_()
+    torch.cuda.synchronize()
+    ctx.forward_dep(d.tokens, d.logits, d.routed, d.shared, wl.top_k, r_1, r_2, dep_order, attn_us,
+                    n_tokens=d.T, out=d.out)
+    torch.cuda.synchronize()
+    return d.out.cpu().numpy().view(np.uint16)[:d.T].copy()

@@ -1,0 +1,135 @@
+"""moe_ep_forward_dep on the GPU: the layer run as the disaggregated schedule of Sec. 2.3 (micro-batches,
+attention stand-ins, shared experts on the attention-group stream in ASAS / AASS order) gives the bits of
+the plain forward, its routing matches the oracle chunk by chunk, and its measured timeline obeys the
+rules of Eq. limitation."""
+import numpy as np
+import pytest
+
+import oracle
+from workloads import CONFIGS, bf16_bits_to_f32, make_inputs, tiny_workload
+from helpers import rel_err
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+ASAS, AASS = 0, 1
+
+
+def _gpu():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import gpu_util
+    return gpu_util
+
+
+def _wl():
+    return tiny_workload(name="dep_layer", n_tokens=700, hidden=256, inter=192, n_experts=16, local_begin=2,
+                         n_local=12, top_k=3, n_shared=1, shared_inter=256)
+
+
+@pytest.mark.parametrize("pinned", [False, True])
+def test_same_bits_as_the_plain_forward_for_every_schedule(pinned):
+    g = _gpu()
+    wl = _wl()
+    inp = make_inputs(wl, seed=51)
+    ctx = g.make_ctx(wl, max_chunks=12, pinned=pinned)
+    d = g.DeviceInputs(wl, inp, pinned=pinned)
+    base = g.run_forward(ctx, wl, d, r=1)
+    ref = oracle.forward(inp["tokens"], inp["gate_logits"], inp["routed_w"], inp["shared_w"], hidden=wl.hidden,
+                         inter=wl.inter, n_experts=wl.n_experts, local_begin=wl.local_begin, n_local=wl.n_local,
+                         n_shared=wl.n_shared, shared_inter=wl.shared_inter, top_k=wl.top_k, r_chunks=1)
+    assert rel_err(bf16_bits_to_f32(base), ref["out"]) <= 2e-2
+    for r_1, r_2, order, attn_us in ((1, 1, ASAS, 0.0), (3, 2, ASAS, 50.0), (3, 2, AASS, 50.0), (4, 3, AASS, 0.0),
+                                     (2, 1, ASAS, 200.0), (12, 1, AASS, 5.0)):
+        print(f"[case] dep r_1={r_1} r_2={r_2} order={order} attn_us={attn_us} pinned={pinned}", flush=True)
+        out = g.run_forward_dep(ctx, wl, d, r_1, r_2, order, attn_us)
+        assert np.array_equal(out, base), (r_1, r_2, order)
+    # routing of chunk (i, j) = the oracle's routing of the same token range
+    g.run_forward_dep(ctx, wl, d, 3, 2, ASAS, 0.0)
+    import paper_2512_21487_amd as pkg
+    for c in range(6):
+        t0, Tn = pkg.binding.chunk_range(wl.n_tokens, 3, 2, c)
+        got = ctx.get_routing(c)
+        assert np.array_equal(got["idx"], ref["idx"][t0:t0 + Tn])
+        assert got["idx"].shape[0] == Tn and got["count"].sum() == (got["pos"] >= 0).sum()
+    ctx.destroy()
+
+
+def test_no_shared_experts_and_more_micro_batches_than_tokens():
+    g = _gpu()
+    wl = tiny_workload(name="dep_small", n_tokens=5, hidden=64, inter=64, n_experts=8, n_local=8, top_k=2)
+    inp = make_inputs(wl, seed=52)
+    ctx = g.make_ctx(wl, max_chunks=16)
+    d = g.DeviceInputs(wl, inp)
+    base = g.run_forward(ctx, wl, d, r=1)
+    for r_1, r_2, order in ((8, 2, ASAS), (1, 16, AASS), (16, 1, ASAS)):
+        print(f"[case] dep_small r_1={r_1} r_2={r_2} order={order}", flush=True)
+        assert np.array_equal(g.run_forward_dep(ctx, wl, d, r_1, r_2, order, 10.0), base)
+    ctx.destroy()
+
+
+def test_bad_schedule_arguments_are_rejected():
+    g = _gpu()
+    import paper_2512_21487_amd as pkg
+    wl = CONFIGS["tiny"]
+    ctx = g.make_ctx(wl, max_chunks=8)
+    d = g.DeviceInputs(wl, make_inputs(wl))
+    for r_1, r_2, order, attn_us in ((0, 1, ASAS, 0.0), (1, 0, ASAS, 0.0), (3, 3, ASAS, 0.0), (1, 1, 2, 0.0),
+                                     (1, 1, ASAS, -1.0), (1, 1, ASAS, 2e6), (1, 1, ASAS, float("nan"))):
+        with pytest.raises(pkg.MoeEpError) as ei:
+            g.run_forward_dep(ctx, wl, d, r_1, r_2, order, attn_us)
+        assert ei.value.code == -1
+    ctx.destroy()
+
+
+@pytest.mark.parametrize("order", [ASAS, AASS])
+def test_measured_timeline_obeys_the_rules(order):
+    """Eq. limitation on the measured schedule (moe_ep_get_timeline) of a pinned-host run with r_1 = 3,
+    r_2 = 2: the attention group runs one task at a time in the order asked for (rules 1, 2), a
+    micro-batch's inbound copies start after its attention (rule 6), a chunk's experts after its inbound
+    copy (rule 7), its outbound copy after its aggregation (rule 8), its aggregation after the
+    micro-batch's shared experts, links and experts take their chunks in order (rules 3-5), and the
+    attention stand-ins last about as long as asked."""
+    g = _gpu()
+    wl = _wl()
+    r_1, r_2, attn_us = 3, 2, 300.0
+    ctx = g.make_ctx(wl, max_chunks=8, pinned=True)
+    d = g.DeviceInputs(wl, make_inputs(wl, seed=53), pinned=True)
+    g.run_forward_dep(ctx, wl, d, r_1, r_2, order, attn_us)
+    ctx.set_profiling(1)
+    g.run_forward_dep(ctx, wl, d, r_1, r_2, order, attn_us)
+    tl = ctx.get_timeline()
+    ctx.get_stage_ms()
+    ctx.set_profiling(0)
+    by = {}
+    for name, fwd, b, e in tl:
+        assert fwd == 0 and e >= b >= 0.0
+        by.setdefault(name, []).append((b, e))
+    eps = 2e-3
+    assert len(by["attention"]) == r_1 and len(by["shared_gate_up_gemm"]) == r_1 and len(by["shared_down_gemm"]) == r_1
+    for b, e in by["attention"]:
+        assert 0.8 * attn_us <= (e - b) * 1e3 <= 2.0 * attn_us + 50.0
+    for name in ("copy_in", "router", "routed_gate_up_gemm", "routed_down_gemm", "aggregation", "copy_out"):
+        assert len(by[name]) == r_1 * r_2, name
+        for (b0, e0), (b1, e1) in zip(by[name], by[name][1:]):
+            assert b1 >= e0 - eps, f"{name}: two tasks overlap on one resource"
+    # the attention group's sequence
+    ag = []
+    for i in range(r_1):
+        ag.append(("a", i, by["attention"][i]))
+        ag.append(("s", i, (by["shared_gate_up_gemm"][i][0], by["shared_down_gemm"][i][1])))
+    want = [("a", i) if x == 0 else ("s", i) for i in range(r_1) for x in (0, 1)] if order == ASAS else \
+           [("a", i) for i in range(r_1)] + [("s", i) for i in range(r_1)]
+    ag.sort(key=lambda t: t[2][0])
+    assert [(k, i) for k, i, _ in ag] == want
+    for (_, _, (b0, e0)), (_, _, (b1, e1)) in zip(ag, ag[1:]):
+        assert b1 >= e0 - eps
+    for i in range(r_1):
+        for j in range(r_2):
+            c = i * r_2 + j
+            assert by["copy_in"][c][0] >= by["attention"][i][1] - eps            # rule 6
+            assert by["router"][c][0] >= by["copy_in"][c][1] - eps               # rule 7
+            assert by["aggregation"][c][0] >= by["shared_down_gemm"][i][1] - eps
+            assert by["copy_out"][c][0] >= by["aggregation"][c][1] - eps         # rule 8
+    assert by["forward"][0][1] >= max(by["copy_out"][-1][1], by["shared_down_gemm"][-1][1]) - eps
+    ctx.destroy()

@@ -334,14 +334,18 @@ for pinned in (False, True):
     for r, order in ((1, 0), (4, 1)):
         out = g.run_forward(ctx, wl, d, r=r, order=order)
         print(hashlib.sha256(out.tobytes()).hexdigest())
+    for r_1, r_2, dep_order in ((2, 2, 0), (4, 2, 1)):
+        out = g.run_forward_dep(ctx, wl, d, r_1, r_2, dep_order, 30.0)
+        print(hashlib.sha256(out.tobytes()).hexdigest())
     ctx.destroy()
 """
 
 
 def test_serialised_launches_give_the_same_bits():
-    """The event graph between the three streams is the race surface: with every launch made
-    blocking (HIP_LAUNCH_BLOCKING=1, AMD_SERIALIZE_KERNEL=3) the outputs must be the bits of the
-    asynchronous run, in device and pinned-host mode, chunked and not."""
+    """The event graph between the streams is the race surface: with every launch made blocking
+    (HIP_LAUNCH_BLOCKING=1, AMD_SERIALIZE_KERNEL=3) the outputs must be the bits of the asynchronous
+    run, in device and pinned-host mode, chunked and not, through moe_ep_forward and through
+    moe_ep_forward_dep (attention-group stream, both orders)."""
     import subprocess
     import sys
     here = os.path.dirname(os.path.abspath(__file__))
@@ -352,7 +356,7 @@ def test_serialised_launches_give_the_same_bits():
         p = subprocess.run([sys.executable, "-c", script], capture_output=True, text=True, env=env, timeout=300)
         assert p.returncode == 0, p.stderr[-2000:]
         digests.append([l for l in p.stdout.split() if len(l) == 64])
-    assert len(digests[0]) == 4 and digests[0] == digests[1]
+    assert len(digests[0]) == 8 and digests[0] == digests[1]
     assert len(set(digests[0])) == 1  # and chunking, order and I/O mode change nothing either
 
 
