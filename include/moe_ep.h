@@ -252,6 +252,15 @@ typedef enum { MOE_EP_DEP_ASAS = 0, MOE_EP_DEP_AASS = 1 } moe_ep_dep_order;
  * rules, its makespan is not the paper's.  Not for stream capture (the first call creates the
  * attention-group stream).
  */
+/*
+ * Host only: the token range [*first, *first + *count) of chunk `chunk` = i * r_2 + j when n_tokens
+ * are cut into r_1 micro-batches of ceil(n_tokens / r_1) tokens and each micro-batch into r_2 chunks
+ * of ceil(micro-batch / r_2) tokens (Sec. 2.3; the last micro-batches and chunks may be short or
+ * empty).  moe_ep_forward uses r_1 = 1, r_2 = r_chunks.  MOE_EP_EINVAL on arguments out of range.
+ */
+int moe_ep_chunk_range(int32_t n_tokens, int32_t r_1, int32_t r_2, int32_t chunk, int32_t *first,
+                       int32_t *count);
+
 int moe_ep_forward_dep(moe_ep_ctx *ctx, const void *tokens, const float *gate_logits,
                        const void *routed_w, const void *shared_w, int32_t top_k, int32_t r_1,
                        int32_t r_2, int32_t dep_order, double attn_us, int32_t n_tokens, void *out,

@@ -23,17 +23,12 @@ _STATUS = {0: "OK", -1: "EINVAL", -2: "ENOMEM", -3: "EHIP", -4: "ESTATE"}
 
 
 def chunk_range(T: int, r_1: int, r_2: int, c: int):
-    """(first token, tokens) of chunk c = i * r_2 + j: r_1 micro-batches of ceil(T / r_1) tokens, each
-    cut into r_2 chunks of ceil(micro-batch / r_2) tokens (argument marshalling for get_routing)."""
-    Tm = (T + r_1 - 1) // r_1
-    i, j = divmod(c, r_2)
-    mb0 = i * Tm
-    if mb0 >= T:
-        return T, 0
-    mb1 = min(T, mb0 + Tm)
-    Tc = (Tm + r_2 - 1) // r_2
-    a = min(mb0 + j * Tc, mb1)
-    return a, min(a + Tc, mb1) - a
+    """moe_ep_chunk_range: (first token, tokens) of chunk c = i * r_2 + j."""
+    first, count = ctypes.c_int32(0), ctypes.c_int32(0)
+    rc = load_library().moe_ep_chunk_range(T, r_1, r_2, c, ctypes.byref(first), ctypes.byref(count))
+    if rc != 0:
+        raise ValueError("moe_ep_chunk_range: arguments out of range")
+    return first.value, count.value
 
 
 class MoeEpError(RuntimeError):
@@ -114,6 +109,8 @@ def load_library() -> ctypes.CDLL:
     lib.moe_ep_forward.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, vp, vp]
     lib.moe_ep_forward_dep.restype = ctypes.c_int
     lib.moe_ep_forward_dep.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, ctypes.c_double, i32, vp, vp]
+    lib.moe_ep_chunk_range.restype = ctypes.c_int
+    lib.moe_ep_chunk_range.argtypes = [i32, i32, i32, i32, vp, vp]
     lib.moe_ep_get_routing.restype = ctypes.c_int
     lib.moe_ep_get_routing.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp]
     lib.moe_ep_set_profiling.restype = ctypes.c_int

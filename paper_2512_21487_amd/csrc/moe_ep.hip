@@ -658,6 +658,17 @@ int forward_impl(moe_ep_ctx* ctx, const void* tokens, const float* gate_logits, 
 
 extern "C" {
 
+int moe_ep_chunk_range(int32_t n_tokens, int32_t r_1, int32_t r_2, int32_t chunk, int32_t* first, int32_t* count)
+{
+    if (n_tokens < 0 || r_1 < 1 || r_2 < 1 || chunk < 0 || (long long)chunk >= (long long)r_1 * r_2 || !first || !count)
+        return MOE_EP_EINVAL;
+    int t0 = 0, Tn = 0;
+    if (n_tokens > 0) chunk_range(n_tokens, r_1, r_2, chunk, &t0, &Tn);
+    *first = t0;
+    *count = Tn;
+    return MOE_EP_OK;
+}
+
 int moe_ep_forward(moe_ep_ctx* ctx, const void* tokens, const float* gate_logits,
                    const void* routed_w, const void* shared_w, int32_t top_k, int32_t r_chunks,
                    int32_t order, int32_t n_tokens, void* out, void* stream)

@@ -104,3 +104,37 @@ def test_forward_edge_arguments_that_are_legal():
     args = dict(base, shared_w=None, order=77)                     # order ignored without shared
     assert pkg.validate_forward(noshared, **args)[0] == 0
     assert pkg.validate_forward(noshared, **dict(args, shared_w=0x4000))[0] == -1
+
+
+def test_chunk_ranges_partition_the_tokens():
+    """moe_ep_chunk_range (host only): the r_1 * r_2 chunks tile [0, n_tokens) in order, a micro-batch
+    holds ceil(n_tokens / r_1) tokens except the last ones, a chunk ceil(micro-batch / r_2) except the
+    last ones of its micro-batch, chunks never straddle micro-batches, and r_1 = 1 is the ceil(n / r)
+    cut moe_ep_forward documents (Sec. 2.3)."""
+    from paper_2512_21487_amd.binding import chunk_range
+    for T in (0, 1, 5, 64, 700, 4097):
+        for r_1 in (1, 2, 3, 7, 16):
+            for r_2 in (1, 2, 5):
+                Tm = -(-T // r_1) if T else 0
+                Tc = -(-Tm // r_2) if Tm else 0
+                pos = 0
+                for c in range(r_1 * r_2):
+                    t0, n = chunk_range(T, r_1, r_2, c)
+                    i, j = divmod(c, r_2)
+                    assert 0 <= n <= Tc
+                    if n:
+                        assert t0 == pos and i * Tm <= t0 and t0 + n <= min(T, (i + 1) * Tm)
+                        assert t0 == i * Tm + j * Tc
+                        pos = t0 + n
+                    else:
+                        assert t0 <= T
+                assert pos == T
+                if r_1 == 1:
+                    for c in range(r_2):
+                        want0 = min(c * Tc, T)
+                        assert chunk_range(T, 1, r_2, c) == (want0, min(Tc, T - want0))
+    lib = pkg.load_library()
+    a, b = ctypes.c_int32(), ctypes.c_int32()
+    for args in ((-1, 1, 1, 0), (8, 0, 1, 0), (8, 1, 0, 0), (8, 2, 2, 4), (8, 2, 2, -1)):
+        assert lib.moe_ep_chunk_range(*args, ctypes.byref(a), ctypes.byref(b)) == -1
+    assert lib.moe_ep_chunk_range(8, 1, 1, 0, None, ctypes.byref(b)) == -1
