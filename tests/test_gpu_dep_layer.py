@@ -133,3 +133,41 @@ def test_measured_timeline_obeys_the_rules(order):
             assert by["copy_out"][c][0] >= by["aggregation"][c][1] - eps         # rule 8
     assert by["forward"][0][1] >= max(by["copy_out"][-1][1], by["shared_down_gemm"][-1][1]) - eps
     ctx.destroy()
+
+
+@pytest.mark.parametrize("seed", list(range(10)))
+def test_seeded_random_layers_match_the_oracle(seed):
+    """Ten seeded random layer shapes (K extents from one to nine 64-wide steps, experts with and
+    without tokens, local subsets, zero to two shared experts, Zipf skew or none) through
+    moe_ep_forward with a random chunk count and through moe_ep_forward_dep with a random schedule:
+    routing bit-exact, outputs within the tolerance, and the two entry points give the same bits."""
+    g = _gpu()
+    rng = np.random.default_rng(1000 + seed)
+    n_experts = int(rng.choice([4, 8, 24, 64]))
+    n_local = int(rng.integers(1, n_experts + 1))
+    local_begin = int(rng.integers(0, n_experts - n_local + 1))
+    n_shared = int(rng.integers(0, 3))
+    wl = tiny_workload(name=f"random{seed}", n_tokens=int(rng.integers(1, 900)), hidden=64 * int(rng.integers(1, 10)),
+                       inter=64 * int(rng.integers(1, 7)), n_experts=n_experts, local_begin=local_begin,
+                       n_local=n_local, top_k=int(rng.integers(1, min(n_experts, 8) + 1)), n_shared=n_shared,
+                       shared_inter=64 * int(rng.integers(1, 5)) if n_shared else 0,
+                       zipf_s=float(rng.choice([0.0, 1.2])))
+    inp = make_inputs(wl, seed=seed)
+    r = int(rng.integers(1, 7))
+    r_1, r_2 = int(rng.integers(1, 4)), int(rng.integers(1, 4))
+    pinned = bool(rng.integers(0, 2))
+    print(f"[case] {wl} r={r} r_1={r_1} r_2={r_2} pinned={pinned}", flush=True)
+    ref = oracle.forward(inp["tokens"], inp["gate_logits"], inp["routed_w"], inp["shared_w"], hidden=wl.hidden,
+                         inter=wl.inter, n_experts=wl.n_experts, local_begin=wl.local_begin, n_local=wl.n_local,
+                         n_shared=wl.n_shared, shared_inter=wl.shared_inter, top_k=wl.top_k, r_chunks=1)
+    ctx = g.make_ctx(wl, max_chunks=9, pinned=pinned)
+    d = g.DeviceInputs(wl, inp, pinned=pinned)
+    out = g.run_forward(ctx, wl, d, r=r, order=int(rng.integers(0, 2)))
+    import paper_2512_21487_amd as pkg
+    for c in range(r):
+        t0, Tn = pkg.binding.chunk_range(wl.n_tokens, 1, r, c)
+        assert np.array_equal(ctx.get_routing(c)["idx"], ref["idx"][t0:t0 + Tn])
+    assert rel_err(bf16_bits_to_f32(out), ref["out"]) <= 2e-2
+    out_dep = g.run_forward_dep(ctx, wl, d, r_1, r_2, int(rng.integers(0, 2)), float(rng.choice([0.0, 20.0])))
+    assert np.array_equal(out_dep, out)
+    ctx.destroy()
