@@ -57,16 +57,14 @@ struct GemmCfg {
     // MFMAs between two hand-overs, and over how many of them (counted from the hand-over that
     // frees the slot) a wavefront spreads the RPW loads of one K step: a load blocks the
     // wavefront's instruction stream until the CU's memory pipeline takes it, so loads issued
-    // faster than that pipeline drains stall the MFMAs queued behind them.  A two-slot ring keeps
-    // the last k16 step before the next hand-over free, so that the last load has time to land.
-#ifndef MOE_EP_ISSUE_WINDOW_2
-#define MOE_EP_ISSUE_WINDOW_2 (KKW * MB * NB - MB * NB > RPW ? KKW * MB * NB - MB * NB : RPW)
-#endif
-#ifndef MOE_EP_ISSUE_WINDOW_N
-#define MOE_EP_ISSUE_WINDOW_N (KKW * MB * NB)
+    // faster than that pipeline drains stall the MFMAs queued behind them.  The last k16 step
+    // before the next hand-over stays free: in a two-slot ring the last load needs that time to
+    // land, and the deeper rings measure about 1 % faster with it than with the whole K step.
+#ifndef MOE_EP_ISSUE_WINDOW
+#define MOE_EP_ISSUE_WINDOW (KKW * MB * NB - MB * NB > RPW ? KKW * MB * NB - MB * NB : RPW)
 #endif
     static constexpr int SLOTS = KKW * MB * NB;
-    static constexpr int WINDOW = STAGES == 2 ? (MOE_EP_ISSUE_WINDOW_2) : (MOE_EP_ISSUE_WINDOW_N);
+    static constexpr int WINDOW = MOE_EP_ISSUE_WINDOW;
     static_assert(WINDOW >= RPW && WINDOW <= SLOTS, "at most one load per MFMA between two hand-overs");
     // the load issued behind MFMA number p after a hand-over, or -1
     static constexpr int load_at(int p)
