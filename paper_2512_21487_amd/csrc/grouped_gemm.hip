@@ -85,12 +85,15 @@ __device__ __forceinline__ float silu_f(float g)
 // read has returned (gfx9 encoding: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[5:4] << 14)
 #define MOE_EP_WAIT_VMCNT_LGKM0(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | (((n) >> 4) << 14) | 0x0070)
 
+constexpr int kMaxGroups = 512;
+constexpr int kTileCache = 32;  // tiles per workgroup whose coordinates are decoded ahead (4 ints each)
+
 // All tiles of one shape that a workgroup owns.  Ragged mode reads the groups from LDS tables the
 // caller has filled: s_pref[g] = row tiles of this shape before group g (s_pref[G] = all of them),
 // s_row0[g] / s_rowend[g] = the rows of group g this shape covers.
 template <int BM, int BN, int BK, int STAGES, int WGM, int WGN, bool SWIGLU, bool RAGGED>
 __device__ __forceinline__ void gemm_tiles(const GemmArgs& a, uint4* lds, const int* s_pref, const int* s_row0,
-                                           const int* s_rowend)
+                                           const int* s_rowend, int* s_tile)
 {
     using Cfg = GemmCfg<BM, BN, BK, STAGES, WGM, WGN, SWIGLU>;
     constexpr int MB = Cfg::MB, NB = Cfg::NB, RPW = Cfg::RPW, XRPW = Cfg::XRPW, NW = Cfg::NW;
@@ -128,8 +131,8 @@ __device__ __forceinline__ void gemm_tiles(const GemmArgs& a, uint4* lds, const 
     // and one activation panel are checked by the launcher to span less than 2^32 bytes)
     uint32_t goff[RPW];
 
-    // tile number it of this workgroup -> coordinates, Xi / Wi / goff; false past the last tile
-    auto setup_tile = [&](int it, Tile& t) __attribute__((always_inline)) -> bool {
+    // tile number it of this workgroup -> coordinates; false past the last tile
+    auto decode_tile = [&](int it, int& g, int& row0, int& nrows, int& n0) -> bool {
         const int L = (it * 8 + xcd) * per_xcd + slot;
         if (L >= total) return false;
         // tile id -> (group, row tile, column tile): inside a group the row tiles are taken in bands
@@ -137,7 +140,7 @@ __device__ __forceinline__ void gemm_tiles(const GemmArgs& a, uint4* lds, const 
         // consecutive ids (one XCD's share) then covers about kBand row panels x 32/kBand
         // weight panels instead of 32 x 1, which is what that XCD's L2 has to fetch.
         constexpr int kBand = 8;
-        int g, mi, ni, row0, nrows, mt_g, l;
+        int mi, ni, mt_g, l;
         if (RAGGED) {
             int lo = 0, hi = a.G;
             while (hi - lo > 1) {
@@ -167,12 +170,33 @@ __device__ __forceinline__ void gemm_tiles(const GemmArgs& a, uint4* lds, const 
             row0 = mi * BM;
             nrows = min(BM, a.dense_rows - row0);
         }
+        n0 = ni * BN_OUT;
+        return true;
+    };
+    // The search and the divisions of a tile's coordinates would sit in the middle of a K loop, once
+    // per tile and wavefront, with the matrix pipe waiting: the workgroup's first kTileCache tiles
+    // are decoded once, one per thread, before the first tile starts.
+    for (int it = tid; it < kTileCache; it += THREADS) {
+        int g = -1, row0 = 0, nrows = 0, n0 = 0;
+        if (!decode_tile(it, g, row0, nrows, n0)) g = -1;
+        s_tile[4 * it + 0] = g; s_tile[4 * it + 1] = row0; s_tile[4 * it + 2] = nrows; s_tile[4 * it + 3] = n0;
+    }
+    __syncthreads();
+    // tile number it of this workgroup -> coordinates, Xi / Wi / goff; false past the last tile
+    auto setup_tile = [&](int it, Tile& t) __attribute__((always_inline)) -> bool {
+        int g, row0, nrows, n0;
+        if (it < kTileCache) {
+            g = s_tile[4 * it + 0]; row0 = s_tile[4 * it + 1]; nrows = s_tile[4 * it + 2]; n0 = s_tile[4 * it + 3];
+            if (g < 0) return false;
+        } else if (!decode_tile(it, g, row0, nrows, n0)) {
+            return false;
+        }
         // the coordinates came through LDS; telling the compiler they are wavefront-uniform keeps
         // base addresses in scalar registers and leaves the lanes 32-bit offsets only
         t.g = __builtin_amdgcn_readfirstlane(g);
         t.row0 = __builtin_amdgcn_readfirstlane(row0);
         t.nrows = __builtin_amdgcn_readfirstlane(nrows);
-        t.n0 = __builtin_amdgcn_readfirstlane(ni * BN_OUT);
+        t.n0 = __builtin_amdgcn_readfirstlane(n0);
         Wi = a.W + (size_t)t.g * a.w_group_stride;
         Xi = mapped ? a.A : a.A + (size_t)t.row0 * a.lda;
 #pragma unroll
@@ -396,14 +420,13 @@ __device__ __forceinline__ void gemm_tiles(const GemmArgs& a, uint4* lds, const 
 #undef MOE_EP_FRAG1
 }
 
-constexpr int kMaxGroups = 512;
 
 // one tile shape for all groups (the ragged groups' row-tile prefix comes from the dispatch scan)
 template <int BM, int BN, int BK, int STAGES, int WGM, int WGN, bool SWIGLU, bool RAGGED>
 __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_kernel(GemmArgs a)
 {
     extern __shared__ uint4 lds[];
-    __shared__ int s_pref[kMaxGroups + 1], s_row0[kMaxGroups + 1], s_rowend[kMaxGroups + 1];
+    __shared__ int s_pref[kMaxGroups + 1], s_row0[kMaxGroups + 1], s_rowend[kMaxGroups + 1], s_tile[4 * kTileCache];
     if (RAGGED) {
         for (int i = threadIdx.x; i <= a.G; i += WGM * WGN * 64) {
             s_pref[i] = a.mt_prefix[i];
@@ -412,7 +435,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_kernel(GemmArgs a)
         }
         __syncthreads();
     }
-    gemm_tiles<BM, BN, BK, STAGES, WGM, WGN, SWIGLU, RAGGED>(a, lds, s_pref, s_row0, s_rowend);
+    gemm_tiles<BM, BN, BK, STAGES, WGM, WGN, SWIGLU, RAGGED>(a, lds, s_pref, s_row0, s_rowend, s_tile);
 }
 
 // Two tile shapes in one launch, ragged groups only: the rows of a group are covered by tall tiles
@@ -426,7 +449,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_two_shape_kernel(G
 {
     static_assert(WGM * WGN * 64 >= 64 && BMA > BMB, "tall tiles first");
     extern __shared__ uint4 lds[];
-    __shared__ int s_pref[kMaxGroups + 1], s_row0[kMaxGroups + 1], s_rowend[kMaxGroups + 1];
+    __shared__ int s_pref[kMaxGroups + 1], s_row0[kMaxGroups + 1], s_rowend[kMaxGroups + 1], s_tile[4 * kTileCache];
     const int tid = threadIdx.x;
     // exclusive prefix sum of per-group tile counts by the first wavefront: 8 groups per lane,
     // then a scan over the lanes
@@ -464,9 +487,9 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_two_shape_kernel(G
         __syncthreads();
     };
     fill(true);
-    gemm_tiles<BMA, BN, BKA, STA, WGM, WGN, SWIGLU, true>(a, lds, s_pref, s_row0, s_rowend);
+    gemm_tiles<BMA, BN, BKA, STA, WGM, WGN, SWIGLU, true>(a, lds, s_pref, s_row0, s_rowend, s_tile);
     fill(false);  // its first barrier also separates the two passes' use of the ring
-    gemm_tiles<BMB, BN, BKB, STB, WGM, WGN, SWIGLU, true>(a, lds, s_pref, s_row0, s_rowend);
+    gemm_tiles<BMB, BN, BKB, STB, WGM, WGN, SWIGLU, true>(a, lds, s_pref, s_row0, s_rowend, s_tile);
 }
 
 // what every kernel here assumes of its arguments beyond the shapes the caller has checked
