@@ -118,7 +118,12 @@ int moe_ep_create(const moe_ep_config *cfg, moe_ep_ctx **out_ctx);
  *               host, so it may be recorded into a HIP graph (stream capture) and replayed.
  *
  * tokens / gate_logits / out are device pointers in MOE_EP_IO_DEVICE mode and pinned host
- * pointers in MOE_EP_IO_PINNED_HOST mode.  The caller owns every buffer passed in; the
+ * pointers in MOE_EP_IO_PINNED_HOST mode.  Before anything is enqueued the runtime is asked what
+ * each of the five pointers points at: one that is not GPU-addressable memory of the kind the mode
+ * needs, or that lies in an allocation which ends before the bytes the forward will touch, gives
+ * MOE_EP_EINVAL and a message naming the argument (the environment variable
+ * MOE_EP_CHECK_POINTERS=0, read by moe_ep_create, skips the device-side queries; a bad pointer is
+ * then a GPU memory fault).  The caller owns every buffer passed in; the
  * library owns its workspaces.  n_tokens == 0 is a no-op.  Results are deterministic:
  * the same inputs give the same bits, for every r_chunks and order.
  */

@@ -166,6 +166,22 @@ def _ptr(x) -> Optional[int]:
     raise TypeError(f"cannot take the address of {type(x)}")
 
 
+def _check_tensor(x, name: str, n_bytes: int, want_pinned: bool) -> None:
+    """Marshalling check of a torch tensor argument: dense, at least ``n_bytes`` long and resident where
+    the call will read it (raw addresses pass through; the library queries those itself)."""
+    if x is None or not hasattr(x, "is_contiguous"):
+        return
+    if not x.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    have = x.numel() * x.element_size()
+    if have < n_bytes:
+        raise ValueError(f"{name} holds {have} bytes, the forward needs {n_bytes}")
+    if want_pinned and not (x.device.type == "cpu" and x.is_pinned()):
+        raise ValueError(f"{name} must be a pinned host tensor in IO_PINNED_HOST mode")
+    if not want_pinned and not (x.is_cuda or x.is_pinned()):
+        raise ValueError(f"{name} must be a device tensor")
+
+
 def validate_config(cfg: MoeEpConfig) -> Tuple[int, str]:
     why = ctypes.c_char_p()
     rc = load_library().moe_ep_validate_config(ctypes.byref(cfg), ctypes.byref(why))
@@ -283,6 +299,16 @@ class MoeEp:
             raise MoeEpError(rc, "moe_ep_create failed (no usable HIP device or out of memory)")
         self._last = (0, 0, 0, 1)
 
+    def _check_forward_tensors(self, tokens, gate_logits, routed_w, shared_w, n_tokens, out) -> None:
+        c = self.cfg
+        pinned = c.io_mode == IO_PINNED_HOST
+        T = max(int(n_tokens), 0)
+        _check_tensor(tokens, "tokens", T * c.hidden * 2, pinned)
+        _check_tensor(gate_logits, "gate_logits", T * c.n_experts * 4, pinned)
+        _check_tensor(out, "out", T * c.hidden * 2, pinned)
+        _check_tensor(routed_w, "routed_w", c.n_local * 3 * c.inter * c.hidden * 2, False)
+        _check_tensor(shared_w, "shared_w", c.n_shared * 3 * c.shared_inter * c.hidden * 2, False)
+
     # -- moe_ep_forward -------------------------------------------------------------------
     def forward(self, tokens, gate_logits, routed_w, shared_w, top_k: int, r_chunks: int = 1,
                 order: int = ORDER_SHARED_FIRST, n_tokens: Optional[int] = None, out=None,
@@ -292,6 +318,7 @@ class MoeEp:
         if stream is None:
             import torch
             stream = torch.cuda.current_stream().cuda_stream
+        self._check_forward_tensors(tokens, gate_logits, routed_w, shared_w, n_tokens, out)
         rc = self._lib.moe_ep_forward(self._ctx, _ptr(tokens), _ptr(gate_logits), _ptr(routed_w),
                                       _ptr(shared_w), top_k, r_chunks, order, n_tokens, _ptr(out),
                                       stream)
@@ -309,6 +336,7 @@ class MoeEp:
         if stream is None:
             import torch
             stream = torch.cuda.current_stream().cuda_stream
+        self._check_forward_tensors(tokens, gate_logits, routed_w, shared_w, n_tokens, out)
         rc = self._lib.moe_ep_forward_dep(self._ctx, _ptr(tokens), _ptr(gate_logits), _ptr(routed_w),
                                           _ptr(shared_w), top_k, r_1, r_2, dep_order, float(attn_us),
                                           n_tokens, _ptr(out), stream)

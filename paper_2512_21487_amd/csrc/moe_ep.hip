@@ -34,6 +34,7 @@ struct moe_ep_ctx {
     bool fused_gather = true;  // the gate/up projection gathers the token rows itself (no grouped copy)
     int link_grid = 8;         // workgroups of a host-link copy kernel
     bool memcpy_in = false, memcpy_out = false;  // host-link copies through the runtime instead of kernels
+    bool check_spans = true;   // every forward asks the runtime what its pointer arguments point at
     // device workspaces
     void* d_tokens = nullptr; float* d_logits = nullptr; void* d_out = nullptr;  // pinned-host mode staging
     int32_t* idx = nullptr; float* w = nullptr; int32_t* pos = nullptr; int32_t* perm = nullptr;
@@ -118,6 +119,44 @@ int fail(moe_ep_ctx* ctx, int code, const char* what, hipError_t e = hipSuccess)
         hipError_t e__ = (call);                                                \
         if (e__ != hipSuccess) return fail((ctx), MOE_EP_EHIP, #call, e__);     \
     } while (0)
+
+// What the kernels are about to read or write through a caller's pointer: memory the GPU can
+// address, of at least `bytes` bytes where the runtime knows the allocation's extent.  Turns a host
+// pointer or an undersized buffer into an error before a kernel faults on it.  Returns nullptr when
+// the span is usable, else what is wrong with it.  `want_host`: pinned host memory is required
+// (the link stand-ins of MOE_EP_IO_PINNED_HOST); *dev_ptr receives the address kernels use.
+const char* check_span(const void* p, size_t bytes, bool want_host, const void** dev_ptr)
+{
+    hipPointerAttribute_t attr;
+    if (hipPointerGetAttributes(&attr, p) != hipSuccess) {
+        (void)hipGetLastError();
+        return want_host ? "must be pinned host memory in MOE_EP_IO_PINNED_HOST mode" : "is not memory the GPU can address";
+    }
+    if (want_host) {
+        if (attr.type != hipMemoryTypeHost || attr.devicePointer == nullptr)
+            return "must be pinned host memory in MOE_EP_IO_PINNED_HOST mode";
+        if (dev_ptr) *dev_ptr = attr.devicePointer;
+        return nullptr;
+    }
+    if (dev_ptr) *dev_ptr = p;
+    if (attr.type == hipMemoryTypeHost) {  // pinned host memory works (at the host link's rate)
+        if (attr.devicePointer == nullptr) return "is host memory the GPU cannot address";
+        if (dev_ptr) *dev_ptr = attr.devicePointer;
+        return nullptr;
+    }
+    if (attr.type != hipMemoryTypeDevice && attr.type != hipMemoryTypeManaged && attr.type != hipMemoryTypeUnified)
+        return "is not memory the GPU can address";
+    hipDeviceptr_t base = nullptr;
+    size_t size = 0;
+    if (hipMemGetAddressRange(&base, &size, const_cast<void*>(p)) != hipSuccess) {
+        (void)hipGetLastError();  // mapped ranges without one owner: extent unknown, nothing to compare
+        return nullptr;
+    }
+    const char* lo = static_cast<const char*>(base);
+    const char* q = static_cast<const char*>(p);
+    if (q < lo || (size_t)(lo + size - q) < bytes) return "points at an allocation smaller than the forward needs";
+    return nullptr;
+}
 
 hipEvent_t prof_event(moe_ep_ctx* ctx)
 {
@@ -246,6 +285,8 @@ int moe_ep_create(const moe_ep_config* cfg, moe_ep_ctx** out_ctx)
         ctx->memcpy_out = v[0] == '1' || v[0] == 'o';
     }
     ctx->fused_gather = fused_gather_enabled();
+    // MOE_EP_CHECK_POINTERS=0 skips the per-forward pointer queries (a few microseconds of host time)
+    if (const char* v = getenv("MOE_EP_CHECK_POINTERS")) ctx->check_spans = atoi(v) != 0;
     if (grouped_gemm_init() != hipSuccess) { delete ctx; return MOE_EP_EHIP; }
 
     const WsLayout L = ws_layout(*cfg);
@@ -405,8 +446,10 @@ int forward_impl(moe_ep_ctx* ctx, const void* tokens, const float* gate_logits, 
     const int T = n_tokens, k = top_k, r = r_1 * r_2;
     const int M = c.hidden, H = c.inter, E = c.n_experts, El = c.n_local, e0 = c.local_begin;
     const int Ns = c.n_shared, Hs = c.shared_inter;
-    ctx->last_T = T; ctx->last_k = k; ctx->last_r = r; ctx->last_r1 = r_1;
-    if (T == 0) return MOE_EP_OK;
+    if (T == 0) {
+        ctx->last_T = T; ctx->last_k = k; ctx->last_r = r; ctx->last_r1 = r_1;
+        return MOE_EP_OK;
+    }
     HIP_TRY(ctx, hipSetDevice(c.device));
 
     hipStream_t user = static_cast<hipStream_t>(stream);
@@ -424,24 +467,32 @@ int forward_impl(moe_ep_ctx* ctx, const void* tokens, const float* gate_logits, 
     const uint16_t* rw = static_cast<const uint16_t*>(routed_w);
     const uint16_t* sw = static_cast<const uint16_t*>(shared_w);
 
-    // pinned-host mode: the copy kernels address the host buffers directly, so they must be
-    // pinned (page-locked, device-visible) memory; anything else is rejected here
+    // What every pointer argument points at is checked before anything is enqueued.  Pinned-host
+    // mode: the copy kernels address the host buffers directly, so they must be pinned
+    // (page-locked, device-visible) memory; that check is never skipped, it yields the device addresses.
     const char* h_tokens = nullptr; const char* h_logits = nullptr; char* h_out = nullptr;
-    if (pinned) {
-        const void* in[3] = {tokens, gate_logits, out};
-        void* dev[3] = {nullptr, nullptr, nullptr};
-        for (int i = 0; i < 3; ++i) {
-            hipPointerAttribute_t attr;
-            if (hipPointerGetAttributes(&attr, in[i]) != hipSuccess || attr.type != hipMemoryTypeHost ||
-                attr.devicePointer == nullptr) {
-                (void)hipGetLastError();
-                return fail(ctx, MOE_EP_EINVAL, "tokens, gate_logits and out must be pinned host memory in MOE_EP_IO_PINNED_HOST mode");
+    {
+        struct Span { const void* p; size_t bytes; bool host; const char* name; };
+        Span sp[5] = {
+            {tokens, (size_t)T * M * 2, pinned, "tokens"},
+            {gate_logits, (size_t)T * E * 4, pinned, "gate_logits"},
+            {out, (size_t)T * M * 2, pinned, "out"},
+            {routed_w, (size_t)El * 3 * H * M * 2, false, "routed_w"},
+            {shared_w, (size_t)Ns * 3 * Hs * M * 2, false, "shared_w"},
+        };
+        for (const Span& x : sp) {
+            if (!x.p || !(x.host || ctx->check_spans)) continue;
+            const void* dev = nullptr;
+            if (const char* bad = check_span(x.p, x.bytes, x.host, &dev)) {
+                snprintf(ctx->err, sizeof ctx->err, "%s %s", x.name, bad);
+                return MOE_EP_EINVAL;
             }
-            dev[i] = attr.devicePointer;
+            if (&x == &sp[0]) h_tokens = static_cast<const char*>(dev);
+            if (&x == &sp[1]) h_logits = static_cast<const char*>(dev);
+            if (&x == &sp[2]) h_out = static_cast<char*>(const_cast<void*>(dev));
         }
-        h_tokens = static_cast<const char*>(dev[0]); h_logits = static_cast<const char*>(dev[1]);
-        h_out = static_cast<char*>(dev[2]);
     }
+    ctx->last_T = T; ctx->last_k = k; ctx->last_r = r; ctx->last_r1 = r_1;
     auto link_copy = [&](void* dst, const void* src, size_t bytes, int grid, hipStream_t st) -> hipError_t {
         if (st == s_in ? ctx->memcpy_in : ctx->memcpy_out)
             return bytes ? hipMemcpyAsync(dst, src, bytes, hipMemcpyDefault, st) : hipSuccess;

@@ -138,3 +138,20 @@ def test_chunk_ranges_partition_the_tokens():
     for args in ((-1, 1, 1, 0), (8, 0, 1, 0), (8, 1, 0, 0), (8, 2, 2, 4), (8, 2, 2, -1)):
         assert lib.moe_ep_chunk_range(*args, ctypes.byref(a), ctypes.byref(b)) == -1
     assert lib.moe_ep_chunk_range(8, 1, 1, 0, None, ctypes.byref(b)) == -1
+
+
+def test_tensor_marshalling_checks():
+    """The binding's tensor checks (size, density, placement) need no GPU."""
+    torch = pytest.importorskip("torch")
+    from paper_2512_21487_amd.binding import _check_tensor
+    t = torch.zeros((8, 64), dtype=torch.int16)
+    _check_tensor(None, "shared_w", 0, False)
+    _check_tensor(12345, "tokens", 1 << 20, False)          # raw addresses are the library's to check
+    with pytest.raises(ValueError, match="holds 1024 bytes"):
+        _check_tensor(t, "tokens", 1025, True)
+    with pytest.raises(ValueError, match="contiguous"):
+        _check_tensor(t.t(), "tokens", 16, True)
+    with pytest.raises(ValueError, match="pinned host tensor"):
+        _check_tensor(t, "tokens", 1024, True)
+    with pytest.raises(ValueError, match="device tensor"):
+        _check_tensor(t, "tokens", 1024, False)

@@ -431,6 +431,74 @@ def test_errors_surface_as_status_codes():
     ctx.destroy()
 
 
+def test_pointers_the_gpu_cannot_use_are_rejected_before_any_launch():
+    """Raw addresses (which the binding passes through unchecked) of pageable host memory, of pinned
+    memory in the wrong mode and of a device allocation that ends before the forward's extent give
+    MOE_EP_EINVAL naming the argument; nothing is enqueued and the context stays usable."""
+    import ctypes
+    g = _gpu()
+    import paper_2512_21487_amd as pkg
+    wl = CONFIGS["tiny"]
+    inp = make_inputs(wl)
+    ctx = g.make_ctx(wl)
+    d = g.DeviceInputs(wl, inp)
+    good = g.run_forward(ctx, wl, d)
+    args = dict(tokens=d.tokens.data_ptr(), logits=d.logits.data_ptr(), routed=d.routed.data_ptr(),
+                shared=d.shared.data_ptr(), out=d.out.data_ptr())
+
+    def call(**swap):
+        a = dict(args, **swap)
+        ctx.forward(a["tokens"], a["logits"], a["routed"], a["shared"], wl.top_k, 1, 0,
+                    n_tokens=wl.n_tokens, out=a["out"])
+
+    pageable = np.ascontiguousarray(inp["tokens"])
+    with pytest.raises(pkg.MoeEpError) as ei:
+        call(tokens=pageable.ctypes.data)
+    assert ei.value.code == -1 and "tokens" in str(ei.value)
+    host_w = np.ascontiguousarray(inp["routed_w"])
+    with pytest.raises(pkg.MoeEpError) as ei:
+        call(routed=host_w.ctypes.data)
+    assert ei.value.code == -1 and "routed_w" in str(ei.value)
+    # a device allocation of its own that is too short for [T, M] bf16
+    hip = ctypes.CDLL("libamdhip64.so")
+    small = ctypes.c_void_p()
+    assert hip.hipMalloc(ctypes.byref(small), ctypes.c_size_t(4096)) == 0
+    try:
+        base, size = ctypes.c_void_p(), ctypes.c_size_t()
+        assert hip.hipMemGetAddressRange(ctypes.byref(base), ctypes.byref(size), small) == 0
+        assert (base.value, size.value) == (small.value, 4096)  # what the library will be told
+        with pytest.raises(pkg.MoeEpError) as ei:
+            call(out=small.value)
+        assert ei.value.code == -1 and "out" in str(ei.value) and "smaller" in str(ei.value)
+    finally:
+        assert hip.hipFree(small) == 0
+    assert np.array_equal(g.run_forward(ctx, wl, d), good)
+    ctx.destroy()
+    # pinned-host mode wants pinned host memory for the three streamed buffers
+    pctx = g.make_ctx(wl, pinned=True)
+    pd = g.DeviceInputs(wl, inp, pinned=True)
+    with pytest.raises(pkg.MoeEpError) as ei:
+        pctx.forward(d.tokens.data_ptr(), pd.logits.data_ptr(), pd.routed.data_ptr(), pd.shared.data_ptr(),
+                     wl.top_k, 1, 0, n_tokens=wl.n_tokens, out=pd.out.data_ptr())
+    assert ei.value.code == -1 and "tokens" in str(ei.value) and "pinned" in str(ei.value)
+    assert np.array_equal(g.run_forward(pctx, wl, pd), good)
+    pctx.destroy()
+
+
+def test_binding_rejects_tensors_of_the_wrong_size_or_place():
+    g = _gpu()
+    wl = CONFIGS["tiny"]
+    ctx = g.make_ctx(wl)
+    d = g.DeviceInputs(wl, make_inputs(wl))
+    with pytest.raises(ValueError, match="out holds"):
+        ctx.forward(d.tokens, d.logits, d.routed, d.shared, wl.top_k, 1, 0, out=d.out[: wl.n_tokens // 2])
+    with pytest.raises(ValueError, match="tokens must be contiguous"):
+        ctx.forward(d.tokens.t(), d.logits, d.routed, d.shared, wl.top_k, 1, 0, n_tokens=wl.n_tokens, out=d.out)
+    with pytest.raises(ValueError, match="gate_logits must be a device tensor"):
+        ctx.forward(d.tokens, d.logits.cpu(), d.routed, d.shared, wl.top_k, 1, 0, out=d.out)
+    ctx.destroy()
+
+
 # ------------------------------------------------------------------ full-size configurations
 def _sampled_parity(name, variants, pinned=False, n_sample=24):
     """At the benchmark's sizes: routing of every token bit-exact, outputs of sampled tokens
