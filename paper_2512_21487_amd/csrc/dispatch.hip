@@ -2,7 +2,7 @@
 // a deterministic, stable counting sort in three steps.
 //   scan     per expert, exclusive prefix over the 64-token workgroups of the router's
 //            bit-mask populations -> first row of every (workgroup, expert) pair, the
-//            per-expert counts, their prefix sum and the prefix of row tiles
+//            per-expert counts and their prefix sum
 //   permute  every assignment finds its row: expert base + workgroup base + number of
 //            earlier tokens of the workgroup with the same expert (a popcount)
 //   gather   the token rows are copied into expert-grouped order, 16 bytes per lane
@@ -12,9 +12,8 @@
 namespace moe_ep {
 
 __global__ __launch_bounds__(1024) void dispatch_scan_kernel(
-    const unsigned long long* __restrict__ blk_mask, int nblk, int El, int BM,
-    int32_t* __restrict__ blk_off, int32_t* __restrict__ count, int32_t* __restrict__ offset,
-    int32_t* __restrict__ mt_prefix)
+    const unsigned long long* __restrict__ blk_mask, int nblk, int El,
+    int32_t* __restrict__ blk_off, int32_t* __restrict__ count, int32_t* __restrict__ offset)
 {
     __shared__ int s_count[512];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -37,30 +36,28 @@ __global__ __launch_bounds__(1024) void dispatch_scan_kernel(
     __syncthreads();
     if (wave == 0) {
         // El <= 512: lane owns 8 consecutive experts
-        int c[8], rows = 0, tiles = 0;
+        int c[8], rows = 0;
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             const int e = lane * 8 + i;
             c[i] = (e < El) ? s_count[e] : 0;
             rows += c[i];
-            tiles += (c[i] + BM - 1) / BM;
         }
-        int xr = rows, xt = tiles;
+        int xr = rows;
 #pragma unroll
         for (int d = 1; d < 64; d <<= 1) {
-            const int yr = __shfl_up(xr, d, 64), yt = __shfl_up(xt, d, 64);
-            if (lane >= d) { xr += yr; xt += yt; }
+            const int yr = __shfl_up(xr, d, 64);
+            if (lane >= d) xr += yr;
         }
-        int r = xr - rows, m = xt - tiles;
+        int r = xr - rows;
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             const int e = lane * 8 + i;
-            if (e < El) { count[e] = c[i]; offset[e] = r; mt_prefix[e] = m; }
-            if (e == El) { offset[e] = r; mt_prefix[e] = m; }
+            if (e < El) { count[e] = c[i]; offset[e] = r; }
+            if (e == El) offset[e] = r;
             r += c[i];
-            m += (c[i] + BM - 1) / BM;
         }
-        if (El == 512 && lane == 63) { offset[El] = r; mt_prefix[El] = m; }
+        if (El == 512 && lane == 63) offset[El] = r;
     }
 }
 
@@ -113,12 +110,11 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(
     }
 }
 
-hipError_t launch_dispatch_scan(const unsigned long long* blk_mask, int nblk, int El, int BM,
-                                int32_t* blk_off, int32_t* count, int32_t* offset,
-                                int32_t* mt_prefix, hipStream_t s)
+hipError_t launch_dispatch_scan(const unsigned long long* blk_mask, int nblk, int El,
+                                int32_t* blk_off, int32_t* count, int32_t* offset, hipStream_t s)
 {
-    hipLaunchKernelGGL(dispatch_scan_kernel, dim3(1), dim3(1024), 0, s, blk_mask, nblk, El, BM,
-                       blk_off, count, offset, mt_prefix);
+    hipLaunchKernelGGL(dispatch_scan_kernel, dim3(1), dim3(1024), 0, s, blk_mask, nblk, El,
+                       blk_off, count, offset);
     return hipGetLastError();
 }
 

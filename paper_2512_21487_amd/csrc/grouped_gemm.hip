@@ -87,6 +87,65 @@ __device__ __forceinline__ float silu_f(float g)
 
 constexpr int kMaxGroups = 512;
 constexpr int kTileCache = 32;  // tiles per workgroup whose coordinates are decoded ahead (4 ints each)
+constexpr int kLdsPerWorkgroup = 160 * 1024;
+
+// Behind the ring, in the same dynamic LDS allocation: the tile coordinate cache and, for ragged
+// groups, three tables of G + 1 ints (sized by the launch, so that a deep ring of large tiles and
+// a few groups fit the 160 KB together).
+struct LdsTables { int *tile, *pref, *row0, *rowend; };
+__device__ __forceinline__ LdsTables lds_tables(uint4* lds, int ring_bytes, int G)
+{
+    LdsTables t;
+    t.tile = reinterpret_cast<int*>(reinterpret_cast<char*>(lds) + ring_bytes);
+    t.pref = t.tile + 4 * kTileCache;
+    t.row0 = t.pref + (G + 1);
+    t.rowend = t.row0 + (G + 1);
+    return t;
+}
+// The tables of one pass over ragged groups, built by the workgroup's first wavefront from the group
+// offsets alone (the host never learns them): split(lo, hi, r0, r1) names the rows [r0, r1) of a
+// group [lo, hi) that this pass covers; they are cut into tiles of bm rows and the tile counts are
+// prefix-summed, 9 groups per lane and a scan over the lanes.
+template <typename Split>
+__device__ __forceinline__ void fill_tables(const GemmArgs& a, const LdsTables& t, int bm, Split split)
+{
+    static_assert(9 * 64 > kMaxGroups, "one wavefront covers every group and the total");
+    const int tid = threadIdx.x;
+    __syncthreads();
+    if (tid < 64) {
+        int cnt[9], sum = 0;
+#pragma unroll
+        for (int j = 0; j < 9; ++j) {
+            const int g = tid * 9 + j;
+            int c = 0;
+            if (g < a.G) {
+                int r0, r1;
+                split(a.offset[g], a.offset[g + 1], r0, r1);
+                t.row0[g] = r0;
+                t.rowend[g] = r1;
+                c = (r1 - r0 + bm - 1) / bm;
+            }
+            cnt[j] = sum;
+            sum += c;
+        }
+        int incl = sum;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const int up = __shfl_up(incl, d, 64);
+            if (tid >= d) incl += up;
+        }
+        const int base = incl - sum;
+#pragma unroll
+        for (int j = 0; j < 9; ++j) {
+            const int g = tid * 9 + j;
+            if (g <= a.G) t.pref[g] = base + cnt[j];
+        }
+    }
+    __syncthreads();
+}
+
+static int lds_table_bytes(bool ragged, int G) { return (4 * kTileCache + (ragged ? 3 * (G + 1) : 0)) * 4; }
+static int lds_cap(int bytes) { return bytes < kLdsPerWorkgroup ? bytes : kLdsPerWorkgroup; }
 
 // All tiles of one shape that a workgroup owns.  Ragged mode reads the groups from LDS tables the
 // caller has filled: s_pref[g] = row tiles of this shape before group g (s_pref[G] = all of them),
@@ -421,21 +480,14 @@ __device__ __forceinline__ void gemm_tiles(const GemmArgs& a, uint4* lds, const 
 }
 
 
-// one tile shape for all groups (the ragged groups' row-tile prefix comes from the dispatch scan)
+// one tile shape for all groups
 template <int BM, int BN, int BK, int STAGES, int WGM, int WGN, bool SWIGLU, bool RAGGED>
 __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_kernel(GemmArgs a)
 {
     extern __shared__ uint4 lds[];
-    __shared__ int s_pref[kMaxGroups + 1], s_row0[kMaxGroups + 1], s_rowend[kMaxGroups + 1], s_tile[4 * kTileCache];
-    if (RAGGED) {
-        for (int i = threadIdx.x; i <= a.G; i += WGM * WGN * 64) {
-            s_pref[i] = a.mt_prefix[i];
-            s_row0[i] = a.offset[i];
-            s_rowend[i] = a.offset[i < a.G ? i + 1 : i];
-        }
-        __syncthreads();
-    }
-    gemm_tiles<BM, BN, BK, STAGES, WGM, WGN, SWIGLU, RAGGED>(a, lds, s_pref, s_row0, s_rowend, s_tile);
+    const LdsTables t = lds_tables(lds, GemmCfg<BM, BN, BK, STAGES, WGM, WGN, SWIGLU>::LDS_BYTES, a.G);
+    if (RAGGED) fill_tables(a, t, BM, [](int lo, int hi, int& r0, int& r1) { r0 = lo; r1 = hi; });
+    gemm_tiles<BM, BN, BK, STAGES, WGM, WGN, SWIGLU, RAGGED>(a, lds, t.pref, t.row0, t.rowend, t.tile);
 }
 
 // Two tile shapes in one launch, ragged groups only: the rows of a group are covered by tall tiles
@@ -449,47 +501,22 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_two_shape_kernel(G
 {
     static_assert(WGM * WGN * 64 >= 64 && BMA > BMB, "tall tiles first");
     extern __shared__ uint4 lds[];
-    __shared__ int s_pref[kMaxGroups + 1], s_row0[kMaxGroups + 1], s_rowend[kMaxGroups + 1], s_tile[4 * kTileCache];
-    const int tid = threadIdx.x;
-    // exclusive prefix sum of per-group tile counts by the first wavefront: 8 groups per lane,
-    // then a scan over the lanes
+    constexpr int ring_a = GemmCfg<BMA, BN, BKA, STA, WGM, WGN, SWIGLU>::LDS_BYTES;
+    constexpr int ring_b = GemmCfg<BMB, BN, BKB, STB, WGM, WGN, SWIGLU>::LDS_BYTES;
+    const LdsTables t = lds_tables(lds, ring_a > ring_b ? ring_a : ring_b, a.G);
+    // a group's rows [lo, hi): tall tiles up to `cut`, short tiles behind it
+    auto cut = [](int lo, int hi) {
+        const int r = hi - lo, n_tall = r / BMA + ((r % BMA) > BMB ? 1 : 0);
+        return min(hi, lo + n_tall * BMA);
+    };
     auto fill = [&](bool tall) {
-        __syncthreads();
-        if (tid < 64) {
-            int cnt[9], sum = 0;
-#pragma unroll
-            for (int j = 0; j < 9; ++j) {
-                const int g = tid * 9 + j;
-                int c = 0;
-                if (g < a.G) {
-                    const int lo = a.offset[g], hi = a.offset[g + 1], r = hi - lo;
-                    const int n_tall = r / BMA + ((r % BMA) > BMB ? 1 : 0);
-                    const int split = min(hi, lo + n_tall * BMA);
-                    if (tall) { s_row0[g] = lo; s_rowend[g] = split; c = n_tall; }
-                    else { s_row0[g] = split; s_rowend[g] = hi; c = (hi - split + BMB - 1) / BMB; }
-                }
-                cnt[j] = sum;
-                sum += c;
-            }
-            int incl = sum;
-#pragma unroll
-            for (int d = 1; d < 64; d <<= 1) {
-                const int up = __shfl_up(incl, d, 64);
-                if (tid >= d) incl += up;
-            }
-            const int base = incl - sum;
-#pragma unroll
-            for (int j = 0; j < 9; ++j) {
-                const int g = tid * 9 + j;
-                if (g <= a.G) s_pref[g] = base + cnt[j];
-            }
-        }
-        __syncthreads();
+        if (tall) fill_tables(a, t, BMA, [&](int lo, int hi, int& r0, int& r1) { r0 = lo; r1 = cut(lo, hi); });
+        else fill_tables(a, t, BMB, [&](int lo, int hi, int& r0, int& r1) { r0 = cut(lo, hi); r1 = hi; });
     };
     fill(true);
-    gemm_tiles<BMA, BN, BKA, STA, WGM, WGN, SWIGLU, true>(a, lds, s_pref, s_row0, s_rowend, s_tile);
+    gemm_tiles<BMA, BN, BKA, STA, WGM, WGN, SWIGLU, true>(a, lds, t.pref, t.row0, t.rowend, t.tile);
     fill(false);  // its first barrier also separates the two passes' use of the ring
-    gemm_tiles<BMB, BN, BKB, STB, WGM, WGN, SWIGLU, true>(a, lds, s_pref, s_row0, s_rowend, s_tile);
+    gemm_tiles<BMB, BN, BKB, STB, WGM, WGN, SWIGLU, true>(a, lds, t.pref, t.row0, t.rowend, t.tile);
 }
 
 // what every kernel here assumes of its arguments beyond the shapes the caller has checked
@@ -506,15 +533,20 @@ static bool args_fit(const GemmArgs& a, bool swiglu, bool ragged, int bm)
 }
 
 template <int BM, int BN, int BK, int STAGES, int WGM, int WGN, bool SWIGLU, bool RAGGED>
-static hipError_t launch_one(const GemmArgs& a, int n_cu, int max_row_tiles, hipStream_t s)
+static hipError_t launch_one(const GemmArgs& a, int n_cu, long long max_rows, hipStream_t s)
 {
     using Cfg = GemmCfg<BM, BN, BK, STAGES, WGM, WGN, SWIGLU>;
     const int NT = (a.N + Cfg::BN_OUT - 1) / Cfg::BN_OUT;
-    const long long max_tiles = (long long)max_row_tiles * NT;
+    // an upper bound of the row tiles the device-side tables can describe
+    const long long max_row_tiles = RAGGED ? (max_rows + BM - 1) / BM + a.G
+                                           : (long long)((a.dense_rows + BM - 1) / BM) * a.G;
+    const long long max_tiles = max_row_tiles * NT;
     if (max_tiles <= 0) return hipSuccess;
     if (!args_fit(a, SWIGLU, RAGGED, BM)) return hipErrorInvalidValue;
-    // workgroups per CU: LDS (160 KB minus the kernel's small static tables) and 8 wavefront slots
-    int occ = (156 * 1024) / Cfg::LDS_BYTES;
+    const int lds_bytes = Cfg::LDS_BYTES + lds_table_bytes(RAGGED, a.G);
+    if (lds_bytes > kLdsPerWorkgroup) return hipErrorInvalidValue;  // launch_grouped_gemm has checked
+    // workgroups per CU: LDS and 8 wavefront slots
+    int occ = kLdsPerWorkgroup / lds_bytes;
     const int by_waves = 8 / Cfg::NW;
     if (occ > by_waves) occ = by_waves;
     if (occ < 1) occ = 1;
@@ -522,7 +554,7 @@ static hipError_t launch_one(const GemmArgs& a, int n_cu, int max_row_tiles, hip
     if (grid > max_tiles) grid = max_tiles;
     grid = (grid + 7) / 8 * 8;
     hipLaunchKernelGGL((grouped_gemm_kernel<BM, BN, BK, STAGES, WGM, WGN, SWIGLU, RAGGED>),
-                       dim3((unsigned)grid), dim3(Cfg::THREADS), Cfg::LDS_BYTES, s, a);
+                       dim3((unsigned)grid), dim3(Cfg::THREADS), lds_bytes, s, a);
     return hipGetLastError();
 }
 
@@ -534,20 +566,21 @@ static hipError_t raise_all()
     if ((e = hipFuncSetAttribute(                                                                       \
              reinterpret_cast<const void*>(&grouped_gemm_kernel<BM, BN, BK, STAGES, WGM, WGN, SW, RG>), \
              hipFuncAttributeMaxDynamicSharedMemorySize,                                                \
-             GemmCfg<BM, BN, BK, STAGES, WGM, WGN, SW>::LDS_BYTES)) != hipSuccess) return e;
+             lds_cap(GemmCfg<BM, BN, BK, STAGES, WGM, WGN, SW>::LDS_BYTES +                             \
+                     lds_table_bytes(RG, kMaxGroups)))) != hipSuccess) return e;
     R(true, true) R(true, false) R(false, true) R(false, false)
 #undef R
     return hipSuccess;
 }
 
 template <int BM, int BN, int BK, int STAGES, int WGM, int WGN>
-static hipError_t launch_cfg(const GemmArgs& a, bool swiglu, int n_cu, int max_row_tiles, hipStream_t s)
+static hipError_t launch_cfg(const GemmArgs& a, bool swiglu, int n_cu, long long max_rows, hipStream_t s)
 {
     const bool ragged = a.offset != nullptr;
-    if (swiglu) return ragged ? launch_one<BM, BN, BK, STAGES, WGM, WGN, true, true>(a, n_cu, max_row_tiles, s)
-                              : launch_one<BM, BN, BK, STAGES, WGM, WGN, true, false>(a, n_cu, max_row_tiles, s);
-    return ragged ? launch_one<BM, BN, BK, STAGES, WGM, WGN, false, true>(a, n_cu, max_row_tiles, s)
-                  : launch_one<BM, BN, BK, STAGES, WGM, WGN, false, false>(a, n_cu, max_row_tiles, s);
+    if (swiglu) return ragged ? launch_one<BM, BN, BK, STAGES, WGM, WGN, true, true>(a, n_cu, max_rows, s)
+                              : launch_one<BM, BN, BK, STAGES, WGM, WGN, true, false>(a, n_cu, max_rows, s);
+    return ragged ? launch_one<BM, BN, BK, STAGES, WGM, WGN, false, true>(a, n_cu, max_rows, s)
+                  : launch_one<BM, BN, BK, STAGES, WGM, WGN, false, false>(a, n_cu, max_rows, s);
 }
 
 // tile variants: id, BM, BN, BK, ring slots, wavefronts in m, in n
@@ -566,7 +599,9 @@ static hipError_t launch_cfg(const GemmArgs& a, bool swiglu, int n_cu, int max_r
     X(6, 128, 256, 32, 2, 2, 2, 6) \
     X(7, 64, 128, 64, 3, 1, 2, 8)  \
     X(8, 64, 128, 32, 2, 1, 2, 8)  \
-    X(9, 256, 256, 32, 2, 2, 2, 9)
+    X(9, 256, 256, 32, 2, 2, 2, 9)  \
+    X(11, 160, 256, 64, 3, 1, 4, 12) \
+    X(12, 160, 256, 32, 2, 1, 2, 12)
 
 // the two-shape kernel of the routed experts: 256-row tiles on a two-slot ring, 128-row tiles on a
 // three-slot ring, 256 output columns, 64-wide K steps, 2 x 2 wavefronts
@@ -580,8 +615,9 @@ static hipError_t launch_two_shape(const GemmArgs& a, bool swiglu, int n_cu, hip
 {
     if (!a.offset || !args_fit(a, swiglu, true, 256)) return hipErrorInvalidValue;
     const unsigned grid = (unsigned)((n_cu + 7) / 8 * 8);
-    if (swiglu) hipLaunchKernelGGL((MOE_EP_TWO_SHAPE(true)), dim3(grid), dim3(256), kTwoShapeLds, s, a);
-    else hipLaunchKernelGGL((MOE_EP_TWO_SHAPE(false)), dim3(grid), dim3(256), kTwoShapeLds, s, a);
+    const int lds_bytes = kTwoShapeLds + lds_table_bytes(true, a.G);
+    if (swiglu) hipLaunchKernelGGL((MOE_EP_TWO_SHAPE(true)), dim3(grid), dim3(256), lds_bytes, s, a);
+    else hipLaunchKernelGGL((MOE_EP_TWO_SHAPE(false)), dim3(grid), dim3(256), lds_bytes, s, a);
     return hipGetLastError();
 }
 
@@ -589,44 +625,38 @@ hipError_t grouped_gemm_init()
 {
     hipError_t e;
     if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(&MOE_EP_TWO_SHAPE(true)),
-                                 hipFuncAttributeMaxDynamicSharedMemorySize, kTwoShapeLds)) != hipSuccess) return e;
+                                 hipFuncAttributeMaxDynamicSharedMemorySize,
+                                 kTwoShapeLds + lds_table_bytes(true, kMaxGroups))) != hipSuccess) return e;
     if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(&MOE_EP_TWO_SHAPE(false)),
-                                 hipFuncAttributeMaxDynamicSharedMemorySize, kTwoShapeLds)) != hipSuccess) return e;
+                                 hipFuncAttributeMaxDynamicSharedMemorySize,
+                                 kTwoShapeLds + lds_table_bytes(true, kMaxGroups))) != hipSuccess) return e;
 #define X(id, BM, BN, BK, ST, WGM, WGN, FB) if ((e = raise_all<BM, BN, BK, ST, WGM, WGN>()) != hipSuccess) return e;
     MOE_EP_VARIANTS(X)
 #undef X
     return hipSuccess;
 }
 
-int grouped_gemm_row_tile(int variant)
-{
-    switch (variant) {
-#define X(id, BM, BN, BK, ST, WGM, WGN, FB) case id: return BM;
-        MOE_EP_VARIANTS(X)
-#undef X
-        default: return 128;
-    }
-}
-
 hipError_t launch_grouped_gemm(const GemmArgs& a, bool swiglu, int variant, int n_cu,
-                               int max_row_tiles, hipStream_t s)
+                               long long max_rows, hipStream_t s)
 {
     if (a.K < 64 || a.K % 64) return hipErrorInvalidValue;
+    if (a.offset ? max_rows <= 0 : a.dense_rows <= 0) return hipSuccess;
     if (variant == kTwoShapeVariant) {
         // dense rows have no ragged tails: 256-row tiles; a K too short for the three-slot ring:
         // the 128-row shape alone, which falls back further by itself
-        if (!a.offset) return launch_grouped_gemm(a, swiglu, 2, n_cu, max_row_tiles, s);
-        if (a.K / 64 < 3) return launch_grouped_gemm(a, swiglu, 1, n_cu, max_row_tiles, s);
+        if (!a.offset) return launch_grouped_gemm(a, swiglu, 2, n_cu, max_rows, s);
+        if (a.K / 64 < 3) return launch_grouped_gemm(a, swiglu, 1, n_cu, max_rows, s);
         return launch_two_shape(a, swiglu, n_cu, s);
     }
     switch (variant) {
 #define X(id, BM, BN, BK, ST, WGM, WGN, FB)                                                          \
         case id:                                                                                    \
-            if (a.K / BK < ST) {                                                                    \
+            if (a.K / BK < ST || GemmCfg<BM, BN, BK, ST, WGM, WGN, false>::LDS_BYTES +              \
+                                         lds_table_bytes(a.offset != nullptr, a.G) > kLdsPerWorkgroup) { \
                 if (FB == id) return hipErrorInvalidValue;                                          \
-                return launch_grouped_gemm(a, swiglu, FB, n_cu, max_row_tiles, s);                  \
+                return launch_grouped_gemm(a, swiglu, FB, n_cu, max_rows, s);                  \
             }                                                                                       \
-            return launch_cfg<BM, BN, BK, ST, WGM, WGN>(a, swiglu, n_cu, max_row_tiles, s);
+            return launch_cfg<BM, BN, BK, ST, WGM, WGN>(a, swiglu, n_cu, max_rows, s);
         MOE_EP_VARIANTS(X)
 #undef X
         default: return hipErrorInvalidValue;

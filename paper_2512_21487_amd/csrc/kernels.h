@@ -13,9 +13,8 @@ hipError_t launch_router(const float* logits, int Tn, int E, int k, int e0, int 
                          float* w, unsigned long long* blk_mask, hipStream_t s);
 
 // ---- partition by expert (Sec. 2.1; Sec. 3.1 "The MoE Part")
-hipError_t launch_dispatch_scan(const unsigned long long* blk_mask, int nblk, int El, int BM,
-                                int32_t* blk_off, int32_t* count, int32_t* offset,
-                                int32_t* mt_prefix, hipStream_t s);
+hipError_t launch_dispatch_scan(const unsigned long long* blk_mask, int nblk, int El,
+                                int32_t* blk_off, int32_t* count, int32_t* offset, hipStream_t s);
 hipError_t launch_dispatch_permute(const int32_t* idx, const unsigned long long* blk_mask,
                                    const int32_t* blk_off, const int32_t* offset, int Tn, int k,
                                    int e0, int El, int32_t* pos, int32_t* perm, hipStream_t s);
@@ -38,7 +37,6 @@ struct GemmArgs {
     const uint16_t* W;         // first group's weight matrix, bf16 rows of length ldw
     uint16_t* C;               // output, bf16 [rows, ldc]
     const int32_t* offset;     // ragged mode: [G+1] first row of each group (device); NULL = dense
-    const int32_t* mt_prefix;  // ragged mode: [G+1] prefix sum of row tiles per group (device)
     int G;                     // groups (experts)
     int dense_rows;            // dense mode: every group multiplies rows [0, dense_rows) of A
     int K;                     // reduction length, multiple of 64
@@ -56,10 +54,11 @@ struct GemmArgs {
     int a_row_div;
     int a_src_rows;
 };
-// variant: index into the tile-shape table of grouped_gemm.hip (0 = default)
+// variant: index into the tile-shape table of grouped_gemm.hip; max_rows: ragged mode, an upper
+// bound of the rows of all groups together (the kernel cuts them into row tiles itself, from
+// `offset`; the bound only sizes the grid); ignored in dense mode
 hipError_t launch_grouped_gemm(const GemmArgs& a, bool swiglu, int variant, int n_cu,
-                               int max_row_tiles, hipStream_t s);
+                               long long max_rows, hipStream_t s);
 hipError_t grouped_gemm_init();   // raises the dynamic-LDS limit of every instantiation once
-int grouped_gemm_row_tile(int variant);  // BM: rows per tile of a variant (the scan kernel counts row tiles with it)
 
 }  // namespace moe_ep

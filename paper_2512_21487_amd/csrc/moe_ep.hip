@@ -7,6 +7,7 @@
 // for the link directions -- and the precedence rules are HIP events.
 #include <hip/hip_runtime.h>
 
+#include <cmath>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
@@ -29,7 +30,7 @@ struct ProfSpan { hipEvent_t a, b; int stage; int forward; };
 struct moe_ep_ctx {
     moe_ep_config cfg;
     int n_cu = 0;
-    int gemm_variant = 1;    // routed experts: 128-row tiles keep the padding of ragged groups small
+    int gemm_variant = -1;   // routed experts: tile variant, -1 = chosen per chunk (routed_variant)
     int shared_variant = 2;  // shared experts: dense rows, 256-row tiles
     bool fused_gather = true;  // the gate/up projection gathers the token rows itself (no grouped copy)
     int link_grid = 8;         // workgroups of a host-link copy kernel
@@ -39,7 +40,7 @@ struct moe_ep_ctx {
     void* d_tokens = nullptr; float* d_logits = nullptr; void* d_out = nullptr;  // pinned-host mode staging
     int32_t* idx = nullptr; float* w = nullptr; int32_t* pos = nullptr; int32_t* perm = nullptr;
     unsigned long long* blk_mask = nullptr; int32_t* blk_off = nullptr;
-    int32_t* count = nullptr; int32_t* offset = nullptr; int32_t* mt_prefix = nullptr;
+    int32_t* count = nullptr; int32_t* offset = nullptr;
     uint16_t* xp = nullptr; uint16_t* h = nullptr; uint16_t* y = nullptr;
     uint16_t* hs = nullptr;
     // streams and events
@@ -71,7 +72,7 @@ const char* set_why(const char** why, const char* msg) { if (why) *why = msg; re
 size_t align256(size_t b) { return (b + 255) & ~(size_t)255; }
 
 struct WsLayout {
-    size_t tokens, logits, out, idx, w, pos, perm, blk_mask, blk_off, count, offset, mt_prefix, xp, h, y, hs, total;
+    size_t tokens, logits, out, idx, w, pos, perm, blk_mask, blk_off, count, offset, xp, h, y, hs, total;
 };
 
 // MOE_EP_FUSED_GATHER=0 brings back the grouped copy of the token rows (for comparison)
@@ -95,7 +96,7 @@ WsLayout ws_layout(const moe_ep_config& c)
     L.out = take(pinned ? T * M * 2 : 0);
     L.idx = take(A * 4); L.w = take(A * 4); L.pos = take(A * 4); L.perm = take(A * 4);
     L.blk_mask = take(nblk * El * 8); L.blk_off = take(nblk * El * 4);
-    L.count = take(R * El * 4); L.offset = take(R * (El + 1) * 4); L.mt_prefix = take(R * (El + 1) * 4);
+    L.count = take(R * El * 4); L.offset = take(R * (El + 1) * 4);
     // the grouped copy of the token rows exists only when the gate/up projection cannot gather them
     // itself: switched off, or a chunk of 4 GB and more (its lanes hold 32-bit byte offsets)
     const bool need_xp = !fused_gather_enabled() || T * M * 2 >= ((size_t)1 << 32);
@@ -156,6 +157,25 @@ const char* check_span(const void* p, size_t bytes, bool want_host, const void**
     const char* q = static_cast<const char*>(p);
     if (q < lo || (size_t)(lo + size - q) < bytes) return "points at an allocation smaller than the forward needs";
     return nullptr;
+}
+
+// Tile shape of a routed projection for a chunk of Tn tokens: 128-row tiles (variant 1) or 160-row
+// tiles (variant 11).  The routed GEMMs run at the rate their workgroups can load operands, and a
+// tile of BM token rows and 256 weight rows loads BM + 256 rows per K step whatever part of it is
+// padding; measured, a 160-row tile takes 1.15 times as long as a 128-row tile for 1.25 times the
+// rows.  A launch lasts as many tiles as its busiest workgroup works through, so the shapes are
+// compared by rounds * time per tile: rounds = expected tiles of all experts and column tiles over
+// the n_cu workgroups, rounded up, with an expert's row count taken as normal around the balanced
+// share Tn * k / E of Sec. 3.1 with a Poisson spread (the host never learns the real counts).
+int routed_variant(int Tn, int k, int E, int El, int col_tiles, int n_cu)
+{
+    const double mean = (double)Tn * k / E, sd = sqrt(mean > 1.0 ? mean : 1.0);
+    auto launch_time = [&](int bm, double tile_time) {
+        double tiles = 0.0;  // E[ceil(rows / bm)] = sum over j of P(rows > j * bm)
+        for (int j = 0; j * (double)bm < mean + 6.0 * sd; ++j) tiles += 0.5 * erfc((j * (double)bm - mean) / (sd * 1.4142135623730951));
+        return ceil(tiles * El * col_tiles / n_cu - 0.02) * tile_time;
+    };
+    return launch_time(160, 1.15) < launch_time(128, 1.0) ? 11 : 1;
 }
 
 hipEvent_t prof_event(moe_ep_ctx* ctx)
@@ -303,7 +323,6 @@ int moe_ep_create(const moe_ep_config* cfg, moe_ep_ctx** out_ctx)
     ctx->blk_off = reinterpret_cast<int32_t*>(slab + L.blk_off);
     ctx->count = reinterpret_cast<int32_t*>(slab + L.count);
     ctx->offset = reinterpret_cast<int32_t*>(slab + L.offset);
-    ctx->mt_prefix = reinterpret_cast<int32_t*>(slab + L.mt_prefix);
     ctx->xp = reinterpret_cast<uint16_t*>(slab + L.xp);
     ctx->h = reinterpret_cast<uint16_t*>(slab + L.h);
     ctx->y = reinterpret_cast<uint16_t*>(slab + L.y);
@@ -514,23 +533,21 @@ int forward_impl(moe_ep_ctx* ctx, const void* tokens, const float* gate_logits, 
         if (Tn <= 0) return MOE_EP_OK;
         GemmArgs g1{};
         g1.A = tok_dev + (size_t)t0 * M; g1.W = sw; g1.C = ctx->hs + (size_t)t0 * Ns * Hs;
-        g1.offset = nullptr; g1.mt_prefix = nullptr; g1.G = Ns; g1.dense_rows = Tn;
+        g1.offset = nullptr; g1.G = Ns; g1.dense_rows = Tn;
         g1.K = M; g1.N = Hs; g1.lda = M; g1.ldc = Ns * Hs; g1.ldw = M;
         g1.w_group_stride = (long long)3 * Hs * M; g1.w_up_offset = (long long)Hs * M;
         g1.kseg_len = M; g1.w_kseg_stride = 0; g1.c_group_col_stride = Hs;
-        const int sbm = grouped_gemm_row_tile(ctx->shared_variant);
-        const int mt = (Tn + sbm - 1) / sbm;
         int sp = prof_begin(ctx, prof, ST_SGEMM1, st);
-        HIP_TRY(ctx, launch_grouped_gemm(g1, true, ctx->shared_variant, n_cu, mt * Ns, st));
+        HIP_TRY(ctx, launch_grouped_gemm(g1, true, ctx->shared_variant, n_cu, 0, st));
         prof_end(ctx, sp, st);
         GemmArgs g2{};
         g2.A = ctx->hs + (size_t)t0 * Ns * Hs; g2.W = sw + (size_t)2 * Hs * M; g2.C = out_dev + (size_t)t0 * M;
-        g2.offset = nullptr; g2.mt_prefix = nullptr; g2.G = 1; g2.dense_rows = Tn;
+        g2.offset = nullptr; g2.G = 1; g2.dense_rows = Tn;
         g2.K = Ns * Hs; g2.N = M; g2.lda = Ns * Hs; g2.ldc = M; g2.ldw = Hs;
         g2.w_group_stride = 0; g2.w_up_offset = 0;
         g2.kseg_len = Hs; g2.w_kseg_stride = (long long)3 * Hs * M; g2.c_group_col_stride = 0;
         sp = prof_begin(ctx, prof, ST_SGEMM2, st);
-        HIP_TRY(ctx, launch_grouped_gemm(g2, false, ctx->shared_variant, n_cu, mt, st));
+        HIP_TRY(ctx, launch_grouped_gemm(g2, false, ctx->shared_variant, n_cu, 0, st));
         prof_end(ctx, sp, st);
         return MOE_EP_OK;
     };
@@ -614,12 +631,13 @@ int forward_impl(moe_ep_ctx* ctx, const void* tokens, const float* gate_logits, 
         chunk_range(T, r_1, r_2, cidx, &t0, &Tn);
         int32_t* count = ctx->count + (size_t)cidx * El;
         int32_t* offset = ctx->offset + (size_t)cidx * (El + 1);
-        int32_t* mt_prefix = ctx->mt_prefix + (size_t)cidx * (El + 1);
         if (pinned) HIP_TRY(ctx, hipStreamWaitEvent(s_comp, ctx->ev_in[cidx], 0));
         else if (dep && cidx % r_2 == 0) HIP_TRY(ctx, hipStreamWaitEvent(s_comp, ctx->ev_attn[cidx / r_2], 0));
         const int nblk = (Tn + kTokPerBlock - 1) / kTokPerBlock;
-        const int variant = ctx->gemm_variant;
-        const int BMv = grouped_gemm_row_tile(variant);
+        // tile shapes of the two routed projections: N = H in tiles of 128 activation columns, N = M in
+        // tiles of 256 columns
+        const int v_up = ctx->gemm_variant >= 0 ? ctx->gemm_variant : routed_variant(Tn, k, E, El, (H + 127) / 128, n_cu);
+        const int v_down = ctx->gemm_variant >= 0 ? ctx->gemm_variant : routed_variant(Tn, k, E, El, (M + 255) / 256, n_cu);
         int32_t* idx = ctx->idx + (size_t)t0 * k;
         float* w = ctx->w + (size_t)t0 * k;
         int32_t* pos = ctx->pos + (size_t)t0 * k;
@@ -632,7 +650,7 @@ int forward_impl(moe_ep_ctx* ctx, const void* tokens, const float* gate_logits, 
         // the fused gather addresses a chunk's token rows with 32-bit byte offsets
         const bool fused = ctx->fused_gather && (unsigned long long)Tn * M * 2 < (1ull << 32);
         sp = prof_begin(ctx, prof, ST_PARTITION, s_comp);
-        HIP_TRY(ctx, launch_dispatch_scan(ctx->blk_mask, nblk, El, BMv, ctx->blk_off, count, offset, mt_prefix, s_comp));
+        HIP_TRY(ctx, launch_dispatch_scan(ctx->blk_mask, nblk, El, ctx->blk_off, count, offset, s_comp));
         if (Tn > 0) {
             HIP_TRY(ctx, launch_dispatch_permute(idx, ctx->blk_mask, ctx->blk_off, offset, Tn, k, e0, El, pos, perm, s_comp));
             if (!fused)
@@ -644,12 +662,10 @@ int forward_impl(moe_ep_ctx* ctx, const void* tokens, const float* gate_logits, 
             continue;
         }
 
-        // an upper bound of the row tiles the device-side prefix sums can describe
-        const long long a_max = (long long)Tn * k;
-        const int max_row_tiles = (int)((a_max + BMv - 1) / BMv) + El;
+        const long long a_max = (long long)Tn * k;  // the most rows the routing can keep
 
         GemmArgs g1{};
-        g1.A = ctx->xp; g1.W = rw; g1.C = ctx->h; g1.offset = offset; g1.mt_prefix = mt_prefix;
+        g1.A = ctx->xp; g1.W = rw; g1.C = ctx->h; g1.offset = offset;
         g1.G = El; g1.dense_rows = 0; g1.K = M; g1.N = H; g1.lda = M; g1.ldc = H; g1.ldw = M;
         g1.w_group_stride = (long long)3 * H * M; g1.w_up_offset = (long long)H * M;
         g1.kseg_len = M; g1.w_kseg_stride = 0; g1.c_group_col_stride = 0;
@@ -657,16 +673,16 @@ int forward_impl(moe_ep_ctx* ctx, const void* tokens, const float* gate_logits, 
             g1.A = tok_dev + (size_t)t0 * M; g1.a_row_map = perm; g1.a_row_div = k; g1.a_src_rows = Tn;
         }
         sp = prof_begin(ctx, prof, ST_GEMM1, s_comp);
-        HIP_TRY(ctx, launch_grouped_gemm(g1, true, variant, n_cu, max_row_tiles, s_comp));
+        HIP_TRY(ctx, launch_grouped_gemm(g1, true, v_up, n_cu, a_max, s_comp));
         prof_end(ctx, sp, s_comp);
 
         GemmArgs g2{};
-        g2.A = ctx->h; g2.W = rw + (size_t)2 * H * M; g2.C = ctx->y; g2.offset = offset; g2.mt_prefix = mt_prefix;
+        g2.A = ctx->h; g2.W = rw + (size_t)2 * H * M; g2.C = ctx->y; g2.offset = offset;
         g2.G = El; g2.dense_rows = 0; g2.K = H; g2.N = M; g2.lda = H; g2.ldc = M; g2.ldw = H;
         g2.w_group_stride = (long long)3 * H * M; g2.w_up_offset = 0;
         g2.kseg_len = H; g2.w_kseg_stride = 0; g2.c_group_col_stride = 0;
         sp = prof_begin(ctx, prof, ST_GEMM2, s_comp);
-        HIP_TRY(ctx, launch_grouped_gemm(g2, false, variant, n_cu, max_row_tiles, s_comp));
+        HIP_TRY(ctx, launch_grouped_gemm(g2, false, v_down, n_cu, a_max, s_comp));
         prof_end(ctx, sp, s_comp);
 
         if (!dep && Ns > 0 && order == MOE_EP_ORDER_INTERLEAVED) {

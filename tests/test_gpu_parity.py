@@ -168,11 +168,11 @@ def test_maximum_expert_count_and_top_k():
     _full_parity(wl, seed=28)
 
 
-@pytest.mark.parametrize("variant", [0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10])
+@pytest.mark.parametrize("variant", [0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12])
 @pytest.mark.parametrize("hidden", [64, 128, 192, 320])
 def test_every_tile_variant_matches_oracle(variant, hidden):
     """Each instantiated tile shape / ring depth of the grouped GEMM (10: tall and short tiles in one
-    launch), for the routed and the shared experts, on K extents of one, two, three and five 64-wide
+    launch; 11, 12: 160-row tiles held by 1 x 4 and 1 x 2 wavefronts), for the routed and the shared experts, on K extents of one, two, three and five 64-wide
     steps (shortest pipelines, fallbacks to the 32-wide variants included) with ragged row and column
     tails."""
     wl = tiny_workload(name=f"v{variant}_M{hidden}", n_tokens=333, hidden=hidden, inter=320, n_experts=6,
