@@ -24,10 +24,10 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 matrix peak
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E peak
 # (workload, r_chunks, stage) -> fetched + written HBM-side bytes per launch of that stage's kernel
 # (rocprofv3 FETCH_SIZE / WRITE_SIZE runs scaled by a 1 GiB copy, profiles/hbm_traffic_dsv2_eg.txt)
-MEASURED_TRAFFIC_BYTES = {("dsv2_eg", 1, "routed_gate_up_gemm"): 1076.9e6 + 37.8e6,
-                          ("dsv2_eg", 1, "shared_gate_up_gemm"): 1515.3e6 + 100.7e6}
+MEASURED_TRAFFIC_BYTES = {("dsv2_eg", 1, "routed_gate_up_gemm"): 922.6e6 + 37.8e6,
+                          ("dsv2_eg", 1, "shared_gate_up_gemm"): 1515.4e6 + 100.7e6}
 KERNEL_NAMES = {
-    "routed_gate_up_gemm": "grouped_gemm_kernel<128,256,64,3,2,2,swiglu,ragged> (routed gate/up projection)",
+    "routed_gate_up_gemm": "grouped_gemm_kernel<160,256,64,3,1,4,swiglu,ragged> (routed gate/up projection)",
     "shared_gate_up_gemm": "grouped_gemm_kernel<256,256,64,2,2,2,swiglu,dense> (shared-expert gate/up projection)",
 }
 
