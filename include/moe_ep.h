@@ -266,6 +266,17 @@ typedef enum { MOE_EP_DEP_ASAS = 0, MOE_EP_DEP_AASS = 1 } moe_ep_dep_order;
 int moe_ep_chunk_range(int32_t n_tokens, int32_t r_1, int32_t r_2, int32_t chunk, int32_t *first,
                        int32_t *count);
 
+/*
+ * Host only: the rows per tile (128 or 160) the library gives a routed projection of a chunk of
+ * n_tokens tokens -- down == 0: gate/up projection, else the down projection -- on a GPU of n_cu
+ * compute units.  An expert of the balanced load of Sec. 3.1 gets n_tokens * top_k / E rows; the
+ * taller tile loads fewer operand rows per output row but takes longer, and a launch lasts as many
+ * tiles as its busiest compute unit works through, so the choice compares expected rounds of tiles
+ * times the time of a tile.  It changes no result bit.  MOE_EP_EINVAL (negative) on bad arguments.
+ */
+int32_t moe_ep_routed_tile_rows(const moe_ep_config *cfg, int32_t n_tokens, int32_t top_k, int32_t down,
+                                int32_t n_cu);
+
 int moe_ep_forward_dep(moe_ep_ctx *ctx, const void *tokens, const float *gate_logits,
                        const void *routed_w, const void *shared_w, int32_t top_k, int32_t r_1,
                        int32_t r_2, int32_t dep_order, double attn_us, int32_t n_tokens, void *out,

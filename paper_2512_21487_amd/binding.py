@@ -111,6 +111,8 @@ def load_library() -> ctypes.CDLL:
     lib.moe_ep_forward_dep.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, ctypes.c_double, i32, vp, vp]
     lib.moe_ep_chunk_range.restype = ctypes.c_int
     lib.moe_ep_chunk_range.argtypes = [i32, i32, i32, i32, vp, vp]
+    lib.moe_ep_routed_tile_rows.restype = i32
+    lib.moe_ep_routed_tile_rows.argtypes = [cfgp, i32, i32, i32, i32]
     lib.moe_ep_get_routing.restype = ctypes.c_int
     lib.moe_ep_get_routing.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp]
     lib.moe_ep_set_profiling.restype = ctypes.c_int
@@ -195,6 +197,14 @@ def validate_forward(cfg: MoeEpConfig, tokens, gate_logits, routed_w, shared_w, 
         ctypes.byref(cfg), _ptr(tokens), _ptr(gate_logits), _ptr(routed_w), _ptr(shared_w),
         top_k, r_chunks, order, n_tokens, _ptr(out), ctypes.byref(why))
     return rc, (why.value or b"").decode()
+
+
+def routed_tile_rows(cfg: MoeEpConfig, n_tokens: int, top_k: int, down: bool, n_cu: int = 256) -> int:
+    """moe_ep_routed_tile_rows: rows per tile (128 or 160) of a routed projection of a chunk."""
+    rows = int(load_library().moe_ep_routed_tile_rows(ctypes.byref(cfg), n_tokens, top_k, int(down), n_cu))
+    if rows < 0:
+        raise ValueError("moe_ep_routed_tile_rows: bad arguments")
+    return rows
 
 
 def workspace_bytes(cfg: MoeEpConfig) -> int:

@@ -736,6 +736,13 @@ int moe_ep_chunk_range(int32_t n_tokens, int32_t r_1, int32_t r_2, int32_t chunk
     return MOE_EP_OK;
 }
 
+int32_t moe_ep_routed_tile_rows(const moe_ep_config* cfg, int32_t n_tokens, int32_t top_k, int32_t down, int32_t n_cu)
+{
+    if (moe_ep_validate_config(cfg, nullptr) != MOE_EP_OK || n_tokens < 0 || top_k < 1 || n_cu < 1) return MOE_EP_EINVAL;
+    const int col_tiles = down ? (cfg->hidden + 255) / 256 : (cfg->inter + 127) / 128;
+    return routed_variant(n_tokens, top_k, cfg->n_experts, cfg->n_local, col_tiles, n_cu) == 11 ? 160 : 128;
+}
+
 int moe_ep_forward(moe_ep_ctx* ctx, const void* tokens, const float* gate_logits,
                    const void* routed_w, const void* shared_w, int32_t top_k, int32_t r_chunks,
                    int32_t order, int32_t n_tokens, void* out, void* stream)

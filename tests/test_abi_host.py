@@ -155,3 +155,28 @@ def test_tensor_marshalling_checks():
         _check_tensor(t, "tokens", 1024, True)
     with pytest.raises(ValueError, match="device tensor"):
         _check_tensor(t, "tokens", 1024, False)
+
+
+def test_row_tile_of_the_routed_projections():
+    """The tile height follows from expected rounds of tiles x time per tile (a 160-row tile counts 1.15
+    128-row tiles): worked by hand for the benchmark shapes on 256 compute units."""
+    from paper_2512_21487_amd import routed_tile_rows
+    dsv2_eg = _good(hidden=5120, inter=1536, n_experts=160, n_local=20, shared_inter=1536, n_shared=2,
+                    max_tokens=16384, max_top_k=6)
+    # 614 rows per expert: 5.15 tiles of 128 or 4.15 of 160; gate/up 12 column tiles: 5 rounds against 4
+    assert routed_tile_rows(dsv2_eg, 16384, 6, False) == 160
+    # down, 20 column tiles: 9 rounds against 7
+    assert routed_tile_rows(dsv2_eg, 16384, 6, True) == 160
+    decode = _good(hidden=4096, inter=1536, n_experts=128, n_local=16, n_shared=0, shared_inter=0,
+                   max_tokens=4096, max_top_k=8)
+    # 256 +- 16 rows per expert: 2.5 tiles of 128 or 2 of 160; gate/up 480 or 384 tiles: 2 rounds both
+    assert routed_tile_rows(decode, 4096, 8, False) == 128
+    # down, 16 column tiles: 640 tiles = 3 rounds against 512 = 2 rounds
+    assert routed_tile_rows(decode, 4096, 8, True) == 160
+    for T in (1, 256, 1024):   # one tile per expert either way: the smaller one
+        assert routed_tile_rows(decode, T, 8, False) == routed_tile_rows(decode, T, 8, True) == 128
+    assert routed_tile_rows(decode, 0, 8, False) == 128
+    with pytest.raises(ValueError):
+        routed_tile_rows(_good(hidden=100), 16, 2, False)
+    with pytest.raises(ValueError):
+        routed_tile_rows(decode, 16, 0, False)

@@ -189,6 +189,24 @@ def test_every_tile_variant_matches_oracle(variant, hidden):
                 os.environ[k] = v
 
 
+@pytest.mark.parametrize("n_experts", [297, 298, 512])
+def test_deepest_ring_at_the_lds_limit(n_experts):
+    """The 160-row tiles keep a 156 KB ring; the per-expert tables behind it fit the 160 KB of a
+    workgroup for up to 297 experts (8 bytes to spare), beyond that the launch falls back to the
+    two-slot variant with the same row tile."""
+    wl = tiny_workload(name=f"lds_limit_E{n_experts}", n_tokens=700, hidden=192, inter=192, n_experts=n_experts,
+                       n_local=n_experts, top_k=8)
+    old = os.environ.get("MOE_EP_GEMM_VARIANT")
+    os.environ["MOE_EP_GEMM_VARIANT"] = "11"
+    try:
+        _full_parity(wl, seed=43)
+    finally:
+        if old is None:
+            os.environ.pop("MOE_EP_GEMM_VARIANT", None)
+        else:
+            os.environ["MOE_EP_GEMM_VARIANT"] = old
+
+
 def test_tall_and_short_tiles_in_one_launch():
     """Tile variant 10 on expert loads that need every case of its row split: experts with several
     256-row tiles, tails longer than 128 rows (one more tall tile), tails of at most 128 rows (a
