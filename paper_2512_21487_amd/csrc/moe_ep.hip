@@ -171,8 +171,12 @@ int routed_variant(int Tn, int k, int E, int El, int col_tiles, int n_cu)
 {
     const double mean = (double)Tn * k / E, sd = sqrt(mean > 1.0 ? mean : 1.0);
     auto launch_time = [&](int bm, double tile_time) {
-        double tiles = 0.0;  // E[ceil(rows / bm)] = sum over j of P(rows > j * bm)
-        for (int j = 0; j * (double)bm < mean + 6.0 * sd; ++j) tiles += 0.5 * erfc((j * (double)bm - mean) / (sd * 1.4142135623730951));
+        // E[ceil(rows / bm)] = sum over j >= 0 of P(rows > j * bm): 1 for every j * bm more than 6 sd
+        // below the mean, 0 beyond 6 sd above it, the normal tail in between
+        const double lo = (mean - 6.0 * sd) / bm;
+        const long long j0 = lo > 0.0 ? (long long)lo : 0;
+        double tiles = (double)j0;
+        for (long long j = j0; j * (double)bm < mean + 6.0 * sd; ++j) tiles += 0.5 * erfc((j * (double)bm - mean) / (sd * 1.4142135623730951));
         return ceil(tiles * El * col_tiles / n_cu - 0.02) * tile_time;
     };
     return launch_time(160, 1.15) < launch_time(128, 1.0) ? 11 : 1;
