@@ -207,6 +207,34 @@ def test_deepest_ring_at_the_lds_limit(n_experts):
             os.environ["MOE_EP_GEMM_VARIANT"] = old
 
 
+def test_tile_shape_does_not_change_a_bit():
+    """Every output element is accumulated over K in the same order whatever tile it falls in, so the
+    tile shape the library picks (or is told to use) never shows in the result."""
+    g = _gpu()
+    wl = tiny_workload(name="tile_bits", n_tokens=1500, hidden=320, inter=256, n_experts=6, n_local=6, top_k=2,
+                       n_shared=1, shared_inter=192)
+    d = g.DeviceInputs(wl, make_inputs(wl, seed=44))
+    old = os.environ.get("MOE_EP_GEMM_VARIANT")
+    outs = {}
+    try:
+        for variant in (None, 0, 1, 2, 5, 10, 11, 12):
+            if variant is None:
+                os.environ.pop("MOE_EP_GEMM_VARIANT", None)
+            else:
+                os.environ["MOE_EP_GEMM_VARIANT"] = str(variant)
+            ctx = g.make_ctx(wl)
+            outs[variant] = g.run_forward(ctx, wl, d)
+            ctx.destroy()
+    finally:
+        if old is None:
+            os.environ.pop("MOE_EP_GEMM_VARIANT", None)
+        else:
+            os.environ["MOE_EP_GEMM_VARIANT"] = old
+    assert outs[None].any()
+    for variant, out in outs.items():
+        assert np.array_equal(out, outs[None]), f"tile variant {variant} changed output bits"
+
+
 def test_tall_and_short_tiles_in_one_launch():
     """Tile variant 10 on expert loads that need every case of its row split: experts with several
     256-row tiles, tails longer than 128 rows (one more tall tile), tails of at most 128 rows (a
