@@ -69,6 +69,8 @@ def main() -> int:
     ap.add_argument("--order", type=int, default=0, help="0 shared first, 1 interleaved")
     ap.add_argument("--variant", type=int, default=None, help="GEMM tile variant (tuning)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-device-probe", action="store_true",
+                    help="skip the register-only MFMA loop and the streaming copy that follow the timed forwards")
     ap.add_argument("--no-stage-timing", action="store_true",
                     help="time the K steps without per-stage HIP events (stage figures are then absent)")
     ap.add_argument("--fit-pipeline", action="store_true",
@@ -386,6 +388,15 @@ def main() -> int:
         per_layer_ms = (time.perf_counter() - t1) / (args.steps * L) * 1e3
         line["multi_layer"] = {"layers": L, "ms_per_layer": per_layer_ms, "tokens_per_s": T / (per_layer_ms * 1e-3),
                                "single_layer_ms": ms_per_step}
+    if not args.no_device_probe:
+        # what this machine sustains, measured right after the timed forwards (outside the timed region):
+        # a register-only MFMA loop on random bf16 operands and a streaming copy; the vendor peaks in
+        # "roofline" assume the maximum clock, which the power limit does not grant real operands
+        probe = pkg.probe_device(0)
+        line["device_probe"] = {"mfma_tflops_random_operands": probe["mfma_tflops"], "mfma_ghz": probe["mfma_ghz"],
+                                "copy_gbs_read_plus_write": probe["copy_gbs"]}
+        if roof.get("bound") == "mfma" and probe["mfma_tflops"] > 0:
+            line["roofline"]["frac_of_measured_ceiling"] = roof["achieved"] / probe["mfma_tflops"]
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(wl, inp)
     if args.copy_probe:

@@ -267,6 +267,18 @@ int moe_ep_chunk_range(int32_t n_tokens, int32_t r_1, int32_t r_2, int32_t chunk
                        int32_t *count);
 
 /*
+ * Measurement aid, not on the path: what `device` sustains right now.  *mfma_tflops and *mfma_ghz:
+ * rate and shader clock of a register-only v_mfma_f32_32x32x16_bf16 loop on all compute units
+ * (no LDS, no memory traffic; operands are standard-normal bf16 values, or all zeros when
+ * zero_operands != 0 -- the part trades clock for matrix-pipe activity under its power limit, so
+ * the two differ); *copy_gbs: bytes read plus bytes written per second by a device-to-device copy
+ * of 1 GiB.  Allocates and frees 2 GiB of device memory, runs on the default stream and returns
+ * when done (about 0.1 s).  MOE_EP_EINVAL on NULL outputs, MOE_EP_EHIP if a HIP call fails.
+ */
+int moe_ep_probe_device(int32_t device, int32_t zero_operands, double *mfma_tflops, double *mfma_ghz,
+                        double *copy_gbs);
+
+/*
  * Host only: the rows per tile (128 or 160) the library gives a routed projection of a chunk of
  * n_tokens tokens -- down == 0: gate/up projection, else the down projection -- on a GPU of n_cu
  * compute units.  An expert of the balanced load of Sec. 3.1 gets n_tokens * top_k / E rows; the

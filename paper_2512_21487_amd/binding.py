@@ -111,6 +111,9 @@ def load_library() -> ctypes.CDLL:
     lib.moe_ep_forward_dep.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, ctypes.c_double, i32, vp, vp]
     lib.moe_ep_chunk_range.restype = ctypes.c_int
     lib.moe_ep_chunk_range.argtypes = [i32, i32, i32, i32, vp, vp]
+    lib.moe_ep_probe_device.restype = ctypes.c_int
+    lib.moe_ep_probe_device.argtypes = [i32, i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double),
+                                        ctypes.POINTER(ctypes.c_double)]
     lib.moe_ep_routed_tile_rows.restype = i32
     lib.moe_ep_routed_tile_rows.argtypes = [cfgp, i32, i32, i32, i32]
     lib.moe_ep_get_routing.restype = ctypes.c_int
@@ -205,6 +208,16 @@ def routed_tile_rows(cfg: MoeEpConfig, n_tokens: int, top_k: int, down: bool, n_
     if rows < 0:
         raise ValueError("moe_ep_routed_tile_rows: bad arguments")
     return rows
+
+
+def probe_device(device: int = 0, zero_operands: bool = False) -> Dict[str, float]:
+    """moe_ep_probe_device: register-only MFMA rate and clock, streaming copy rate of the GPU."""
+    tf, ghz, gbs = ctypes.c_double(), ctypes.c_double(), ctypes.c_double()
+    rc = load_library().moe_ep_probe_device(device, int(zero_operands), ctypes.byref(tf), ctypes.byref(ghz),
+                                            ctypes.byref(gbs))
+    if rc != 0:
+        raise MoeEpError(rc, "moe_ep_probe_device failed")
+    return {"mfma_tflops": tf.value, "mfma_ghz": ghz.value, "copy_gbs": gbs.value}
 
 
 def workspace_bytes(cfg: MoeEpConfig) -> int:

@@ -12,7 +12,7 @@ INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libmoe_ep.so")
 OBJDIR = os.path.join(HERE, "_build")
 
-SOURCES = ["router.hip", "dispatch.hip", "combine.hip", "transfer.hip", "grouped_gemm.hip", "schedule.hip", "dep_schedule.hip", "moe_ep.hip"]
+SOURCES = ["router.hip", "dispatch.hip", "combine.hip", "transfer.hip", "grouped_gemm.hip", "schedule.hip", "dep_schedule.hip", "probe.hip", "moe_ep.hip"]
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     # packed-fp32 code generation is switched off on purpose (silent wrong results were seen

@@ -545,6 +545,18 @@ def test_binding_rejects_tensors_of_the_wrong_size_or_place():
     ctx.destroy()
 
 
+def test_device_probe_reports_plausible_rates():
+    """The measurement aid: the register-only MFMA loop stays below the vendor peak, all-zero operands
+    (less switching, more clock) are not slower than random ones, and the copy moves a few TB/s."""
+    import paper_2512_21487_amd as pkg
+    rnd = pkg.probe_device(0, zero_operands=False)
+    zero = pkg.probe_device(0, zero_operands=True)
+    print(f"       random {rnd}  zero {zero}", flush=True)
+    assert 500.0 < rnd["mfma_tflops"] <= 2600.0 and 0.5 < rnd["mfma_ghz"] <= 2.6
+    assert zero["mfma_tflops"] >= 0.98 * rnd["mfma_tflops"] and zero["mfma_tflops"] <= 2600.0
+    assert 1000.0 < rnd["copy_gbs"] < 8000.0
+
+
 # ------------------------------------------------------------------ full-size configurations
 def _sampled_parity(name, variants, pinned=False, n_sample=24):
     """At the benchmark's sizes: routing of every token bit-exact, outputs of sampled tokens
