@@ -355,7 +355,8 @@ __device__ __forceinline__ void gemm_tiles(const GemmArgs& a, uint4* lds, const 
                 MOE_EP_HANDOVER((STAGES - 2) * RPW)                                               \
             }                                                                                     \
             _Pragma("unroll") for (int q = 0; q < MB * NB; ++q) {                                 \
-                const int nb = q / MB, mb = q % MB;                                               \
+                /* row blocks run down and up in turn: one operand changes per MFMA, never both */ \
+                const int nb = q / MB, mb = (nb & 1) ? MB - 1 - q % MB : q % MB;                  \
                 acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[i & 1][nb], xf[i & 1][mb], acc[mb][nb], 0, 0, 0); \
                 _Pragma("unroll") for (int f = q; f < MB + NB; f += MB * NB) {                    \
                     if (i + 1 < KKW) MOE_EP_FRAG1(sT, i + 1, (i + 1) & 1, MOE_EP_FRAG_ORDER(f))   \
