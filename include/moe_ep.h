@@ -13,7 +13,7 @@
  * Plain C: no C++ types, no exceptions, nothing from PyTorch crosses this
  * boundary.  Every function returns a moe_ep_status (0 = OK, negative = error)
  * unless stated otherwise, never aborts, and validates its arguments before
- * the first HIP call.
+ * anything is launched or allocated.
  *
  * Notation (Table "Notations"): M hidden size, H expert intermediate size,
  * E global experts, top_k experts per token, r_2 chunks.
