@@ -274,6 +274,91 @@ def test_forward_tokens_matches_full_forward():
     np.testing.assert_allclose(sub, full[ids], rtol=1e-12, atol=1e-15)
 
 
+@pytest.mark.parametrize("n_shared", [0, 2])
+@pytest.mark.parametrize("e0,El", [(3, 3), (0, 2), (5, 3), (7, 1)])
+def test_forward_tokens_on_an_expert_group_share(e0, El, n_shared):
+    """The per-token form on a device that holds experts [e0, e0 + El) of 8 (Sec. 3.1, "The MoE
+    Part"): it must keep exactly the assignments to local experts, with the weights the gate gave
+    them over all k selected experts (no second renormalisation), add the shared experts to every
+    token, and give a token with nothing kept the shared part alone.  Checked against the
+    dense-masked brute force (library matmul / softmax / sort) and against the whole-layer oracle."""
+    M, H, Hs, E, k, T = 32, 48, 16, 8, 3, 40
+    wl = tiny_workload(n_tokens=T, hidden=M, inter=H, n_experts=E, local_begin=e0, n_local=El, top_k=k,
+                       n_shared=n_shared, shared_inter=Hs if n_shared else 0)
+    inp = make_inputs(wl, seed=51)
+    inp["gate_logits"][7, e0:e0 + El] = -50.0      # token 7 selects no local expert
+    inp["gate_logits"][11, :] = 0.0                # token 11: all equal -> experts 0, 1, 2
+    ref, G = brute_force_layer(inp["tokens"], inp["gate_logits"], inp["routed_w"], inp["shared_w"],
+                               M=M, H=H, E=E, e0=e0, El=El, Ns=n_shared, Hs=Hs, k=k)
+    kept = (G[:, e0:e0 + El] > 0).sum(axis=1)
+    assert kept[7] == 0 and 0 < kept.min(initial=9, where=kept > 0) < k   # partial selections exist
+    # weights of the kept slots are the gate's own: they sum to less than 1 where a slot was dropped
+    part = G[:, e0:e0 + El].sum(axis=1)
+    assert np.any((part > 1e-3) & (part < 1.0 - 1e-3))
+    ids = np.array([7, 0, 39, 11, 7, 20, 3], dtype=np.int32)
+    args = dict(hidden=M, inter=H, n_experts=E, local_begin=e0, n_local=El, n_shared=n_shared,
+                shared_inter=wl.shared_inter, top_k=k)
+    sub = oracle.forward_tokens(inp["tokens"], inp["gate_logits"], inp["routed_w"], inp["shared_w"],
+                                ids, **args)
+    assert rel_err(sub, ref[ids]) < 1e-9
+    full = oracle.forward(inp["tokens"], inp["gate_logits"], inp["routed_w"], inp["shared_w"], **args)
+    np.testing.assert_allclose(sub, full["out"][ids], rtol=1e-12, atol=1e-15)
+    assert rel_err(full["out"], ref) < 1e-9
+    if n_shared == 0:
+        assert not sub[0].any() and not sub[4].any()          # nothing kept, no shared expert: zeros
+    else:
+        X = f64(inp["tokens"][7:8])
+        alone = sum(dense_ffn(X, *split_expert(inp["shared_w"], i, M, Hs)) for i in range(n_shared))
+        assert rel_err(sub[0:1], alone) < 1e-9
+    # all tokens, and the shares of a partition of the experts add up to the all-local layer
+    every = oracle.forward_tokens(inp["tokens"], inp["gate_logits"], inp["routed_w"], inp["shared_w"],
+                                  np.arange(T, dtype=np.int32), **args)
+    assert rel_err(every, ref) < 1e-9
+
+
+def test_forward_tokens_filter_mistakes_are_caught():
+    """What a wrong local filter would give differs measurably from the brute force: an off-by-one
+    share, and weights renormalised over the kept slots."""
+    M, H, E, k, T, e0, El = 32, 48, 8, 3, 40, 3, 3
+    wl = tiny_workload(n_tokens=T, hidden=M, inter=H, n_experts=E, local_begin=e0, n_local=El, top_k=k)
+    inp = make_inputs(wl, seed=51)
+    ref, G = brute_force_layer(inp["tokens"], inp["gate_logits"], inp["routed_w"], None,
+                               M=M, H=H, E=E, e0=e0, El=El, Ns=0, Hs=0, k=k)
+    ids = np.arange(T, dtype=np.int32)
+    args = dict(hidden=M, inter=H, n_experts=E, n_shared=0, shared_inter=0, top_k=k)
+    good = oracle.forward_tokens(inp["tokens"], inp["gate_logits"], inp["routed_w"], None, ids,
+                                 local_begin=e0, n_local=El, **args)
+    assert rel_err(good, ref) < 1e-9
+    shifted = oracle.forward_tokens(inp["tokens"], inp["gate_logits"], inp["routed_w"], None, ids,
+                                    local_begin=e0 + 1, n_local=El, **args)
+    assert rel_err(shifted, ref) > 1e-2
+    Gl = G[:, e0:e0 + El]
+    renorm = Gl / np.maximum(Gl.sum(axis=1, keepdims=True), 1e-300)
+    X = f64(inp["tokens"])
+    bad = sum(renorm[:, e, None] * dense_ffn(X, *split_expert(inp["routed_w"], e, M, H)) for e in range(El))
+    assert rel_err(bad, ref) > 1e-2
+
+
+def test_bf16_output_is_round_to_nearest():
+    """out_bf16 of the whole-layer oracle is its double output rounded once to bf16 (through one fp32
+    step): for every value the nearer of its two bf16 neighbours, chosen here in double arithmetic;
+    where the two distances differ by less than an fp32 rounding error either neighbour is accepted."""
+    wl = CONFIGS["tiny"]
+    res = _fwd(make_inputs(wl), wl)
+    out = res["out"]
+    as_f32 = out.astype(np.float32)
+    below = (as_f32.view(np.uint32) >> np.uint32(16)).astype(np.uint16)   # a bf16 neighbour of out ...
+    above = (below + np.uint16(1)).astype(np.uint16)                      # ... and the next one away from 0
+    d0, d1 = np.abs(out - f64(below)), np.abs(out - f64(above))
+    clear = np.abs(d0 - d1) > np.abs(out) * 2.0 ** -22
+    assert clear.mean() > 0.99
+    want = np.where(d1 < d0, above, below)
+    assert np.array_equal(res["out_bf16"][clear], want[clear])
+    assert np.all((res["out_bf16"] == below) | (res["out_bf16"] == above))
+    exact = as_f32.astype(np.float64) == out          # no double rounding: the generator's own rule
+    assert np.array_equal(res["out_bf16"][exact], f32_to_bf16_bits(as_f32)[exact])
+
+
 def test_planted_mistakes_are_caught():
     """A transposed projection or a dropped renormalisation must fail the brute force."""
     wl = tiny_workload(n_tokens=8, hidden=16, inter=24, n_experts=4, n_local=4, top_k=2)
