@@ -1,14 +1,16 @@
 """GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same
 seeded inputs.  Integer results (selected experts, counts, offsets, permutation) must be
-bit-exact; outputs must satisfy max_i |gpu_i - ref_i| / max(|ref_i|, rms(ref)) <= 2e-2
-(bf16 inputs, fp32 accumulation, activation and expert outputs rounded to bf16 once)."""
+bit-exact; outputs must satisfy max_i |gpu_i - ref_i| / max(|ref_i|, rms(ref row)) <= 2e-2, the
+floor being the rms of the token's own output row (helpers.rel_err_rows; bf16 inputs, fp32
+accumulation, activation and expert outputs rounded to bf16 once).  The same figure with one floor
+over all rows is printed beside it and bounded at twice the tolerance."""
 import numpy as np
 import pytest
 
 import oracle
 import os
 
-from helpers import load_tiny_golden, rel_err
+from helpers import load_tiny_golden, rel_err, rel_err_rows
 from workloads import CONFIGS, bf16_bits_to_f32, make_inputs, tiny_workload
 
 torch = pytest.importorskip("torch")
@@ -60,9 +62,9 @@ def _full_parity(wl, seed=0, r=1, order=0, mutate=None):
     d = g.DeviceInputs(wl, inp)
     out = g.run_forward(ctx, wl, d, r=r, order=order)
     _check_routing(ctx, ref, r, wl.n_tokens, wl.top_k)
-    err = rel_err(bf16_bits_to_f32(out), ref["out"])
-    print(f"       rel_err={err:.3e}", flush=True)
-    assert err <= TOL
+    err, err_all = rel_err_rows(bf16_bits_to_f32(out), ref["out"]), rel_err(bf16_bits_to_f32(out), ref["out"])
+    print(f"       rel_err={err:.3e} (one floor over all rows: {err_all:.3e})", flush=True)
+    assert err <= TOL and err_all <= 2 * TOL
     ctx.destroy()
     return out, ref
 
@@ -333,7 +335,7 @@ def test_pinned_host_chunks_that_start_off_16_byte_boundaries():
     pd = g.DeviceInputs(wl, inp, pinned=True)
     out = g.run_forward(pctx, wl, pd, r=5, order=1)
     _check_routing(pctx, ref, 5, wl.n_tokens, wl.top_k)
-    assert rel_err(bf16_bits_to_f32(out), ref["out"]) <= TOL
+    assert rel_err_rows(bf16_bits_to_f32(out), ref["out"]) <= TOL
     pctx.destroy()
 
 
@@ -619,18 +621,16 @@ def _full_size_parity(name, variants, pinned=False, seed=0, tile_variants=()):
         assert kept_total == int(local.sum())      # token conservation over the chunks
         if first is None:
             got_f = bf16_bits_to_f32(out)
-            err = rel_err(got_f, ref["out"])
+            err, err_all = rel_err_rows(got_f, ref["out"]), rel_err(got_f, ref["out"])
             # the same figure over the rows most exposed to a tiling mistake: first and last row of
             # every local expert (their tokens), reported so that a failure names where it is
             off = ref["offset"][0]
             rows = np.concatenate([off[:-1][off[1:] > off[:-1]], off[1:][off[1:] > off[:-1]] - 1])
             edge_tok = np.unique(ref["perm"][0][rows] // k)
-            rms = float(np.sqrt(np.mean(ref["out"] ** 2)))
-            edge_err = float(np.max(np.abs(got_f[edge_tok] - ref["out"][edge_tok]) /
-                                    np.maximum(np.abs(ref["out"][edge_tok]), rms))) if edge_tok.size else 0.0
-            print(f"       rel_err={err:.3e} over all {T} x {wl.hidden} elements "
-                  f"(expert edge rows: {edge_err:.3e}), kept={kept_total}", flush=True)
-            assert err <= TOL
+            edge_err = rel_err_rows(got_f[edge_tok], ref["out"][edge_tok])
+            print(f"       rel_err={err:.3e} over all {T} x {wl.hidden} elements (expert edge rows: "
+                  f"{edge_err:.3e}; one floor over all rows: {err_all:.3e}), kept={kept_total}", flush=True)
+            assert err <= TOL and err_all <= 2 * TOL
             if wl.n_shared == 0:                   # rows with nothing kept are exact zeros
                 assert not out[~local.any(axis=1)].any()
             first = out
