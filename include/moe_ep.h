@@ -133,6 +133,37 @@ int moe_ep_forward(moe_ep_ctx *ctx, const void *tokens, const float *gate_logits
                    void *stream);
 
 /*
+ * moe_ep_forward for callers that cannot allocate device memory: code running under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  There is no context: the
+ * workspaces a context would own (routing arrays, activation, expert outputs; the layout
+ * moe_ep_workspace_bytes(cfg) describes) live in one array of MOE_EP_NOALLOC_SCRATCH_BYTES bytes that
+ * is part of the library's device image, so every GPU the library runs on holds it from the first
+ * use until the process ends.  The call allocates and frees nothing, on the host or on the device,
+ * creates no stream or event, sets no memory and never waits on the host; it runs the same kernels
+ * as moe_ep_forward and produces the same bits.
+ *
+ *   cfg       as for moe_ep_create; io_mode must be MOE_EP_IO_DEVICE, device < 16, and
+ *             moe_ep_workspace_bytes(cfg) <= MOE_EP_NOALLOC_SCRATCH_BYTES (size max_tokens, max_top_k
+ *             and max_chunks to the call itself: e.g. 256 tokens of the 4096-wide, top-8 decode
+ *             shape need 23 MiB), else MOE_EP_EINVAL
+ *   r_chunks  1..max_chunks (0 is not accepted: there is no context to hold a timing model)
+ *   why       may be NULL; receives a string naming the first violated rule or the failed HIP call
+ *             (valid until the next call for the same device)
+ *   all other arguments, layouts, ownership and determinism as for moe_ep_forward.
+ *
+ * Every call on a GPU uses that GPU's one array, which keeps the previous call's contents (nothing
+ * in it has to start at zero: each forward overwrites what it reads).  Two calls that overlap on one
+ * GPU -- from two host threads, or on two streams without an order between them -- race; calls
+ * on one stream, or ordered by events, are safe.  The first call on a device looks up the array's
+ * address on that device and raises the kernels' LDS limit.
+ */
+#define MOE_EP_NOALLOC_SCRATCH_BYTES (32u << 20)
+int moe_ep_forward_noalloc(const moe_ep_config *cfg, const void *tokens, const float *gate_logits,
+                           const void *routed_w, const void *shared_w, int32_t top_k,
+                           int32_t r_chunks, int32_t order, int32_t n_tokens, void *out,
+                           void *stream, const char **why);
+
+/*
  * Test / inspection surface: host copies of what the last forward computed for chunk
  * `chunk` (synchronises the context's streams; after moe_ep_forward_dep chunk = i * r_2 + j for
  * chunk j of micro-batch i).  Any pointer may be NULL.  With Tn the tokens of this chunk:

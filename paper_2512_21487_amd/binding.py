@@ -107,6 +107,9 @@ def load_library() -> ctypes.CDLL:
     lib.moe_ep_create.argtypes = [cfgp, ctypes.POINTER(vp)]
     lib.moe_ep_forward.restype = ctypes.c_int
     lib.moe_ep_forward.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, vp, vp]
+    lib.moe_ep_forward_noalloc.restype = ctypes.c_int
+    lib.moe_ep_forward_noalloc.argtypes = [cfgp, vp, vp, vp, vp, i32, i32, i32, i32, vp, vp,
+                                           ctypes.POINTER(ctypes.c_char_p)]
     lib.moe_ep_forward_dep.restype = ctypes.c_int
     lib.moe_ep_forward_dep.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, ctypes.c_double, i32, vp, vp]
     lib.moe_ep_chunk_range.restype = ctypes.c_int
@@ -200,6 +203,27 @@ def validate_forward(cfg: MoeEpConfig, tokens, gate_logits, routed_w, shared_w, 
         ctypes.byref(cfg), _ptr(tokens), _ptr(gate_logits), _ptr(routed_w), _ptr(shared_w),
         top_k, r_chunks, order, n_tokens, _ptr(out), ctypes.byref(why))
     return rc, (why.value or b"").decode()
+
+
+NOALLOC_SCRATCH_BYTES = 32 << 20   # MOE_EP_NOALLOC_SCRATCH_BYTES
+
+
+def forward_noalloc(cfg: MoeEpConfig, tokens, gate_logits, routed_w, shared_w, top_k: int, r_chunks: int = 1,
+                    order: int = ORDER_SHARED_FIRST, n_tokens: Optional[int] = None, out=None,
+                    stream: Optional[int] = None) -> int:
+    """moe_ep_forward_noalloc: the forward without a context, on the library's static workspace."""
+    if n_tokens is None:
+        n_tokens = int(tokens.shape[0])
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream().cuda_stream
+    why = ctypes.c_char_p()
+    rc = load_library().moe_ep_forward_noalloc(ctypes.byref(cfg), _ptr(tokens), _ptr(gate_logits), _ptr(routed_w),
+                                               _ptr(shared_w), top_k, r_chunks, order, n_tokens, _ptr(out), stream,
+                                               ctypes.byref(why))
+    if rc != 0:
+        raise MoeEpError(rc, (why.value or b"").decode())
+    return rc
 
 
 def routed_tile_rows(cfg: MoeEpConfig, n_tokens: int, top_k: int, down: bool, n_cu: int = 256) -> int:

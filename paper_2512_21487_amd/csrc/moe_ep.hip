@@ -11,6 +11,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -104,6 +105,47 @@ WsLayout ws_layout(const moe_ep_config& c)
     L.hs = take(c.n_shared > 0 ? T * (size_t)c.n_shared * (size_t)c.shared_inter * 2 : 0);
     L.total = o;
     return L;
+}
+
+// every workspace pointer of a context, from the base of one block of device memory laid out by ws_layout
+void bind_workspaces(moe_ep_ctx* ctx, char* slab, const WsLayout& L)
+{
+    ctx->d_tokens = slab + L.tokens;
+    ctx->d_logits = reinterpret_cast<float*>(slab + L.logits);
+    ctx->d_out = slab + L.out;
+    ctx->idx = reinterpret_cast<int32_t*>(slab + L.idx);
+    ctx->w = reinterpret_cast<float*>(slab + L.w);
+    ctx->pos = reinterpret_cast<int32_t*>(slab + L.pos);
+    ctx->perm = reinterpret_cast<int32_t*>(slab + L.perm);
+    ctx->blk_mask = reinterpret_cast<unsigned long long*>(slab + L.blk_mask);
+    ctx->blk_off = reinterpret_cast<int32_t*>(slab + L.blk_off);
+    ctx->count = reinterpret_cast<int32_t*>(slab + L.count);
+    ctx->offset = reinterpret_cast<int32_t*>(slab + L.offset);
+    ctx->xp = reinterpret_cast<uint16_t*>(slab + L.xp);
+    ctx->h = reinterpret_cast<uint16_t*>(slab + L.h);
+    ctx->y = reinterpret_cast<uint16_t*>(slab + L.y);
+    ctx->hs = reinterpret_cast<uint16_t*>(slab + L.hs);
+}
+
+// the environment knobs of a context (tuning and comparison aids; none changes a result bit)
+void read_knobs(moe_ep_ctx* ctx)
+{
+    // tile-shape overrides for tuning (indices into the variant table of grouped_gemm.hip)
+    if (const char* v = getenv("MOE_EP_GEMM_VARIANT")) ctx->gemm_variant = atoi(v);
+    if (const char* v = getenv("MOE_EP_SHARED_VARIANT")) ctx->shared_variant = atoi(v);
+    // workgroups of a copy kernel: ~128 KB in flight fills the host link; more only queues up in the
+    // memory fabric in front of the compute kernels
+    if (const char* v = getenv("MOE_EP_LINK_GRID")) ctx->link_grid = atoi(v) > 0 ? atoi(v) : 8;
+    // MOE_EP_LINK_MEMCPY = 1 | in | out: the runtime's asynchronous copies (DMA engines) instead of copy
+    // kernels in both / one direction, kept for comparison: inbound they overlap cleanly with compute,
+    // but each call costs the host thread 0.2-0.3 ms on this system
+    if (const char* v = getenv("MOE_EP_LINK_MEMCPY")) {
+        ctx->memcpy_in = v[0] == '1' || v[0] == 'i';
+        ctx->memcpy_out = v[0] == '1' || v[0] == 'o';
+    }
+    ctx->fused_gather = fused_gather_enabled();
+    // MOE_EP_CHECK_POINTERS=0 skips the per-forward pointer queries (a few microseconds of host time)
+    if (const char* v = getenv("MOE_EP_CHECK_POINTERS")) ctx->check_spans = atoi(v) != 0;
 }
 
 int fail(moe_ep_ctx* ctx, int code, const char* what, hipError_t e = hipSuccess)
@@ -295,42 +337,13 @@ int moe_ep_create(const moe_ep_config* cfg, moe_ep_ctx** out_ctx)
     hipDeviceProp_t prop;
     if (hipGetDeviceProperties(&prop, cfg->device) != hipSuccess) { delete ctx; return MOE_EP_EHIP; }
     ctx->n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
-    // tile-shape overrides for tuning (indices into the variant table of grouped_gemm.hip)
-    if (const char* v = getenv("MOE_EP_GEMM_VARIANT")) ctx->gemm_variant = atoi(v);
-    if (const char* v = getenv("MOE_EP_SHARED_VARIANT")) ctx->shared_variant = atoi(v);
-    // workgroups of a copy kernel: ~128 KB in flight fills the host link; more only queues up in the
-    // memory fabric in front of the compute kernels
-    if (const char* v = getenv("MOE_EP_LINK_GRID")) ctx->link_grid = atoi(v) > 0 ? atoi(v) : 8;
-    // MOE_EP_LINK_MEMCPY = 1 | in | out: the runtime's asynchronous copies (DMA engines) instead of copy
-    // kernels in both / one direction, kept for comparison: inbound they overlap cleanly with compute,
-    // but each call costs the host thread 0.2-0.3 ms on this system
-    if (const char* v = getenv("MOE_EP_LINK_MEMCPY")) {
-        ctx->memcpy_in = v[0] == '1' || v[0] == 'i';
-        ctx->memcpy_out = v[0] == '1' || v[0] == 'o';
-    }
-    ctx->fused_gather = fused_gather_enabled();
-    // MOE_EP_CHECK_POINTERS=0 skips the per-forward pointer queries (a few microseconds of host time)
-    if (const char* v = getenv("MOE_EP_CHECK_POINTERS")) ctx->check_spans = atoi(v) != 0;
+    read_knobs(ctx);
     if (grouped_gemm_init() != hipSuccess) { delete ctx; return MOE_EP_EHIP; }
 
     const WsLayout L = ws_layout(*cfg);
     char* slab = nullptr;
     if (hipMalloc(reinterpret_cast<void**>(&slab), L.total) != hipSuccess) { delete ctx; return MOE_EP_ENOMEM; }
-    ctx->d_tokens = slab + L.tokens;  // L.tokens == 0: the slab base, freed in destroy
-    ctx->d_logits = reinterpret_cast<float*>(slab + L.logits);
-    ctx->d_out = slab + L.out;
-    ctx->idx = reinterpret_cast<int32_t*>(slab + L.idx);
-    ctx->w = reinterpret_cast<float*>(slab + L.w);
-    ctx->pos = reinterpret_cast<int32_t*>(slab + L.pos);
-    ctx->perm = reinterpret_cast<int32_t*>(slab + L.perm);
-    ctx->blk_mask = reinterpret_cast<unsigned long long*>(slab + L.blk_mask);
-    ctx->blk_off = reinterpret_cast<int32_t*>(slab + L.blk_off);
-    ctx->count = reinterpret_cast<int32_t*>(slab + L.count);
-    ctx->offset = reinterpret_cast<int32_t*>(slab + L.offset);
-    ctx->xp = reinterpret_cast<uint16_t*>(slab + L.xp);
-    ctx->h = reinterpret_cast<uint16_t*>(slab + L.h);
-    ctx->y = reinterpret_cast<uint16_t*>(slab + L.y);
-    ctx->hs = reinterpret_cast<uint16_t*>(slab + L.hs);
+    bind_workspaces(ctx, slab, L);  // L.tokens == 0: d_tokens is the slab base, freed in destroy
 
     // the chunk events order GPU work against GPU work only, so they skip the system-scope cache
     // write-back a default event record implies (it stalled the other streams' kernels)
@@ -828,3 +841,68 @@ int moe_ep_get_routing(moe_ep_ctx* ctx, int32_t chunk, int32_t* idx, float* w, i
 }
 
 }  // extern "C"
+
+// ---- the entry point that allocates nothing -------------------------------------------------------
+// Workspaces of moe_ep_forward_noalloc: one array per GPU in the library's own device image, there from
+// the moment the code object is loaded until the process ends.  In host code the name is only a handle
+// for hipGetSymbolAddress; kernels and copies get the address that call returns on each device.
+__device__ __align__(256) static unsigned char scratch[MOE_EP_NOALLOC_SCRATCH_BYTES];
+
+namespace {
+
+constexpr int kMaxStaticDevices = 16;
+struct StaticSlot {
+    bool ready = false;
+    char* base = nullptr;   // this device's copy of `scratch`
+    moe_ep_ctx ctx;         // no streams, no events, no owned memory: device mode needs none
+};
+StaticSlot g_static[kMaxStaticDevices];
+std::mutex g_static_mutex;
+
+}  // namespace
+
+extern "C" int moe_ep_forward_noalloc(const moe_ep_config* cfg, const void* tokens, const float* gate_logits,
+                                      const void* routed_w, const void* shared_w, int32_t top_k, int32_t r_chunks,
+                                      int32_t order, int32_t n_tokens, void* out, void* stream, const char** why)
+{
+    set_why(why, "ok");
+    if (moe_ep_validate_forward(cfg, tokens, gate_logits, routed_w, shared_w, top_k, r_chunks, order, n_tokens, out,
+                                why) != MOE_EP_OK)
+        return MOE_EP_EINVAL;
+    if (r_chunks < 1) { set_why(why, "r_chunks must be at least 1 (there is no context to hold a timing model)"); return MOE_EP_EINVAL; }
+    if (cfg->io_mode != MOE_EP_IO_DEVICE) { set_why(why, "moe_ep_forward_noalloc serves MOE_EP_IO_DEVICE only"); return MOE_EP_EINVAL; }
+    if (cfg->device >= kMaxStaticDevices) { set_why(why, "device ordinal beyond what moe_ep_forward_noalloc serves"); return MOE_EP_EINVAL; }
+    const WsLayout L = ws_layout(*cfg);
+    if (L.total > (size_t)MOE_EP_NOALLOC_SCRATCH_BYTES) {
+        set_why(why, "this configuration needs more workspace than MOE_EP_NOALLOC_SCRATCH_BYTES (see moe_ep_workspace_bytes)");
+        return MOE_EP_EINVAL;
+    }
+    StaticSlot& slot = g_static[cfg->device];
+    moe_ep_ctx* ctx = &slot.ctx;
+    if (hipSetDevice(cfg->device) != hipSuccess) { set_why(why, "hipSetDevice failed"); return MOE_EP_EHIP; }
+    {
+        std::lock_guard<std::mutex> lock(g_static_mutex);
+        if (!slot.ready) {  // once per device, with that device current
+            void* p = nullptr;
+            if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) {
+                (void)hipGetLastError();
+                set_why(why, "hipGetSymbolAddress(scratch) failed");
+                return MOE_EP_EHIP;
+            }
+            hipDeviceProp_t prop;
+            if (hipGetDeviceProperties(&prop, cfg->device) != hipSuccess) { set_why(why, "hipGetDeviceProperties failed"); return MOE_EP_EHIP; }
+            if (grouped_gemm_init() != hipSuccess) { set_why(why, "raising the kernels' LDS limit failed"); return MOE_EP_EHIP; }
+            slot.base = static_cast<char*>(p);
+            ctx->n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+            read_knobs(ctx);
+            slot.ready = true;
+        }
+    }
+    ctx->cfg = *cfg;
+    bind_workspaces(ctx, slot.base, L);
+    ctx->err[0] = 0;
+    const int rc = forward_impl(ctx, tokens, gate_logits, routed_w, shared_w, top_k, 1, r_chunks, order, false, 0.0,
+                                n_tokens, out, stream);
+    if (rc != MOE_EP_OK) set_why(why, ctx->err);
+    return rc;
+}
