@@ -16,6 +16,13 @@ expert-group side:
     with i = 0:  t_in + t_e + t_out + (r - 1) * Y,  Y = max over the three resources
     (the paper assumes t_a2e = t_e2a, which gives its  2 t_a2e + t_e + (r_2 - 1) max(t_e, t_a2e)).
 
+Extension for resources that are not independent (the paper's four "machines" are separate hardware,
+Sec. 3.2; on one GPU a transfer in flight slows the compute beside it and the reverse): every task has a
+second linear model, fitted from runs in which the other resources were active.  With one chunk nothing
+overlaps, so r = 1 is priced with the first set; with r > 1 every task is priced with the second set
+and the same timeline applies (makespan_overlap / simulate_overlap / best_r_overlap).  Equal sets give
+the paper's model back.
+
 Only tests, the smoke check and the benchmark's reporting may import this module.
 """
 from __future__ import annotations
@@ -77,6 +84,27 @@ def best_r(T: float, m_in: LinearModel, m_e: LinearModel, m_out: LinearModel, r_
     best, best_t = 1, makespan(1, T, m_in, m_e, m_out)
     for r in range(2, r_max + 1):
         t = makespan(r, T, m_in, m_e, m_out)
+        if t < best_t:
+            best, best_t = r, t
+    return best
+
+
+def makespan_overlap(r: int, T: float, alone, beside) -> float:
+    """Closed form with two sets of task models: `alone` = (m_in, m_e, m_out) for r = 1, where no two
+    tasks run at once; `beside` = the same three for r > 1, fitted while the other resources ran."""
+    return makespan(r, T, *(alone if r == 1 else beside))
+
+
+def simulate_overlap(r: int, T: float, alone, beside) -> float:
+    """The event-by-event schedule with each task's duration taken from the set that applies."""
+    return simulate(r, T, *(alone if r == 1 else beside))
+
+
+def best_r_overlap(T: float, alone, beside, r_max: int) -> int:
+    """Brute force over r = 1..r_max; the smallest r with the smallest makespan."""
+    best, best_t = 1, makespan_overlap(1, T, alone, beside)
+    for r in range(2, r_max + 1):
+        t = makespan_overlap(r, T, alone, beside)
         if t < best_t:
             best, best_t = r, t
     return best

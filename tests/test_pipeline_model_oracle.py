@@ -4,7 +4,8 @@ in 1/r_2) as a property, and hand-worked values."""
 import numpy as np
 import pytest
 
-from oracle.pipeline_model import LinearModel, best_r, fit_linear, makespan, simulate
+from oracle.pipeline_model import (LinearModel, best_r, best_r_overlap, fit_linear, makespan, makespan_overlap,
+                                   simulate, simulate_overlap)
 
 
 def _rand_models(rng):
@@ -67,3 +68,37 @@ def test_fit_linear_against_normal_equations():
     assert 0.99 < r2 <= 1.0
     a, b, r2 = fit_linear([1, 2, 3, 4], [3, 5, 7, 9])      # exact line t = 1 + 2x
     assert (a, b, r2) == (pytest.approx(1.0), pytest.approx(2.0), pytest.approx(1.0))
+
+
+def test_overlap_models_hand_worked_and_limits():
+    """Two sets of task models (alone / beside other tasks).  T = 1200: alone t_in = t_out = 0.1 + 1e-3 m,
+    t_e = 0.2 + 2e-3 m -> r = 1: 5.2.  Beside: every task 50 % slower -> r = 3 (m = 400):
+    0.75 + 1.5 + 0.75 + 2 * 1.5 = 6.0 > 5.2, so one chunk wins although the paper's model (4.0 at r = 3)
+    would cut."""
+    alone = (LinearModel(0.1, 1e-3), LinearModel(0.2, 2e-3), LinearModel(0.1, 1e-3))
+    beside = tuple(LinearModel(1.5 * m.alpha, 1.5 * m.beta) for m in alone)
+    assert makespan_overlap(1, 1200, alone, beside) == pytest.approx(5.2, abs=1e-12)
+    assert makespan_overlap(3, 1200, alone, beside) == pytest.approx(6.0, abs=1e-12)
+    assert best_r(1200, *alone, 8) > 1 and best_r_overlap(1200, alone, beside, 8) == 1
+    # equal sets: the paper's model
+    for r in (1, 2, 5):
+        assert makespan_overlap(r, 1200, alone, alone) == makespan(r, 1200, *alone)
+    assert best_r_overlap(1200, alone, alone, 8) == best_r(1200, *alone, 8)
+    # a mild slowdown still leaves chunking ahead
+    mild = tuple(LinearModel(1.05 * m.alpha, 1.05 * m.beta) for m in alone)
+    assert best_r_overlap(1200, alone, mild, 8) > 1
+
+
+def test_overlap_closed_form_equals_event_schedule_and_bounds():
+    rng = np.random.default_rng(5)
+    for _ in range(200):
+        alone = _rand_models(rng)
+        beside = tuple(LinearModel(m.alpha * float(rng.uniform(1.0, 2.0)), m.beta * float(rng.uniform(1.0, 2.0)))
+                       for m in alone)
+        T = float(rng.integers(1, 20000))
+        for r in (1, 2, 3, 8, 33):
+            assert makespan_overlap(r, T, alone, beside) == pytest.approx(simulate_overlap(r, T, alone, beside), rel=1e-12)
+            # tasks that are never faster beside others than alone: never better than the paper's model
+            assert makespan_overlap(r, T, alone, beside) >= makespan(r, T, *alone) - 1e-12
+        rb = best_r_overlap(T, alone, beside, 16)
+        assert makespan_overlap(rb, T, alone, beside) == min(makespan_overlap(r, T, alone, beside) for r in range(1, 17))
