@@ -102,12 +102,29 @@ __device__ __forceinline__ LdsTables lds_tables(uint4* lds, int ring_bytes, int 
     t.rowend = t.row0 + (G + 1);
     return t;
 }
-// The tables of one pass over ragged groups, built by the workgroup's first wavefront from the group
-// offsets alone (the host never learns them): split(lo, hi, r0, r1) names the rows [r0, r1) of a
-// group [lo, hi) that this pass covers; they are cut into tiles of bm rows and the tile counts are
-// prefix-summed, 9 groups per lane and a scan over the lanes.
-template <typename Split>
-__device__ __forceinline__ void fill_tables(const GemmArgs& a, const LdsTables& t, int bm, Split split)
+// Row tiles of ragged groups are cut to fit the group, not to a fixed height.  A tile is hb "units"
+// tall, a unit being one 32-row accumulator block for each of the workgroup's WGM rows of wavefronts
+// (unit_rows = 32 * WGM); a group of n rows has u = ceil(n / unit_rows) units and gets
+// ceil(u / max_units) tiles whose heights differ by at most one unit: 616 rows in units of 32 with
+// at most 8 per tile are tiles of 7, 7 and 6 units, not 256 + 256 + 104 rows.  A wavefront skips the
+// MFMAs of the blocks a tile does not have, so a group costs ceil(n / unit_rows) units of matrix
+// work whatever max_units is; max_units (a launch argument, at most the MB the kernel was
+// compiled for) only trades tile count against operand bytes per flop.
+struct TileCut { int tiles, base, rem; };   // tiles of base units, the first rem of them one more
+__host__ __device__ __forceinline__ TileCut cut_group(int rows, int unit_rows, int max_units)
+{
+    TileCut c;
+    const int u = (rows + unit_rows - 1) / unit_rows;
+    c.tiles = (u + max_units - 1) / max_units;
+    c.base = c.tiles ? u / c.tiles : 0;
+    c.rem = c.tiles ? u - c.base * c.tiles : 0;
+    return c;
+}
+
+// The tables of a launch over ragged groups, built by the workgroup's first wavefront from the group
+// offsets alone (the host never learns them): first and last row of every group and the prefix sum
+// of the groups' tile counts, 9 groups per lane and a scan over the lanes.
+__device__ __forceinline__ void fill_tables(const GemmArgs& a, const LdsTables& t, int unit_rows, int max_units)
 {
     static_assert(9 * 64 > kMaxGroups, "one wavefront covers every group and the total");
     const int tid = threadIdx.x;
@@ -119,11 +136,10 @@ __device__ __forceinline__ void fill_tables(const GemmArgs& a, const LdsTables& 
             const int g = tid * 9 + j;
             int c = 0;
             if (g < a.G) {
-                int r0, r1;
-                split(a.offset[g], a.offset[g + 1], r0, r1);
+                const int r0 = a.offset[g], r1 = a.offset[g + 1];
                 t.row0[g] = r0;
                 t.rowend[g] = r1;
-                c = (r1 - r0 + bm - 1) / bm;
+                c = cut_group(r1 - r0, unit_rows, max_units).tiles;
             }
             cnt[j] = sum;
             sum += c;
@@ -147,12 +163,16 @@ __device__ __forceinline__ void fill_tables(const GemmArgs& a, const LdsTables& 
 static int lds_table_bytes(bool ragged, int G) { return (4 * kTileCache + (ragged ? 3 * (G + 1) : 0)) * 4; }
 static int lds_cap(int bytes) { return bytes < kLdsPerWorkgroup ? bytes : kLdsPerWorkgroup; }
 
-// All tiles of one shape that a workgroup owns.  Ragged mode reads the groups from LDS tables the
-// caller has filled: s_pref[g] = row tiles of this shape before group g (s_pref[G] = all of them),
-// s_row0[g] / s_rowend[g] = the rows of group g this shape covers.
-template <int BM, int BN, int BK, int STAGES, int WGM, int WGN, bool SWIGLU, bool RAGGED>
+// All tiles that a workgroup owns.  Ragged mode reads the groups from LDS tables the caller has
+// filled: s_pref[g] = row tiles before group g (s_pref[G] = all of them), s_row0[g] / s_rowend[g] =
+// the rows of group g; its tiles are at most max_units units tall (cut_group).
+// EPI, what the epilogue writes (the down projection of the routed experts only; 0 everywhere else):
+// 0 bf16 results; 1 fp32 results (the experts' outputs are then not rounded before the aggregation);
+// 2 bf16 results already multiplied by the routing weight of the row's assignment (Sec. 2.1: the
+// aggregation then only adds)
+template <int BM, int BN, int BK, int STAGES, int WGM, int WGN, bool SWIGLU, bool RAGGED, int EPI = 0>
 __device__ __forceinline__ void gemm_tiles(const GemmArgs& a, uint4* lds, const int* s_pref, const int* s_row0,
-                                           const int* s_rowend, int* s_tile)
+                                           const int* s_rowend, int* s_tile, int max_units)
 {
     using Cfg = GemmCfg<BM, BN, BK, STAGES, WGM, WGN, SWIGLU>;
     constexpr int MB = Cfg::MB, NB = Cfg::NB, RPW = Cfg::RPW, XRPW = Cfg::XRPW, NW = Cfg::NW;
@@ -170,8 +190,17 @@ __device__ __forceinline__ void gemm_tiles(const GemmArgs& a, uint4* lds, const 
         mt_total = mt_per * a.G;
     }
     const int total = mt_total * NT;
-    const int per_xcd = gridDim.x >> 3;
+    // A launch lasts as many tiles as its busiest workgroup works through: rounds = ceil(total /
+    // workgroups).  Only as many workgroups as it takes to finish in that many rounds stay: the
+    // others would run one tile less and then wait, and under the package power limit the clock
+    // the remaining ones get is worth more than the idle ones' head start (984 tiles on 256 compute
+    // units are 4 rounds on 248 as well: measured 3 % faster).  The count is a multiple of 8 so that
+    // every XCD (workgroup id mod 8) keeps the same number of workgroups.
+    const int rounds = (total + (int)gridDim.x - 1) / (int)gridDim.x;
+    const int active = rounds > 0 ? min((int)gridDim.x, (((total + rounds - 1) / rounds) + 7) & ~7) : 0;
+    const int per_xcd = active >> 3;
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    if (slot >= per_xcd) return;   // the whole workgroup leaves, before any barrier of the tile pass
     const int KT = a.K / BK;
     // fragment geometry of this lane: row inside a 32-row block, swizzle term, k half
     const int fr_row = lane & 31, fr_sw = ((lane & 31) / RP) % CPR, fr_kh = lane >> 5;
@@ -181,7 +210,9 @@ __device__ __forceinline__ void gemm_tiles(const GemmArgs& a, uint4* lds, const 
     // Coordinates of a tile (wavefront-uniform) and, separately, the issue side: where the
     // direct-to-LDS loads of the tile whose K steps are being fetched come from.  The two differ at
     // the end of a tile, when the ring already takes in the next tile's first K steps.
-    struct Tile { int g, row0, nrows, n0; };
+    // hb: accumulator blocks per wavefront this tile has (MB in dense mode and for a full-height tile);
+    // the rows of a tile are dealt to the WGM rows of wavefronts hb * 32 at a time
+    struct Tile { int g, row0, nrows, n0, hb; };
     const bool mapped = RAGGED && a.a_row_map != nullptr;   // token rows gathered by the tile loads
     const uint16_t* Xi = a.A;
     const uint16_t* Wi = a.W;
@@ -191,7 +222,7 @@ __device__ __forceinline__ void gemm_tiles(const GemmArgs& a, uint4* lds, const 
     uint32_t goff[RPW];
 
     // tile number it of this workgroup -> coordinates; false past the last tile
-    auto decode_tile = [&](int it, int& g, int& row0, int& nrows, int& n0) -> bool {
+    auto decode_tile = [&](int it, int& g, int& row0, int& nrows, int& n0, int& hb) -> bool {
         const int L = (it * 8 + xcd) * per_xcd + slot;
         if (L >= total) return false;
         // tile id -> (group, row tile, column tile): inside a group the row tiles are taken in bands
@@ -223,9 +254,12 @@ __device__ __forceinline__ void gemm_tiles(const GemmArgs& a, uint4* lds, const 
             mi = band * kBand + (lb - ni * band_h);
         }
         if (RAGGED) {
-            row0 = s_row0[g] + mi * BM;
-            nrows = min(BM, s_rowend[g] - row0);
+            const TileCut c = cut_group(s_rowend[g] - s_row0[g], 32 * WGM, max_units);
+            hb = c.base + (mi < c.rem ? 1 : 0);
+            row0 = s_row0[g] + (mi * c.base + min(mi, c.rem)) * (32 * WGM);
+            nrows = min(hb * 32 * WGM, s_rowend[g] - row0);
         } else {
+            hb = MB;
             row0 = mi * BM;
             nrows = min(BM, a.dense_rows - row0);
         }
@@ -236,18 +270,19 @@ __device__ __forceinline__ void gemm_tiles(const GemmArgs& a, uint4* lds, const 
     // per tile and wavefront, with the matrix pipe waiting: the workgroup's first kTileCache tiles
     // are decoded once, one per thread, before the first tile starts.
     for (int it = tid; it < kTileCache; it += THREADS) {
-        int g = -1, row0 = 0, nrows = 0, n0 = 0;
-        if (!decode_tile(it, g, row0, nrows, n0)) g = -1;
-        s_tile[4 * it + 0] = g; s_tile[4 * it + 1] = row0; s_tile[4 * it + 2] = nrows; s_tile[4 * it + 3] = n0;
+        int g = -1, row0 = 0, nrows = 0, n0 = 0, hb = 0;
+        if (!decode_tile(it, g, row0, nrows, n0, hb)) g = -1;
+        s_tile[4 * it + 0] = g; s_tile[4 * it + 1] = row0; s_tile[4 * it + 2] = nrows | (hb << 16); s_tile[4 * it + 3] = n0;
     }
     __syncthreads();
     // tile number it of this workgroup -> coordinates, Xi / Wi / goff; false past the last tile
     auto setup_tile = [&](int it, Tile& t) __attribute__((always_inline)) -> bool {
-        int g, row0, nrows, n0;
+        int g, row0, nrows, n0, hb;
         if (it < kTileCache) {
-            g = s_tile[4 * it + 0]; row0 = s_tile[4 * it + 1]; nrows = s_tile[4 * it + 2]; n0 = s_tile[4 * it + 3];
+            g = s_tile[4 * it + 0]; row0 = s_tile[4 * it + 1]; n0 = s_tile[4 * it + 3];
+            nrows = s_tile[4 * it + 2] & 0xffff; hb = s_tile[4 * it + 2] >> 16;
             if (g < 0) return false;
-        } else if (!decode_tile(it, g, row0, nrows, n0)) {
+        } else if (!decode_tile(it, g, row0, nrows, n0, hb)) {
             return false;
         }
         // the coordinates came through LDS; telling the compiler they are wavefront-uniform keeps
@@ -256,6 +291,7 @@ __device__ __forceinline__ void gemm_tiles(const GemmArgs& a, uint4* lds, const 
         t.row0 = __builtin_amdgcn_readfirstlane(row0);
         t.nrows = __builtin_amdgcn_readfirstlane(nrows);
         t.n0 = __builtin_amdgcn_readfirstlane(n0);
+        t.hb = __builtin_amdgcn_readfirstlane(hb);
         Wi = a.W + (size_t)t.g * a.w_group_stride;
         Xi = mapped ? a.A : a.A + (size_t)t.row0 * a.lda;
 #pragma unroll
@@ -264,7 +300,13 @@ __device__ __forceinline__ void gemm_tiles(const GemmArgs& a, uint4* lds, const 
             const int r = j * RPR + ld_row;              // row in the stacked [activations; weights] tile
             const int c = ld_p ^ ((r / RP) % CPR);       // logical chunk stored at physical slot ld_p
             if (i < XRPW) {
-                int rr = min(r, t.nrows - 1);            // rows past the end re-read the last valid row
+                // LDS row r belongs to wavefront row r / WTM, which holds tile rows
+                // [(r / WTM) * hb * 32, +hb * 32); blocks the tile does not have and rows past its
+                // end re-read the last valid row (one cache line for the whole region)
+                const int within = r % Cfg::WTM;
+                int rr = (RAGGED && WGM > 1) ? (r / Cfg::WTM) * t.hb * 32 + within : r;
+                if (RAGGED && within >= t.hb * 32) rr = t.nrows - 1;
+                rr = min(rr, t.nrows - 1);
                 if (mapped) rr = a.a_row_map[t.row0 + rr] / a.a_row_div;
                 goff[i] = ((uint32_t)rr * (uint32_t)a.lda + c * 8) * 2u;
             } else {
@@ -431,8 +473,25 @@ __device__ __forceinline__ void gemm_tiles(const GemmArgs& a, uint4* lds, const 
                     // a row of blocks is pinned in its accumulator registers right before its turn
                     if (NB == 4) asm volatile("; accumulator row %4" : "+a"(acc[mb][0]), "+a"(acc[mb][1]), "+a"(acc[mb][NB > 2 ? 2 : 0]), "+a"(acc[mb][NB > 3 ? 3 : 1]) : "n"(mb));
                     else if (NB == 2) asm volatile("; accumulator row %2" : "+a"(acc[mb][0]), "+a"(acc[mb][1]) : "n"(mb));
-                    const int m = wm * Cfg::WTM + mb * 32 + fr_row;
+                    if (RAGGED && mb >= cur.hb) continue;
+                    const int m = (RAGGED ? wm * cur.hb * 32 : wm * Cfg::WTM) + mb * 32 + fr_row;
                     if (m >= cur.nrows) continue;  // the same for both lanes of an exchange
+                    if (EPI == 1) {
+                        // fp32 results: a lane's register quad is 4 consecutive columns = one 16-byte store
+                        float* frow = reinterpret_cast<float*>(a.C) + (size_t)cur.g * a.c_group_col_stride +
+                                      (size_t)(cur.row0 + m) * a.ldc + cur.n0 + wn * Cfg::WTN + fr_kh * 4;
+#pragma unroll
+                        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                            for (int q = 0; q < 4; ++q) {
+                                if (GUARD_N && cur.n0 + wn * Cfg::WTN + fr_kh * 4 + nb * 32 + q * 8 >= a.N) continue;
+                                f32x4_t o = {acc[mb][nb][q * 4], acc[mb][nb][q * 4 + 1], acc[mb][nb][q * 4 + 2], acc[mb][nb][q * 4 + 3]};
+                                *reinterpret_cast<f32x4_t*>(frow + nb * 32 + q * 8) = o;
+                            }
+                        continue;
+                    }
+                    // EPI == 2: the routing weight of the assignment this grouped row belongs to
+                    const float rw = EPI == 2 ? a.row_weight[a.row_assignment[cur.row0 + m]] : 1.0f;
                     uint16_t* crow = Cg + (size_t)(cur.row0 + m) * a.ldc;
 #pragma unroll
                     for (int nb = 0; nb < (SWIGLU ? NB / 2 : NB); ++nb) {
@@ -448,7 +507,8 @@ __device__ __forceinline__ void gemm_tiles(const GemmArgs& a, uint4* lds, const 
 #pragma unroll
                                 for (int i = 0; i < 4; ++i)
                                     h[i] = SWIGLU ? silu_f(acc[mb][nb][(q + j) * 4 + i]) * acc[mb][nb + NB / 2][(q + j) * 4 + i]
-                                                  : acc[mb][nb][(q + j) * 4 + i];
+                                         : EPI == 2 ? rw * acc[mb][nb][(q + j) * 4 + i]
+                                                    : acc[mb][nb][(q + j) * 4 + i];
                                 pk[j][0] = pack_bf16x2(h[0], h[1]);
                                 pk[j][1] = pack_bf16x2(h[2], h[3]);
                             }
@@ -481,43 +541,15 @@ __device__ __forceinline__ void gemm_tiles(const GemmArgs& a, uint4* lds, const 
 }
 
 
-// one tile shape for all groups
-template <int BM, int BN, int BK, int STAGES, int WGM, int WGN, bool SWIGLU, bool RAGGED>
+template <int BM, int BN, int BK, int STAGES, int WGM, int WGN, bool SWIGLU, bool RAGGED, int EPI = 0>
 __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_kernel(GemmArgs a)
 {
     extern __shared__ uint4 lds[];
-    const LdsTables t = lds_tables(lds, GemmCfg<BM, BN, BK, STAGES, WGM, WGN, SWIGLU>::LDS_BYTES, a.G);
-    if (RAGGED) fill_tables(a, t, BM, [](int lo, int hi, int& r0, int& r1) { r0 = lo; r1 = hi; });
-    gemm_tiles<BM, BN, BK, STAGES, WGM, WGN, SWIGLU, RAGGED>(a, lds, t.pref, t.row0, t.rowend, t.tile);
-}
-
-// Two tile shapes in one launch, ragged groups only: the rows of a group are covered by tall tiles
-// (BMA rows, fewer operand bytes per flop) as far as they fill them to more than BMB rows, and
-// what is left at the end of the group by short tiles of BMB rows, which waste fewer MFMAs on a
-// short tail.  Every workgroup first works through its share of the tall tiles, then, once its
-// ring has drained, through its share of the short ones; the tables of both passes are derived
-// here from the group offsets alone.
-template <int BMA, int BKA, int STA, int BMB, int BKB, int STB, int BN, int WGM, int WGN, bool SWIGLU>
-__global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_two_shape_kernel(GemmArgs a)
-{
-    static_assert(WGM * WGN * 64 >= 64 && BMA > BMB, "tall tiles first");
-    extern __shared__ uint4 lds[];
-    constexpr int ring_a = GemmCfg<BMA, BN, BKA, STA, WGM, WGN, SWIGLU>::LDS_BYTES;
-    constexpr int ring_b = GemmCfg<BMB, BN, BKB, STB, WGM, WGN, SWIGLU>::LDS_BYTES;
-    const LdsTables t = lds_tables(lds, ring_a > ring_b ? ring_a : ring_b, a.G);
-    // a group's rows [lo, hi): tall tiles up to `cut`, short tiles behind it
-    auto cut = [](int lo, int hi) {
-        const int r = hi - lo, n_tall = r / BMA + ((r % BMA) > BMB ? 1 : 0);
-        return min(hi, lo + n_tall * BMA);
-    };
-    auto fill = [&](bool tall) {
-        if (tall) fill_tables(a, t, BMA, [&](int lo, int hi, int& r0, int& r1) { r0 = lo; r1 = cut(lo, hi); });
-        else fill_tables(a, t, BMB, [&](int lo, int hi, int& r0, int& r1) { r0 = cut(lo, hi); r1 = hi; });
-    };
-    fill(true);
-    gemm_tiles<BMA, BN, BKA, STA, WGM, WGN, SWIGLU, true>(a, lds, t.pref, t.row0, t.rowend, t.tile);
-    fill(false);  // its first barrier also separates the two passes' use of the ring
-    gemm_tiles<BMB, BN, BKB, STB, WGM, WGN, SWIGLU, true>(a, lds, t.pref, t.row0, t.rowend, t.tile);
+    using Cfg = GemmCfg<BM, BN, BK, STAGES, WGM, WGN, SWIGLU>;
+    const LdsTables t = lds_tables(lds, Cfg::LDS_BYTES, a.G);
+    const int max_units = (a.max_units > 0 && a.max_units < Cfg::MB) ? a.max_units : Cfg::MB;
+    if (RAGGED) fill_tables(a, t, 32 * WGM, max_units);
+    gemm_tiles<BM, BN, BK, STAGES, WGM, WGN, SWIGLU, RAGGED, EPI>(a, lds, t.pref, t.row0, t.rowend, t.tile, max_units);
 }
 
 // what every kernel here assumes of its arguments beyond the shapes the caller has checked
@@ -533,13 +565,14 @@ static bool args_fit(const GemmArgs& a, bool swiglu, bool ragged, int bm)
     return !(a.N % 8 || a.ldc % 8 || a.c_group_col_stride % 8 || (reinterpret_cast<uintptr_t>(a.C) & 15));
 }
 
-template <int BM, int BN, int BK, int STAGES, int WGM, int WGN, bool SWIGLU, bool RAGGED>
+template <int BM, int BN, int BK, int STAGES, int WGM, int WGN, bool SWIGLU, bool RAGGED, int EPI = 0>
 static hipError_t launch_one(const GemmArgs& a, int n_cu, long long max_rows, hipStream_t s)
 {
     using Cfg = GemmCfg<BM, BN, BK, STAGES, WGM, WGN, SWIGLU>;
     const int NT = (a.N + Cfg::BN_OUT - 1) / Cfg::BN_OUT;
     // an upper bound of the row tiles the device-side tables can describe
-    const long long max_row_tiles = RAGGED ? (max_rows + BM - 1) / BM + a.G
+    const int tile_rows = 32 * WGM * ((a.max_units > 0 && a.max_units < Cfg::MB) ? a.max_units : Cfg::MB);
+    const long long max_row_tiles = RAGGED ? (max_rows + tile_rows - 1) / tile_rows + a.G
                                            : (long long)((a.dense_rows + BM - 1) / BM) * a.G;
     const long long max_tiles = max_row_tiles * NT;
     if (max_tiles <= 0) return hipSuccess;
@@ -554,7 +587,7 @@ static hipError_t launch_one(const GemmArgs& a, int n_cu, long long max_rows, hi
     long long grid = (long long)n_cu * occ;
     if (grid > max_tiles) grid = max_tiles;
     grid = (grid + 7) / 8 * 8;
-    hipLaunchKernelGGL((grouped_gemm_kernel<BM, BN, BK, STAGES, WGM, WGN, SWIGLU, RAGGED>),
+    hipLaunchKernelGGL((grouped_gemm_kernel<BM, BN, BK, STAGES, WGM, WGN, SWIGLU, RAGGED, EPI>),
                        dim3((unsigned)grid), dim3(Cfg::THREADS), lds_bytes, s, a);
     return hipGetLastError();
 }
@@ -571,6 +604,14 @@ static hipError_t raise_all()
                      lds_table_bytes(RG, kMaxGroups)))) != hipSuccess) return e;
     R(true, true) R(true, false) R(false, true) R(false, false)
 #undef R
+#define R(EPI)                                                                                          \
+    if ((e = hipFuncSetAttribute(                                                                       \
+             reinterpret_cast<const void*>(&grouped_gemm_kernel<BM, BN, BK, STAGES, WGM, WGN, false, true, EPI>), \
+             hipFuncAttributeMaxDynamicSharedMemorySize,                                                \
+             lds_cap(GemmCfg<BM, BN, BK, STAGES, WGM, WGN, false>::LDS_BYTES +                          \
+                     lds_table_bytes(true, kMaxGroups)))) != hipSuccess) return e;
+    R(1) R(2)
+#undef R
     return hipSuccess;
 }
 
@@ -578,63 +619,62 @@ template <int BM, int BN, int BK, int STAGES, int WGM, int WGN>
 static hipError_t launch_cfg(const GemmArgs& a, bool swiglu, int n_cu, long long max_rows, hipStream_t s)
 {
     const bool ragged = a.offset != nullptr;
+    if (swiglu && a.epi != 0) return hipErrorInvalidValue;
     if (swiglu) return ragged ? launch_one<BM, BN, BK, STAGES, WGM, WGN, true, true>(a, n_cu, max_rows, s)
                               : launch_one<BM, BN, BK, STAGES, WGM, WGN, true, false>(a, n_cu, max_rows, s);
+    if (a.epi != 0) {  // only the routed down projection has other epilogues
+        if (!ragged || a.epi < 0 || a.epi > 2 || (a.epi == 2 && (!a.row_weight || !a.row_assignment))) return hipErrorInvalidValue;
+        return a.epi == 1 ? launch_one<BM, BN, BK, STAGES, WGM, WGN, false, true, 1>(a, n_cu, max_rows, s)
+                          : launch_one<BM, BN, BK, STAGES, WGM, WGN, false, true, 2>(a, n_cu, max_rows, s);
+    }
     return ragged ? launch_one<BM, BN, BK, STAGES, WGM, WGN, false, true>(a, n_cu, max_rows, s)
                   : launch_one<BM, BN, BK, STAGES, WGM, WGN, false, false>(a, n_cu, max_rows, s);
 }
 
 // tile variants: id, BM, BN, BK, ring slots, wavefronts in m, in n
-// (0 and 7: short row tiles; with exactly 16 rows per expert they stream the weights 13 % faster than
+// (0: short row tiles; with exactly 16 rows per expert they stream the weights 13 % faster than
 // the 128-row tiles, with the ragged counts of real routing they do not, so nothing selects them by
-// default).  A ring of S slots needs K >= S * BK; for a shorter K the launcher takes the two-slot
-// variant with the same row tile and 32-wide K steps (K is a multiple of 64), listed in the last
-// column.
+// default).  BM is the tallest tile of a variant: over ragged groups the tiles are cut to fit the group
+// (cut_group) in units of 32 rows per row of wavefronts.  A ring of S slots needs K >= S * BK; for a
+// shorter K the launcher takes the two-slot variant with 32-wide K steps (K is a multiple of 64)
+// listed in the last column.
 #define MOE_EP_VARIANTS(X)         \
     X(0, 64, 128, 64, 2, 1, 2, 8)  \
     X(1, 128, 256, 64, 3, 2, 2, 6) \
     X(2, 256, 256, 64, 2, 2, 2, 9) \
-    X(3, 256, 256, 32, 4, 2, 2, 9) \
-    X(4, 128, 128, 64, 2, 2, 2, 6) \
-    X(5, 128, 256, 32, 3, 2, 2, 6) \
     X(6, 128, 256, 32, 2, 2, 2, 6) \
-    X(7, 64, 128, 64, 3, 1, 2, 8)  \
     X(8, 64, 128, 32, 2, 1, 2, 8)  \
     X(9, 256, 256, 32, 2, 2, 2, 9)  \
     X(11, 160, 256, 64, 3, 1, 4, 12) \
-    X(12, 160, 256, 32, 2, 1, 2, 12)
-
-// the two-shape kernel of the routed experts: 256-row tiles on a two-slot ring, 128-row tiles on a
-// three-slot ring, 256 output columns, 64-wide K steps, 2 x 2 wavefronts
-constexpr int kTwoShapeVariant = 10;
-#define MOE_EP_TWO_SHAPE(SW) grouped_gemm_two_shape_kernel<256, 64, 2, 128, 64, 3, 256, 2, 2, SW>
-constexpr int kTwoShapeLds = GemmCfg<128, 256, 64, 3, 2, 2, false>::LDS_BYTES > GemmCfg<256, 256, 64, 2, 2, 2, false>::LDS_BYTES
-                                 ? GemmCfg<128, 256, 64, 3, 2, 2, false>::LDS_BYTES
-                                 : GemmCfg<256, 256, 64, 2, 2, 2, false>::LDS_BYTES;
-
-static hipError_t launch_two_shape(const GemmArgs& a, bool swiglu, int n_cu, hipStream_t s)
-{
-    if (!a.offset || !args_fit(a, swiglu, true, 256)) return hipErrorInvalidValue;
-    const unsigned grid = (unsigned)((n_cu + 7) / 8 * 8);
-    const int lds_bytes = kTwoShapeLds + lds_table_bytes(true, a.G);
-    if (swiglu) hipLaunchKernelGGL((MOE_EP_TWO_SHAPE(true)), dim3(grid), dim3(256), lds_bytes, s, a);
-    else hipLaunchKernelGGL((MOE_EP_TWO_SHAPE(false)), dim3(grid), dim3(256), lds_bytes, s, a);
-    return hipGetLastError();
-}
+    X(12, 160, 256, 32, 2, 1, 2, 12) \
+    X(13, 224, 256, 64, 2, 1, 4, 12) \
+    X(14, 256, 256, 64, 2, 1, 4, 12)
 
 hipError_t grouped_gemm_init()
 {
     hipError_t e;
-    if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(&MOE_EP_TWO_SHAPE(true)),
-                                 hipFuncAttributeMaxDynamicSharedMemorySize,
-                                 kTwoShapeLds + lds_table_bytes(true, kMaxGroups))) != hipSuccess) return e;
-    if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(&MOE_EP_TWO_SHAPE(false)),
-                                 hipFuncAttributeMaxDynamicSharedMemorySize,
-                                 kTwoShapeLds + lds_table_bytes(true, kMaxGroups))) != hipSuccess) return e;
 #define X(id, BM, BN, BK, ST, WGM, WGN, FB) if ((e = raise_all<BM, BN, BK, ST, WGM, WGN>()) != hipSuccess) return e;
     MOE_EP_VARIANTS(X)
 #undef X
     return hipSuccess;
+}
+
+bool grouped_gemm_variant_shape(int variant, int K, bool ragged, int G, int shape[6])
+{
+    switch (variant) {
+#define X(id, BM, BN, BK, ST, WGM, WGN, FB)                                                          \
+        case id:                                                                                    \
+            if (K / BK < ST || GemmCfg<BM, BN, BK, ST, WGM, WGN, false>::LDS_BYTES +                \
+                                       lds_table_bytes(ragged, G) > kLdsPerWorkgroup) {              \
+                if (FB == id) return false;                                                         \
+                return grouped_gemm_variant_shape(FB, K, ragged, G, shape);                         \
+            }                                                                                       \
+            shape[0] = BM; shape[1] = BN; shape[2] = BK; shape[3] = ST; shape[4] = WGM; shape[5] = WGN; \
+            return true;
+        MOE_EP_VARIANTS(X)
+#undef X
+        default: return false;
+    }
 }
 
 hipError_t launch_grouped_gemm(const GemmArgs& a, bool swiglu, int variant, int n_cu,
@@ -642,13 +682,6 @@ hipError_t launch_grouped_gemm(const GemmArgs& a, bool swiglu, int variant, int 
 {
     if (a.K < 64 || a.K % 64) return hipErrorInvalidValue;
     if (a.offset ? max_rows <= 0 : a.dense_rows <= 0) return hipSuccess;
-    if (variant == kTwoShapeVariant) {
-        // dense rows have no ragged tails: 256-row tiles; a K too short for the three-slot ring:
-        // the 128-row shape alone, which falls back further by itself
-        if (!a.offset) return launch_grouped_gemm(a, swiglu, 2, n_cu, max_rows, s);
-        if (a.K / 64 < 3) return launch_grouped_gemm(a, swiglu, 1, n_cu, max_rows, s);
-        return launch_two_shape(a, swiglu, n_cu, s);
-    }
     switch (variant) {
 #define X(id, BM, BN, BK, ST, WGM, WGN, FB)                                                          \
         case id:                                                                                    \

@@ -22,8 +22,10 @@ hipError_t launch_gather_rows(const void* tokens, const int32_t* perm, const int
                               int k, int M, void* xp, int grid, hipStream_t s);
 
 // ---- weighted aggregation (Sec. 2.1)
+// y_mode: 0 bf16 expert outputs, weighted here; 1 fp32 expert outputs, weighted here; 2 bf16 expert
+// outputs that already carry their routing weight
 hipError_t launch_combine(const void* y, const int32_t* pos, const float* w, int Tn, int k, int M,
-                          bool accumulate, void* out, int grid, hipStream_t s);
+                          bool accumulate, int y_mode, void* out, int grid, hipStream_t s);
 
 // ---- chunk transfers over the host link (pinned-host mode); bytes must be a multiple of 4
 hipError_t launch_copy(void* dst, const void* src, size_t bytes, int grid, hipStream_t s);
@@ -53,6 +55,15 @@ struct GemmArgs {
     const int32_t* a_row_map;
     int a_row_div;
     int a_src_rows;
+    // ragged mode: tallest row tile, in units of 32 rows per row of wavefronts of the variant
+    // (0 or more than the variant holds = the variant's full height); every group's tiles are cut
+    // to equal heights below this
+    int max_units;
+    // what the epilogue writes (ragged, no SwiGLU only; see grouped_gemm.hip): 0 bf16, 1 fp32 (C then
+    // points at floats, ldc counts floats), 2 bf16 scaled by row_weight[row_assignment[grouped row]]
+    int epi;
+    const float* row_weight;
+    const int32_t* row_assignment;
 };
 // variant: index into the tile-shape table of grouped_gemm.hip; max_rows: ragged mode, an upper
 // bound of the rows of all groups together (the kernel cuts them into row tiles itself, from
@@ -60,5 +71,9 @@ struct GemmArgs {
 hipError_t launch_grouped_gemm(const GemmArgs& a, bool swiglu, int variant, int n_cu,
                                long long max_rows, hipStream_t s);
 hipError_t grouped_gemm_init();   // raises the dynamic-LDS limit of every instantiation once
+// the shape a launch of `variant` really runs (after the fall-backs for a short K or many groups):
+// shape[] = tallest tile rows, weight rows per tile, K step, ring slots, wavefronts in m, in n;
+// false for an unknown variant
+bool grouped_gemm_variant_shape(int variant, int K, bool ragged, int G, int shape[6]);
 
 }  // namespace moe_ep
