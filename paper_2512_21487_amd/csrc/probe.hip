@@ -3,13 +3,13 @@
 // fractions of the vendor peaks that the layer's kernels reach are read against these: the part
 // trades clock for matrix-pipe activity under its power limit, so the 2.5 PFLOP/s figure, which
 // assumes the maximum clock, is not a corner real operands reach.  Measurement aid only: nothing
-// on the path calls it.
+// on the path calls it; it is built into a library of its own (libmoe_ep_probe.so) for the benchmark.
 #include <cmath>
 #include <cstring>
 #include <vector>
 
 #include "common.h"
-#include "moe_ep.h"
+#include "moe_ep_probe.h"
 
 namespace moe_ep {
 
@@ -89,8 +89,8 @@ using namespace moe_ep;
 extern "C" int moe_ep_probe_device(int32_t device, int32_t zero_operands, double* mfma_tflops, double* mfma_ghz,
                                    double* copy_gbs)
 {
-    if (device < 0 || !mfma_tflops || !mfma_ghz || !copy_gbs) return MOE_EP_EINVAL;
-#define PROBE_TRY(call) do { if ((call) != hipSuccess) { (void)hipGetLastError(); return MOE_EP_EHIP; } } while (0)
+    if (device < 0 || !mfma_tflops || !mfma_ghz || !copy_gbs) return -1;
+#define PROBE_TRY(call) do { if ((call) != hipSuccess) { (void)hipGetLastError(); return -3; } } while (0)
     PROBE_TRY(hipSetDevice(device));
     hipDeviceProp_t prop;
     PROBE_TRY(hipGetDeviceProperties(&prop, device));
@@ -105,7 +105,7 @@ extern "C" int moe_ep_probe_device(int32_t device, int32_t zero_operands, double
         auto uni = [&]() { state = state * 1664525u + 1013904223u; return ((state >> 8) + 1.0f) / 16777218.0f; };
         for (uint16_t& v : h) v = to_bf16(sqrtf(-2.0f * logf(uni())) * cosf(6.2831853f * uni()));
     }
-    const size_t copy_bytes = (size_t)1 << 30;
+    const size_t copy_bytes = (size_t)1 << 29;  // twice the 256 MB memory-side cache
     Buffers buf;
     PROBE_TRY(hipMalloc(&buf.p[0], n_in * 2));
     PROBE_TRY(hipMalloc(&buf.p[1], (size_t)n_cu * 256 * 4));
@@ -114,8 +114,8 @@ extern "C" int moe_ep_probe_device(int32_t device, int32_t zero_operands, double
     PROBE_TRY(hipMemcpy(buf.p[0], h.data(), n_in * 2, hipMemcpyHostToDevice));
     hipEvent_t e0 = nullptr, e1 = nullptr;
     PROBE_TRY(hipEventCreate(&e0));
-    if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return MOE_EP_EHIP; }
-    int rc = MOE_EP_OK;
+    if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return -3; }
+    int rc = 0;
     float ms = 0.f;
     do {
         // the first launch brings the clock controller to its steady state for this load, the second is timed
@@ -124,27 +124,27 @@ extern "C" int moe_ep_probe_device(int32_t device, int32_t zero_operands, double
         auto* out = static_cast<float*>(buf.p[1]);
         auto* clk = static_cast<long long*>(buf.p[2]);
         hipLaunchKernelGGL(mfma_probe_kernel, dim3(n_cu), dim3(256), 0, 0, in, out, iters, clk);
-        if (hipEventRecord(e0, 0) != hipSuccess) { rc = MOE_EP_EHIP; break; }
+        if (hipEventRecord(e0, 0) != hipSuccess) { rc = -3; break; }
         hipLaunchKernelGGL(mfma_probe_kernel, dim3(n_cu), dim3(256), 0, 0, in, out, iters, clk);
         if (hipEventRecord(e1, 0) != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
-            hipEventElapsedTime(&ms, e0, e1) != hipSuccess || hipGetLastError() != hipSuccess) { rc = MOE_EP_EHIP; break; }
+            hipEventElapsedTime(&ms, e0, e1) != hipSuccess || hipGetLastError() != hipSuccess) { rc = -3; break; }
         std::vector<long long> hc((size_t)2 * n_cu);
-        if (hipMemcpy(hc.data(), clk, (size_t)n_cu * 16, hipMemcpyDeviceToHost) != hipSuccess) { rc = MOE_EP_EHIP; break; }
+        if (hipMemcpy(hc.data(), clk, (size_t)n_cu * 16, hipMemcpyDeviceToHost) != hipSuccess) { rc = -3; break; }
         double cycles = 0.0, ticks = 0.0;
         for (int i = 0; i < n_cu; ++i) { cycles += (double)hc[2 * i]; ticks += (double)hc[2 * i + 1]; }
         const double flop = (double)n_cu * 4.0 * iters * (kProbeSets * kProbeBlocks * kProbeBlocks) * 2.0 * 32 * 32 * 16;
         *mfma_tflops = flop / (ms * 1e-3) / 1e12;
         *mfma_ghz = ticks > 0.0 ? cycles / ticks * 0.1 : 0.0;
 
-        // streaming copy of 1 GiB: bytes read + bytes written per second
+        // streaming copy of 512 MiB: bytes read + bytes written per second
         auto* src = static_cast<uint4*>(buf.p[3]);
         auto* dst = reinterpret_cast<uint4*>(static_cast<char*>(buf.p[3]) + copy_bytes);
-        if (hipMemsetAsync(src, 1, copy_bytes, 0) != hipSuccess) { rc = MOE_EP_EHIP; break; }
+        if (hipMemsetAsync(src, 1, copy_bytes, 0) != hipSuccess) { rc = -3; break; }
         hipLaunchKernelGGL(copy_probe_kernel, dim3(n_cu * 8), dim3(256), 0, 0, src, dst, copy_bytes / 16);
-        if (hipEventRecord(e0, 0) != hipSuccess) { rc = MOE_EP_EHIP; break; }
+        if (hipEventRecord(e0, 0) != hipSuccess) { rc = -3; break; }
         hipLaunchKernelGGL(copy_probe_kernel, dim3(n_cu * 8), dim3(256), 0, 0, src, dst, copy_bytes / 16);
         if (hipEventRecord(e1, 0) != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
-            hipEventElapsedTime(&ms, e0, e1) != hipSuccess || hipGetLastError() != hipSuccess) { rc = MOE_EP_EHIP; break; }
+            hipEventElapsedTime(&ms, e0, e1) != hipSuccess || hipGetLastError() != hipSuccess) { rc = -3; break; }
         *copy_gbs = 2.0 * (double)copy_bytes / (ms * 1e-3) / 1e9;
     } while (false);
     (void)hipEventDestroy(e0);
