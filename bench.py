@@ -22,14 +22,37 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 matrix peak
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E peak
-# (workload, r_chunks, stage) -> fetched + written HBM-side bytes per launch of that stage's kernel
-# (rocprofv3 FETCH_SIZE / WRITE_SIZE runs scaled by a 1 GiB copy, profiles/hbm_traffic_dsv2_eg.txt)
-MEASURED_TRAFFIC_BYTES = {("dsv2_eg", 1, "routed_gate_up_gemm"): 922.6e6 + 37.8e6,
-                          ("dsv2_eg", 1, "shared_gate_up_gemm"): 1515.4e6 + 100.7e6}
-KERNEL_NAMES = {
-    "routed_gate_up_gemm": "grouped_gemm_kernel<160,256,64,3,1,4,swiglu,ragged> (routed gate/up projection)",
-    "shared_gate_up_gemm": "grouped_gemm_kernel<256,256,64,2,2,2,swiglu,dense> (shared-expert gate/up projection)",
-}
+RIDGE_FLOP_PER_BYTE = PEAK_BF16_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9)   # below it a GEMM launch is HBM-bound
+STAGE_LABEL = {"routed_gate_up_gemm": "routed gate/up projection", "routed_down_gemm": "routed down projection",
+               "shared_gate_up_gemm": "shared-expert gate/up projection",
+               "shared_down_gemm": "shared-expert down projection"}
+
+
+def kernel_name(ctx, stage):
+    """The kernel the last forward launched for a projection, as rocprofv3 names its template
+    arguments (read from the library: moe_ep_last_tile_shape), or None."""
+    sh = ctx.last_tile_shape(stage)
+    if sh is None:
+        return None
+    swiglu = "true" if "gate_up" in stage else "false"
+    ragged = "true" if stage.startswith("routed") else "false"
+    return (f"grouped_gemm_kernel<{sh['rows']}, {sh['cols']}, {sh['k_step']}, {sh['ring_slots']}, "
+            f"{sh['waves_m']}, {sh['waves_n']}, {swiglu}, {ragged}>")
+
+
+def measured_traffic(workload, r_chunks, stage, kernel):
+    """HBM-side bytes of one launch from the committed counter summary profiles/hbm_traffic_<workload>.txt
+    (lines "traffic <r_chunks> <stage> <kernel> <read bytes> <written bytes>"): returned only when
+    the kernel the library launches now is the one that was measured, else None."""
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        f = line.split("|")
+        if len(f) == 6 and f[0].strip() == "traffic" and int(f[1]) == r_chunks and f[2].strip() == stage:
+            if f[3].strip() == kernel:
+                return float(f[4]) + float(f[5])
+    return None
 
 
 def cpu_baseline(wl, inp, budget_s=15.0):
@@ -59,6 +82,120 @@ def cpu_baseline(wl, inp, budget_s=15.0):
                       f"(fp64, plain C) in {total_t:.1f} s"}
 
 
+COMPUTE_STAGES = ("router", "partition", "routed_gate_up_gemm", "routed_down_gemm", "shared_gate_up_gemm",
+                  "shared_down_gemm", "aggregation")
+
+
+def fit_pipeline(ctx, tokens, logits, routed, shared, out, T, k, order, stream, r_sweep=(1, 2, 4, 8)):
+    """Pinned-host contexts: fit the linear task models of Sec. 4.1 (10 warm-up + 20 timed forwards per
+    point, the protocol of Sec. 5.2), give them to the context, let it choose r_2, and measure the sweep.
+
+    First set (tasks alone): forwards of ONE chunk of m tokens, where nothing overlaps; the copy times
+    are the measured stage times, the compute time is the rest of the forward's wall time, so the three
+    add up to what a one-chunk forward takes.  Second set (tasks beside other tasks): on one GPU the
+    copies and the kernels slow each other down and kernel boundaries wait for host-bound writes, so
+    isolated task times under-price a pipeline; instead the closed form S(r, m) = t_in + t_e + t_out +
+    (r - 1) Y of Sec. 4.2 is fitted to forwards of 2 and of 4 chunks of m tokens each:
+    S(2, m) and S(4, m) are fitted as alpha + beta m; Y(m) = (S(4, m) - S(2, m)) / 2 is the step per
+    extra chunk and becomes the compute model, S(2, m) - 2 Y(m) is what the two links add and is split
+    over them."""
+    import torch
+    import paper_2512_21487_amd as pkg
+
+    def run(n_tokens, r, stages):
+        for _ in range(10):
+            ctx.forward(tokens, logits, routed, shared, k, r, order, n_tokens=n_tokens, out=out, stream=stream)
+        torch.cuda.synchronize()
+        if stages:
+            ctx.set_profiling_stages(["copy_in", "copy_out"])
+            ctx.set_profiling(20)
+        t1 = time.perf_counter()
+        for _ in range(20):
+            ctx.forward(tokens, logits, routed, shared, k, r, order, n_tokens=n_tokens, out=out, stream=stream)
+        torch.cuda.synchronize()
+        wall = (time.perf_counter() - t1) / 20 * 1e3
+        st = None
+        if stages:
+            st = ctx.get_stage_ms()
+            ctx.set_profiling(0)
+            ctx.set_profiling_stages(None)
+        return wall, st
+
+    pts = sorted({max(64, T // d) for d in (64, 32, 16, 8, 4, 2, 1)})
+    alone = {n: [] for n in ("copy_in", "copy_out", "compute")}
+    for m_tok in pts:
+        wall, st = run(m_tok, 1, True)
+        alone["copy_in"].append(st["copy_in"])
+        alone["copy_out"].append(st["copy_out"])
+        alone["compute"].append(max(wall - st["copy_in"] - st["copy_out"], 0.0))
+    fit_a = {n: pkg.fit_linear(pts, v) for n, v in alone.items()}
+    coeff = [fit_a["copy_in"][0], fit_a["copy_in"][1], fit_a["compute"][0], fit_a["compute"][1],
+             fit_a["copy_out"][0], fit_a["copy_out"][1]]
+    model_paper = pkg.PipelineModel(*coeff)                 # independent resources, as the paper assumes
+    xs2 = [m for m in pts if 2 * m <= T] if ctx.cfg.max_chunks >= 4 else []
+    xs4 = [m for m in pts if 4 * m <= T] if ctx.cfg.max_chunks >= 4 else []
+    fit_b = None
+    if len(xs4) >= 2:
+        f2 = pkg.fit_linear(xs2, [run(2 * m, 2, False)[0] for m in xs2])       # S(2, m) = alpha + beta m
+        f4 = pkg.fit_linear(xs4, [run(4 * m, 4, False)[0] for m in xs4])       # S(4, m)
+        fy = (max(0.5 * (f4[0] - f2[0]), 0.0), max(0.5 * (f4[1] - f2[1]), 0.0))  # Y = (S4 - S2) / 2
+        fr = (max(f2[0] - 2.0 * fy[0], 0.0), max(f2[1] - 2.0 * fy[1], 0.0))      # t_in + t_out = S2 - 2 Y
+        fit_b = {"two_chunks": f2, "four_chunks": f4, "step_per_chunk": (*fy, min(f2[2], f4[2])),
+                 "links_together": (*fr, min(f2[2], f4[2]))}
+        coeff += [0.5 * fr[0], 0.5 * fr[1], fy[0], fy[1], 0.5 * fr[0], 0.5 * fr[1]]
+    model = pkg.PipelineModel(*coeff)
+    chosen = pkg.choose_chunks(model, T, ctx.cfg.max_chunks)
+    r_sweep = sorted({r for r in r_sweep if r <= ctx.cfg.max_chunks} | {chosen})
+    measured = {r: run(T, r, False)[0] for r in r_sweep}
+    ctx.set_pipeline_model(model)
+    ctx.forward(tokens, logits, routed, shared, k, 0, order, n_tokens=T, out=out, stream=stream)
+    torch.cuda.synchronize()
+    fmt = lambda fit: {n: {"alpha_ms": f[0], "beta_ms_per_token": f[1], "r2": f[2]} for n, f in fit.items()}
+    return {
+        "tokens_per_point": pts,
+        "alpha_beta_r2": fmt(fit_a),
+        "alpha_beta_r2_beside_other_tasks": fmt(fit_b) if fit_b else None,
+        "predicted_ms": {str(r): pkg.pipeline_makespan(model, T, r) for r in r_sweep},
+        "predicted_ms_independent_resources": {str(r): pkg.pipeline_makespan(model_paper, T, r) for r in r_sweep},
+        "measured_ms": {str(r): measured[r] for r in r_sweep},
+        "chosen_r": ctx.last_chunks(), "measured_best_r": min(measured, key=measured.get),
+        "chosen_r_independent_resources": pkg.choose_chunks(model_paper, T, ctx.cfg.max_chunks),
+    }
+
+
+def run_repeats(args) -> int:
+    """The measurement in args.repeats fresh processes, one after the other; one JSON line whose value and
+    ms_per_step are the means over the processes (Sec. 5.4), with the per-process figures beside them."""
+    import subprocess
+    argv = [a for a in sys.argv[1:]]
+    for i, a in enumerate(argv):
+        if a == "--repeats":
+            del argv[i:i + 2]
+            break
+        if a.startswith("--repeats="):
+            del argv[i]
+            break
+    lines = []
+    for rep_i in range(args.repeats):
+        extra = [] if rep_i == 0 else ["--no-cpu-baseline"]   # the oracle is timed once
+        p = subprocess.run([sys.executable, os.path.abspath(__file__), *argv, *extra], capture_output=True, text=True)
+        if p.returncode != 0:
+            sys.stderr.write(p.stderr[-4000:])
+            return p.returncode
+        lines.append(json.loads(p.stdout.strip().splitlines()[-1]))
+    line = lines[0]
+    vals = [l["value"] for l in lines]
+    line["repeats"] = {"processes": len(lines), "value_each": vals, "ms_per_step_each": [l["ms_per_step"] for l in lines],
+                       "grouped_gemm_pct_each": [l["grouped_gemm_pct_of_bf16_mfma_peak"] for l in lines]}
+    line["value"] = sum(vals) / len(vals)
+    line["ms_per_step"] = sum(l["ms_per_step"] for l in lines) / len(lines)
+    pcts = [l["grouped_gemm_pct_of_bf16_mfma_peak"] for l in lines if l["grouped_gemm_pct_of_bf16_mfma_peak"] is not None]
+    if pcts:
+        line["grouped_gemm_pct_of_bf16_mfma_peak"] = sum(pcts) / len(pcts)
+    print(json.dumps(line))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -69,6 +206,9 @@ def main() -> int:
     ap.add_argument("--order", type=int, default=0, help="0 shared first, 1 interleaved")
     ap.add_argument("--variant", type=int, default=None, help="GEMM tile variant (tuning)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--repeats", type=int, default=1,
+                    help="run the whole measurement in this many fresh processes (Sec. 5.4: throughput is the "
+                         "average of 3 runs) and print one line: value = mean over the processes")
     ap.add_argument("--no-device-probe", action="store_true",
                     help="skip the register-only MFMA loop and the streaming copy that follow the timed forwards")
     ap.add_argument("--no-stage-timing", action="store_true",
@@ -101,6 +241,8 @@ def main() -> int:
         return 2
     if args.variant is not None:
         os.environ["MOE_EP_GEMM_VARIANT"] = str(args.variant)
+    if args.repeats > 1:
+        return run_repeats(args)
 
     import numpy as np
     import torch
@@ -157,7 +299,7 @@ def main() -> int:
     dominant = "shared_gate_up_gemm" if wl.n_shared > 0 else "routed_gate_up_gemm"
     timed_stages = sorted({dominant, "routed_gate_up_gemm", "routed_down_gemm"})
     if not args.no_stage_timing:
-        ctx.set_profiling_stages(timed_stages)
+        ctx.set_profiling_stages(timed_stages + ["forward"])   # + one event pair around every forward
         ctx.set_profiling(args.steps)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -169,6 +311,8 @@ def main() -> int:
     if args.no_stage_timing:
         stages = {n: 0.0 for n in pkg.STAGES}
     else:
+        # device time of each of the K forwards (Sec. 5.2 reports the timed trials of a point by one figure)
+        per_forward_ms = [e - b for n, _, b, e in ctx.get_timeline() if n == "forward"]
         in_region = ctx.get_stage_ms()
         # Second pass, outside the timed region: the same forwards with events around every stage
         # (the per-stage breakdown; its "forward" is a little longer than ms_per_step for that reason).
@@ -189,12 +333,17 @@ def main() -> int:
     ms_per_step = dt / args.steps * 1e3
     value = T * args.steps / dt
 
-    def gemm_line(flop, ms):
+    def gemm_line(flop, nbytes, ms):
+        """One projection: against the matrix peak, or, when its algorithmic flops per algorithmic byte
+        (weights streamed once + activations in and out) lie below the ridge, against the HBM peak."""
         if ms <= 0:
             return None
-        ach = flop / (ms * 1e-3) / 1e12
-        return {"bound": "mfma", "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                "frac": ach / PEAK_BF16_TFLOPS, "ms_per_step": ms}
+        tf, gbs = flop / (ms * 1e-3) / 1e12, nbytes / (ms * 1e-3) / 1e9
+        if flop / max(nbytes, 1.0) < RIDGE_FLOP_PER_BYTE:
+            return {"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS,
+                    "ms_per_step": ms, "tflops": tf, "flop_per_byte": flop / nbytes}
+        return {"bound": "mfma", "achieved": tf, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                "frac": tf / PEAK_BF16_TFLOPS, "ms_per_step": ms, "flop_per_byte": flop / nbytes}
 
     def hbm_line(nbytes, ms):
         if ms <= 0:
@@ -204,11 +353,18 @@ def main() -> int:
                 "frac": ach / PEAK_HBM_GBS, "ms_per_step": ms}
 
     Ns, Hs = wl.n_shared, wl.shared_inter
+    # algorithmic bytes of a projection launch: every chunk streams the weights of all local (or shared)
+    # experts once, reads its input rows and writes its output rows (bf16)
+    r = args.r
     kernels = {
-        "routed_gate_up_gemm": gemm_line(4.0 * kept * M * H, stages["routed_gate_up_gemm"]),
-        "routed_down_gemm": gemm_line(2.0 * kept * M * H, stages["routed_down_gemm"]),
-        "shared_gate_up_gemm": gemm_line(4.0 * T * Ns * M * Hs, stages["shared_gate_up_gemm"]),
-        "shared_down_gemm": gemm_line(2.0 * T * Ns * M * Hs, stages["shared_down_gemm"]),
+        "routed_gate_up_gemm": gemm_line(4.0 * kept * M * H, r * wl.n_local * 4.0 * H * M + kept * 2.0 * (M + H),
+                                         stages["routed_gate_up_gemm"]),
+        "routed_down_gemm": gemm_line(2.0 * kept * M * H, r * wl.n_local * 2.0 * H * M + kept * 2.0 * (M + H),
+                                      stages["routed_down_gemm"]),
+        "shared_gate_up_gemm": gemm_line(4.0 * T * Ns * M * Hs, Ns * 4.0 * Hs * M + T * 2.0 * (M + Ns * Hs),
+                                         stages["shared_gate_up_gemm"]),
+        "shared_down_gemm": gemm_line(2.0 * T * Ns * M * Hs, Ns * 2.0 * Hs * M + T * 2.0 * (M + Ns * Hs),
+                                      stages["shared_down_gemm"]),
         # partition: the routing arrays (masks, offsets, positions, row map); the token rows are
         # gathered by the gate/up projection's own tile loads unless MOE_EP_FUSED_GATHER=0, in which
         # case a grouped copy adds 2M bytes read + 2M written per kept row
@@ -221,13 +377,17 @@ def main() -> int:
         "router": hbm_line(T * (4.0 * wl.n_experts + 8.0 * k), stages["router"]),
     }
     routed_ms = stages["routed_gate_up_gemm"] + stages["routed_down_gemm"]
-    routed_line = gemm_line(6.0 * kept * M * H, routed_ms)
+    routed_pct = 100.0 * 6.0 * kept * M * H / (routed_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS if routed_ms > 0 else None
     roof = dict(kernels[dominant] or {})
     roof.pop("ms_per_step", None)
-    # HBM-side bytes of one launch of that kernel; measured for the default workload only
-    roof["traffic"] = MEASURED_TRAFFIC_BYTES.get((wl.name, args.r, dominant))
-    roof["kernel"] = KERNEL_NAMES[dominant]
+    names = {st: kernel_name(ctx, st) for st in STAGE_LABEL}
+    # HBM-side bytes of one launch of that kernel, from the committed counter summary, if it is of this kernel
+    roof["traffic"] = measured_traffic(wl.name, args.r, dominant, names[dominant])
+    roof["kernel"] = f"{names[dominant]} ({STAGE_LABEL[dominant]})"
     roof["launches_per_step"] = args.r if dominant.startswith("routed") or args.order == 1 else 1
+    for st, line_ in kernels.items():
+        if line_ is not None and st in names:
+            line_["kernel"] = names[st]
 
     line = {
         "metric": "expert-layer tokens/sec at 1 GPU; grouped-GEMM % of bf16 MFMA peak",
@@ -239,7 +399,7 @@ def main() -> int:
                    "r_chunks": args.r, "order": args.order, "kept_assignments": kept,
                    "expert_load": {"max": int(load.max()), "mean": float(load.mean()), "min": int(load.min()),
                                    "empty": int((load == 0).sum())}},
-        "grouped_gemm_pct_of_bf16_mfma_peak": None if routed_line is None else 100.0 * routed_line["frac"],
+        "grouped_gemm_pct_of_bf16_mfma_peak": routed_pct,
         "roofline": roof,
         "kernels": kernels,
         "stage_ms": stages,
@@ -249,6 +409,10 @@ def main() -> int:
                              " (there: " + ", ".join(f"{n} {second_pass[n]:.4f}" for n in timed_stages) + " ms)")),
         "host_enqueue_ms_per_step": t_enq / args.steps * 1e3,
     }
+    if not args.no_stage_timing and per_forward_ms:
+        med = float(np.median(per_forward_ms))
+        line["ms_per_step_median"] = med                   # median device time of one forward over the K steps
+        line["value_at_median"] = T / (med * 1e-3)
     if pinned:
         # Chunk pipeline against the closed form of Sec. 4.2 (layer 0, one slice): three resources
         # (inbound link, expert compute, outbound link), r chunks, steady-state step = the slowest
@@ -265,47 +429,7 @@ def main() -> int:
             "bytes_in_per_chunk": (T // r) * (2 * M + 4 * wl.n_experts), "bytes_out_per_chunk": (T // r) * 2 * M,
         }
     if pinned and args.fit_pipeline:
-        # Sec. 4.1: t = alpha + beta * m for each resource, m = tokens of a chunk; fitted from r=1
-        # forwards over a sweep of m (10 warm-up + 20 timed per point, the protocol of Sec. 5.2)
-        pts = sorted({max(64, T // d) for d in (64, 32, 16, 8, 4, 2, 1)})
-        samples = {"copy_in": [], "copy_out": [], "compute": []}
-        for m_tok in pts:
-            for _ in range(10):
-                ctx.forward(tokens, logits, routed, shared, k, 1, args.order, n_tokens=m_tok, out=out, stream=stream)
-            torch.cuda.synchronize()
-            ctx.set_profiling(20)
-            for _ in range(20):
-                ctx.forward(tokens, logits, routed, shared, k, 1, args.order, n_tokens=m_tok, out=out, stream=stream)
-            st = ctx.get_stage_ms()
-            ctx.set_profiling(0)
-            samples["copy_in"].append(st["copy_in"]); samples["copy_out"].append(st["copy_out"])
-            samples["compute"].append(sum(st[n] for n in ("router", "partition", "routed_gate_up_gemm",
-                                                          "routed_down_gemm", "shared_gate_up_gemm",
-                                                          "shared_down_gemm", "aggregation")))
-        fit = {n: pkg.fit_linear(pts, v) for n, v in samples.items()}
-        model = pkg.PipelineModel(fit["copy_in"][0], fit["copy_in"][1], fit["compute"][0], fit["compute"][1],
-                                  fit["copy_out"][0], fit["copy_out"][1])
-        r_sweep = [r for r in (1, 2, 4, 8) if r <= ctx.cfg.max_chunks]
-        measured = {}
-        for r in r_sweep:
-            for _ in range(5):
-                ctx.forward(tokens, logits, routed, shared, k, r, args.order, n_tokens=T, out=out, stream=stream)
-            torch.cuda.synchronize()
-            t1 = time.perf_counter()
-            for _ in range(20):
-                ctx.forward(tokens, logits, routed, shared, k, r, args.order, n_tokens=T, out=out, stream=stream)
-            torch.cuda.synchronize()
-            measured[r] = (time.perf_counter() - t1) / 20 * 1e3
-        ctx.set_pipeline_model(model)
-        ctx.forward(tokens, logits, routed, shared, k, 0, args.order, n_tokens=T, out=out, stream=stream)
-        torch.cuda.synchronize()
-        line["pipeline_fit"] = {
-            "tokens_per_point": pts,
-            "alpha_beta_r2": {n: {"alpha_ms": f[0], "beta_ms_per_token": f[1], "r2": f[2]} for n, f in fit.items()},
-            "predicted_ms": {str(r): pkg.pipeline_makespan(model, T, r) for r in r_sweep},
-            "measured_ms": {str(r): measured[r] for r in r_sweep},
-            "chosen_r": ctx.last_chunks(), "measured_best_r": min(measured, key=measured.get),
-        }
+        line["pipeline_fit"] = fit_pipeline(ctx, tokens, logits, routed, shared, out, T, k, args.order, stream)
     if args.graph and not pinned:
         side = torch.cuda.Stream()
         graph = torch.cuda.CUDAGraph()
@@ -386,8 +510,19 @@ def main() -> int:
             layer_step()
         torch.cuda.synchronize()
         per_layer_ms = (time.perf_counter() - t1) / (args.steps * L) * 1e3
+        # the schedule model's per-layer term max(G, r_1 F) (Sec. 4.2), fed with this run's task times; it
+        # assumes shared experts, links and routed experts on hardware of their own, here they share one GPU
+        rr = args.r
+        t_s = stages["shared_gate_up_gemm"] + stages["shared_down_gemm"]
+        t_e = sum(stages[n] for n in ("router", "partition", "routed_gate_up_gemm", "routed_down_gemm", "aggregation")) / rr
+        t_c = 0.5 * (stages["copy_in"] + stages["copy_out"]) / rr
+        mod = pkg.DepModels(0.0, 0.0, t_s, 0.0, t_e, 0.0, t_c, 0.0)
+        span = lambda n: pkg.dep_makespan(mod, pkg.DepProblem(ag=1, n_experts=wl.n_experts, top_k=k, seq_len=1,
+                                                              n_layers=n), 1, 1, rr)
         line["multi_layer"] = {"layers": L, "ms_per_layer": per_layer_ms, "tokens_per_s": T / (per_layer_ms * 1e-3),
-                               "single_layer_ms": ms_per_step}
+                               "single_layer_ms": ms_per_step,
+                               "model_ms_per_layer": (span(L) - span(1)) / (L - 1),
+                               "model_tasks_ms": {"shared": t_s, "experts_per_chunk": t_e, "link_per_chunk": t_c}}
     if not args.no_device_probe:
         # what this machine sustains, measured right after the timed forwards (outside the timed region):
         # a register-only MFMA loop on random bf16 operands and a streaming copy; the vendor peaks in
@@ -397,6 +532,8 @@ def main() -> int:
                                 "copy_gbs_read_plus_write": probe["copy_gbs"]}
         if roof.get("bound") == "mfma" and probe["mfma_tflops"] > 0:
             line["roofline"]["frac_of_measured_ceiling"] = roof["achieved"] / probe["mfma_tflops"]
+        if roof.get("bound") == "hbm" and probe["copy_gbs"] > 0:
+            line["roofline"]["frac_of_measured_ceiling"] = roof["achieved"] / probe["copy_gbs"]
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(wl, inp)
     if args.copy_probe:

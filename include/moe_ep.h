@@ -219,6 +219,14 @@ typedef struct {
     double alpha_in, beta_in;   /* inbound transfer (A2E stand-in)  */
     double alpha_e, beta_e;     /* expert compute of a chunk        */
     double alpha_out, beta_out; /* outbound transfer (E2A stand-in) */
+    /* The same three tasks while the other resources are active.  The paper's resources are separate
+     * hardware (Sec. 3.2); where they share a GPU a transfer in flight slows the compute beside it and
+     * the reverse, so coefficients fitted from forwards with r_chunks > 1 go here.  All six zero = the
+     * resources are independent (the paper's model).  When set, one chunk (nothing overlaps) is priced
+     * with the coefficients above and every r_chunks > 1 with these. */
+    double alpha_in_beside, beta_in_beside;
+    double alpha_e_beside, beta_e_beside;
+    double alpha_out_beside, beta_out_beside;
 } moe_ep_pipeline_model;
 
 /* Least-squares fit of t = alpha + beta * x over n >= 2 samples (host arrays); *r2 (may be NULL)
@@ -228,13 +236,15 @@ int moe_ep_fit_linear(const double *x, const double *t, int32_t n, double *alpha
 
 /* Finish time of one slice of n_tokens cut into r_chunks chunks on three serial resources:
  * t_in + t_e + t_out + (r - 1) * max(t_in, t_e, t_out), each at n_tokens / r_chunks tokens
- * (the paper's 2 t_a2e + t_e + (r_2 - 1) max(t_e, t_a2e) when both links are alike).
- * Returns a negative value on bad arguments. */
+ * (the paper's 2 t_a2e + t_e + (r_2 - 1) max(t_e, t_a2e) when both links are alike); with the
+ * second set of coefficients present it prices r_chunks > 1.  Returns a negative value on bad
+ * arguments. */
 double moe_ep_pipeline_makespan(const moe_ep_pipeline_model *m, int32_t n_tokens, int32_t r_chunks);
 
 /* The smallest r in 1..r_max that minimises moe_ep_pipeline_makespan: golden-section search over
- * 1/r (the objective is convex there) and a walk over the neighbouring integers.  Returns r, or
- * MOE_EP_EINVAL (negative) on bad arguments. */
+ * 1/r (the objective is convex there) and a walk over the neighbouring integers; with the second
+ * set of coefficients present the search covers r >= 2 and its result is compared with r = 1.
+ * Returns r, or MOE_EP_EINVAL (negative) on bad arguments. */
 int32_t moe_ep_choose_chunks(const moe_ep_pipeline_model *m, int32_t n_tokens, int32_t r_max);
 
 /* Give a context its timing model: afterwards moe_ep_forward accepts r_chunks == 0 and picks
@@ -298,27 +308,27 @@ int moe_ep_chunk_range(int32_t n_tokens, int32_t r_1, int32_t r_2, int32_t chunk
                        int32_t *count);
 
 /*
- * Measurement aid, not on the path: what `device` sustains right now.  *mfma_tflops and *mfma_ghz:
- * rate and shader clock of a register-only v_mfma_f32_32x32x16_bf16 loop on all compute units
- * (no LDS, no memory traffic; operands are standard-normal bf16 values, or all zeros when
- * zero_operands != 0 -- the part trades clock for matrix-pipe activity under its power limit, so
- * the two differ); *copy_gbs: bytes read plus bytes written per second by a device-to-device copy
- * of 1 GiB.  Allocates and frees 2 GiB of device memory, runs on the default stream and returns
- * when done (about 0.1 s).  MOE_EP_EINVAL on NULL outputs, MOE_EP_EHIP if a HIP call fails.
- */
-int moe_ep_probe_device(int32_t device, int32_t zero_operands, double *mfma_tflops, double *mfma_ghz,
-                        double *copy_gbs);
-
-/*
- * Host only: the rows per tile (128 or 160) the library gives a routed projection of a chunk of
- * n_tokens tokens -- down == 0: gate/up projection, else the down projection -- on a GPU of n_cu
- * compute units.  An expert of the balanced load of Sec. 3.1 gets n_tokens * top_k / E rows; the
- * taller tile loads fewer operand rows per output row but takes longer, and a launch lasts as many
- * tiles as its busiest compute unit works through, so the choice compares expected rounds of tiles
- * times the time of a tile.  It changes no result bit.  MOE_EP_EINVAL (negative) on bad arguments.
+ * Host only: the tallest row tile (128, 160, 224 or 256 rows) the library gives a routed projection
+ * (Sec. 3.1, Eq. moe_detail) of a chunk of n_tokens tokens -- down == 0: gate/up projection, else
+ * the down projection -- on a GPU of n_cu compute units.  An expert of the balanced load of Sec. 3.1
+ * gets n_tokens * top_k / E rows; its row tiles are cut to equal heights below the tallest; the
+ * choice compares expected rounds of tiles times the measured time of a tile of each shape.  It
+ * changes no result bit.  MOE_EP_EINVAL (negative) on bad arguments.
  */
 int32_t moe_ep_routed_tile_rows(const moe_ep_config *cfg, int32_t n_tokens, int32_t top_k, int32_t down,
                                 int32_t n_cu);
+
+/*
+ * What the last forward launched for a projection: stage = index into ms[] of moe_ep_get_stage_ms
+ * (2 routed gate/up, 3 routed down, 4 shared gate/up, 5 shared down; Sec. 3.1, Eq. moe_detail and
+ * Eq. shared_detail), chunk = the chunk of that forward (ignored for the shared experts).  Receives
+ * the kernel's tile shape -- tallest tile rows, weight rows per tile, K step, LDS ring slots,
+ * wavefronts along rows and along columns -- so that a measurement can name the kernel it timed.
+ * Any pointer may be NULL.  MOE_EP_ESTATE before any forward or for a stage the layer does not have.
+ */
+int moe_ep_last_tile_shape(const moe_ep_ctx *ctx, int32_t chunk, int32_t stage, int32_t *rows,
+                           int32_t *cols, int32_t *k_step, int32_t *ring_slots, int32_t *waves_m,
+                           int32_t *waves_n);
 
 int moe_ep_forward_dep(moe_ep_ctx *ctx, const void *tokens, const float *gate_logits,
                        const void *routed_w, const void *shared_w, int32_t top_k, int32_t r_1,

@@ -38,9 +38,12 @@ class MoeEpError(RuntimeError):
 
 
 class PipelineModel(ctypes.Structure):
-    """Mirror of ``moe_ep_pipeline_model`` (alpha + beta * tokens-per-chunk for each resource)."""
+    """Mirror of ``moe_ep_pipeline_model`` (alpha + beta * tokens-per-chunk for each resource; the
+    ``*_beside`` coefficients, all zero when absent, price the tasks while other resources are active)."""
     _fields_ = [(n, ctypes.c_double) for n in (
-        "alpha_in", "beta_in", "alpha_e", "beta_e", "alpha_out", "beta_out")]
+        "alpha_in", "beta_in", "alpha_e", "beta_e", "alpha_out", "beta_out",
+        "alpha_in_beside", "beta_in_beside", "alpha_e_beside", "beta_e_beside", "alpha_out_beside",
+        "beta_out_beside")]
 
 
 class DepModels(ctypes.Structure):
@@ -114,11 +117,10 @@ def load_library() -> ctypes.CDLL:
     lib.moe_ep_forward_dep.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, ctypes.c_double, i32, vp, vp]
     lib.moe_ep_chunk_range.restype = ctypes.c_int
     lib.moe_ep_chunk_range.argtypes = [i32, i32, i32, i32, vp, vp]
-    lib.moe_ep_probe_device.restype = ctypes.c_int
-    lib.moe_ep_probe_device.argtypes = [i32, i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double),
-                                        ctypes.POINTER(ctypes.c_double)]
     lib.moe_ep_routed_tile_rows.restype = i32
     lib.moe_ep_routed_tile_rows.argtypes = [cfgp, i32, i32, i32, i32]
+    lib.moe_ep_last_tile_shape.restype = ctypes.c_int
+    lib.moe_ep_last_tile_shape.argtypes = [vp, i32, i32] + [ctypes.POINTER(i32)] * 6
     lib.moe_ep_get_routing.restype = ctypes.c_int
     lib.moe_ep_get_routing.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp]
     lib.moe_ep_set_profiling.restype = ctypes.c_int
@@ -227,18 +229,36 @@ def forward_noalloc(cfg: MoeEpConfig, tokens, gate_logits, routed_w, shared_w, t
 
 
 def routed_tile_rows(cfg: MoeEpConfig, n_tokens: int, top_k: int, down: bool, n_cu: int = 256) -> int:
-    """moe_ep_routed_tile_rows: rows per tile (128 or 160) of a routed projection of a chunk."""
+    """moe_ep_routed_tile_rows: tallest row tile (128, 160, 224 or 256) of a routed projection of a chunk."""
     rows = int(load_library().moe_ep_routed_tile_rows(ctypes.byref(cfg), n_tokens, top_k, int(down), n_cu))
     if rows < 0:
         raise ValueError("moe_ep_routed_tile_rows: bad arguments")
     return rows
 
 
+_PROBE_LIB_PATH = os.path.join(_HERE, "libmoe_ep_probe.so")
+_probe_lib: Optional[ctypes.CDLL] = None
+
+
+def load_probe_library() -> ctypes.CDLL:
+    """libmoe_ep_probe.so (include/moe_ep_probe.h): the benchmark's measurement aid, a library of its own."""
+    global _probe_lib
+    if _probe_lib is None:
+        if not os.path.exists(_PROBE_LIB_PATH):
+            raise ImportError(f"{_PROBE_LIB_PATH} is missing: run `python -m paper_2512_21487_amd.build` first")
+        lib = ctypes.CDLL(_PROBE_LIB_PATH)
+        dp = ctypes.POINTER(ctypes.c_double)
+        lib.moe_ep_probe_device.restype = ctypes.c_int
+        lib.moe_ep_probe_device.argtypes = [ctypes.c_int32, ctypes.c_int32, dp, dp, dp]
+        _probe_lib = lib
+    return _probe_lib
+
+
 def probe_device(device: int = 0, zero_operands: bool = False) -> Dict[str, float]:
     """moe_ep_probe_device: register-only MFMA rate and clock, streaming copy rate of the GPU."""
     tf, ghz, gbs = ctypes.c_double(), ctypes.c_double(), ctypes.c_double()
-    rc = load_library().moe_ep_probe_device(device, int(zero_operands), ctypes.byref(tf), ctypes.byref(ghz),
-                                            ctypes.byref(gbs))
+    rc = load_probe_library().moe_ep_probe_device(device, int(zero_operands), ctypes.byref(tf), ctypes.byref(ghz),
+                                                  ctypes.byref(gbs))
     if rc != 0:
         raise MoeEpError(rc, "moe_ep_probe_device failed")
     return {"mfma_tflops": tf.value, "mfma_ghz": ghz.value, "copy_gbs": gbs.value}
@@ -410,6 +430,18 @@ class MoeEp:
         return {"idx": idx, "w": w, "pos": pos, "count": count, "offset": offset,
                 "perm": perm[:offset[-1]].copy()}
 
+    # -- moe_ep_last_tile_shape -----------------------------------------------------------
+    def last_tile_shape(self, stage: str, chunk: int = 0) -> Optional[Dict[str, int]]:
+        """Tile shape of the kernel the last forward launched for `stage` (an entry of STAGES naming a
+        projection); None if the layer has no such stage."""
+        v = [ctypes.c_int32() for _ in range(6)]
+        rc = self._lib.moe_ep_last_tile_shape(self._ctx, chunk, STAGES.index(stage), *[ctypes.byref(x) for x in v])
+        if rc == -4:
+            return None
+        if rc != 0:
+            raise MoeEpError(rc, "moe_ep_last_tile_shape: bad arguments")
+        return dict(zip(("rows", "cols", "k_step", "ring_slots", "waves_m", "waves_n"), (x.value for x in v)))
+
     # -- timing model ---------------------------------------------------------------------
     def set_pipeline_model(self, model: Optional[PipelineModel]) -> None:
         rc = self._lib.moe_ep_set_pipeline_model(self._ctx, ctypes.byref(model) if model else None)
@@ -460,6 +492,12 @@ class MoeEp:
             self._ctx = ctypes.c_void_p()
 
     def __del__(self):
+        # At interpreter shutdown the HIP runtime, a preloaded profiler and torch's allocators are being
+        # torn down in an order this object does not control: calling into the library then could touch
+        # streams and events that are already gone.  The process is ending; the driver reclaims the memory.
+        import sys
+        if sys is None or sys.is_finalizing():
+            return
         try:
             self.destroy()
         except Exception:

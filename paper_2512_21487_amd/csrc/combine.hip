@@ -14,6 +14,17 @@ __device__ __forceinline__ void fma8(float* acc, float ws, const uint4& v) {
     acc[6] = fmaf(ws, bf16_lo(v.w), acc[6]); acc[7] = fmaf(ws, bf16_hi(v.w), acc[7]);
 }
 
+// 8 fp32 values of an expert's output row, weighted into the accumulator
+__device__ __forceinline__ void fma8f(float* acc, float ws, const f32x4_t& lo, const f32x4_t& hi) {
+    acc[0] = fmaf(ws, lo[0], acc[0]); acc[1] = fmaf(ws, lo[1], acc[1]);
+    acc[2] = fmaf(ws, lo[2], acc[2]); acc[3] = fmaf(ws, lo[3], acc[3]);
+    acc[4] = fmaf(ws, hi[0], acc[4]); acc[5] = fmaf(ws, hi[1], acc[5]);
+    acc[6] = fmaf(ws, hi[2], acc[6]); acc[7] = fmaf(ws, hi[3], acc[7]);
+}
+
+// YMODE: 0 = y holds bf16 expert outputs, 1 = fp32 expert outputs (rows of M floats), 2 = bf16
+// expert outputs that already carry their routing weight (the sum then uses weight 1)
+template <int YMODE>
 __global__ __launch_bounds__(256) void combine_kernel(
     const uint4* __restrict__ y, const int32_t* __restrict__ pos, const float* __restrict__ w, int Tn,
     int k, int M8, bool accumulate, uint4* out)
@@ -36,13 +47,22 @@ __global__ __launch_bounds__(256) void combine_kernel(
             float acc_b[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
             for (int s = 0; s < k; ++s) {
                 const int p = __shfl(my_pos, s, 64);  // uniform over the wavefront
-                const float ws = __shfl(my_w, s, 64);
+                const float ws = YMODE == 2 ? 1.0f : __shfl(my_w, s, 64);
                 if (p >= 0) {
-                    uint4 va, vb;
-                    if (in_a) va = y[(size_t)p * M8 + ca];
-                    if (in_b) vb = y[(size_t)p * M8 + cb];
-                    if (in_a) fma8(acc_a, ws, va);
-                    if (in_b) fma8(acc_b, ws, vb);
+                    if (YMODE == 1) {
+                        const f32x4_t* yf = reinterpret_cast<const f32x4_t*>(y) + (size_t)p * M8 * 2;
+                        f32x4_t a0, a1, b0, b1;
+                        if (in_a) { a0 = yf[2 * ca]; a1 = yf[2 * ca + 1]; }
+                        if (in_b) { b0 = yf[2 * cb]; b1 = yf[2 * cb + 1]; }
+                        if (in_a) fma8f(acc_a, ws, a0, a1);
+                        if (in_b) fma8f(acc_b, ws, b0, b1);
+                    } else {
+                        uint4 va, vb;
+                        if (in_a) va = y[(size_t)p * M8 + ca];
+                        if (in_b) vb = y[(size_t)p * M8 + cb];
+                        if (in_a) fma8(acc_a, ws, va);
+                        if (in_b) fma8(acc_b, ws, vb);
+                    }
                 }
             }
             if (in_a) {
@@ -64,11 +84,15 @@ __global__ __launch_bounds__(256) void combine_kernel(
 }
 
 hipError_t launch_combine(const void* y, const int32_t* pos, const float* w, int Tn, int k, int M,
-                          bool accumulate, void* out, int grid, hipStream_t s)
+                          bool accumulate, int y_mode, void* out, int grid, hipStream_t s)
 {
     if (Tn <= 0) return hipSuccess;
-    hipLaunchKernelGGL(combine_kernel, dim3(grid), dim3(256), 0, s, static_cast<const uint4*>(y), pos, w, Tn, k,
-                       M / 8, accumulate, static_cast<uint4*>(out));
+    if (y_mode < 0 || y_mode > 2) return hipErrorInvalidValue;
+    auto* yy = static_cast<const uint4*>(y);
+    auto* oo = static_cast<uint4*>(out);
+    if (y_mode == 0) hipLaunchKernelGGL(combine_kernel<0>, dim3(grid), dim3(256), 0, s, yy, pos, w, Tn, k, M / 8, accumulate, oo);
+    else if (y_mode == 1) hipLaunchKernelGGL(combine_kernel<1>, dim3(grid), dim3(256), 0, s, yy, pos, w, Tn, k, M / 8, accumulate, oo);
+    else hipLaunchKernelGGL(combine_kernel<2>, dim3(grid), dim3(256), 0, s, yy, pos, w, Tn, k, M / 8, accumulate, oo);
     return hipGetLastError();
 }
 

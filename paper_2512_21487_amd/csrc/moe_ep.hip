@@ -32,8 +32,11 @@ struct moe_ep_ctx {
     moe_ep_config cfg;
     int n_cu = 0;
     int gemm_variant = -1;   // routed experts: tile variant, -1 = chosen per chunk (routed_variant)
+    int up_variant = -1, down_variant = -1;  // the same for one projection only (tuning)
+    int up_units = 0, down_units = 0;        // tallest row tile in units (0 = chosen / the variant's height)
     int shared_variant = 2;  // shared experts: dense rows, 256-row tiles
     bool fused_gather = true;  // the gate/up projection gathers the token rows itself (no grouped copy)
+    int y_mode = 0;            // expert outputs: 0 bf16, 1 fp32, 2 bf16 scaled by the routing weight (expert_out_mode)
     int link_grid = 8;         // workgroups of a host-link copy kernel
     bool memcpy_in = false, memcpy_out = false;  // host-link copies through the runtime instead of kernels
     bool check_spans = true;   // every forward asks the runtime what its pointer arguments point at
@@ -55,6 +58,8 @@ struct moe_ep_ctx {
     std::vector<hipEvent_t> ev_attn, ev_shared;
     // last forward (for moe_ep_get_routing): tokens, top_k, chunks = micro-batches x chunks of each
     int last_T = -1, last_k = 0, last_r = 0, last_r1 = 1;
+    struct ChunkVariants { int up, down; };
+    std::vector<ChunkVariants> last_variants;  // per chunk of the last forward: tile variants of the routed projections
     // stage profiling
     int prof_depth = 0, prof_recorded = 0;
     uint32_t prof_mask = ~0u;
@@ -83,6 +88,17 @@ bool fused_gather_enabled()
     return v == nullptr || atoi(v) != 0;
 }
 
+// MOE_EP_EXPERT_OUT = fp32 | scaled: how the routed experts' outputs travel from the down projection
+// to the aggregation -- as fp32 (not rounded in between; twice the bytes) or as bf16 already
+// multiplied by the routing weight (Sec. 2.1).  Unset: bf16, weighted by the aggregation.  Both
+// change where the path rounds, hence the output bits; they exist to be measured against the default.
+int expert_out_mode()
+{
+    const char* v = getenv("MOE_EP_EXPERT_OUT");
+    if (!v) return 0;
+    return v[0] == 'f' ? 1 : v[0] == 's' ? 2 : 0;
+}
+
 WsLayout ws_layout(const moe_ep_config& c)
 {
     WsLayout L{};
@@ -101,7 +117,7 @@ WsLayout ws_layout(const moe_ep_config& c)
     // the grouped copy of the token rows exists only when the gate/up projection cannot gather them
     // itself: switched off, or a chunk of 4 GB and more (its lanes hold 32-bit byte offsets)
     const bool need_xp = !fused_gather_enabled() || T * M * 2 >= ((size_t)1 << 32);
-    L.xp = take(need_xp ? A * M * 2 : 0); L.h = take(A * H * 2); L.y = take(A * M * 2);
+    L.xp = take(need_xp ? A * M * 2 : 0); L.h = take(A * H * 2); L.y = take(A * M * (expert_out_mode() == 1 ? 4 : 2));
     L.hs = take(c.n_shared > 0 ? T * (size_t)c.n_shared * (size_t)c.shared_inter * 2 : 0);
     L.total = o;
     return L;
@@ -133,6 +149,10 @@ void read_knobs(moe_ep_ctx* ctx)
     // tile-shape overrides for tuning (indices into the variant table of grouped_gemm.hip)
     if (const char* v = getenv("MOE_EP_GEMM_VARIANT")) ctx->gemm_variant = atoi(v);
     if (const char* v = getenv("MOE_EP_SHARED_VARIANT")) ctx->shared_variant = atoi(v);
+    if (const char* v = getenv("MOE_EP_UP_VARIANT")) ctx->up_variant = atoi(v);
+    if (const char* v = getenv("MOE_EP_DOWN_VARIANT")) ctx->down_variant = atoi(v);
+    if (const char* v = getenv("MOE_EP_UP_UNITS")) ctx->up_units = atoi(v);
+    if (const char* v = getenv("MOE_EP_DOWN_UNITS")) ctx->down_units = atoi(v);
     // workgroups of a copy kernel: ~128 KB in flight fills the host link; more only queues up in the
     // memory fabric in front of the compute kernels
     if (const char* v = getenv("MOE_EP_LINK_GRID")) ctx->link_grid = atoi(v) > 0 ? atoi(v) : 8;
@@ -144,6 +164,7 @@ void read_knobs(moe_ep_ctx* ctx)
         ctx->memcpy_out = v[0] == '1' || v[0] == 'o';
     }
     ctx->fused_gather = fused_gather_enabled();
+    ctx->y_mode = expert_out_mode();
     // MOE_EP_CHECK_POINTERS=0 skips the per-forward pointer queries (a few microseconds of host time)
     if (const char* v = getenv("MOE_EP_CHECK_POINTERS")) ctx->check_spans = atoi(v) != 0;
 }
@@ -201,27 +222,46 @@ const char* check_span(const void* p, size_t bytes, bool want_host, const void**
     return nullptr;
 }
 
-// Tile shape of a routed projection for a chunk of Tn tokens: 128-row tiles (variant 1) or 160-row
-// tiles (variant 11).  The routed GEMMs run at the rate their workgroups can load operands, and a
-// tile of BM token rows and 256 weight rows loads BM + 256 rows per K step whatever part of it is
-// padding; measured, a 160-row tile takes 1.15 times as long as a 128-row tile for 1.25 times the
-// rows.  A launch lasts as many tiles as its busiest workgroup works through, so the shapes are
-// compared by rounds * time per tile: rounds = expected tiles of all experts and column tiles over
-// the n_cu workgroups, rounded up, with an expert's row count taken as normal around the balanced
-// share Tn * k / E of Sec. 3.1 with a Poisson spread (the host never learns the real counts).
-int routed_variant(int Tn, int k, int E, int El, int col_tiles, int n_cu)
+// Tile shape of a routed projection for a chunk of Tn tokens.  Row tiles are cut to fit each expert
+// (units of unit_rows rows, at most max_units per tile, equal heights), so a shape is judged by how
+// many tiles the experts need with it and what a tile of it costs.  A launch lasts as many tiles as
+// its busiest workgroup works through: cost = rounds * time per tile, rounds = expected tiles of
+// all experts and column tiles over the n_cu workgroups, rounded up, with an expert's row count
+// taken as normal around the balanced share Tn * k / E of Sec. 3.1 with a Poisson spread (the host
+// never learns the real counts).  Time per tile, relative to the 128-row shape, is a measurement
+// (MI355X, DeepSeek-V2-shaped share, both projections; profiles/routed_tile_times_dsv2_eg.txt): the
+// launches run at a matrix-instruction rate the package power limit sets, so a tile costs roughly
+// what its rows cost, plus what loading its 256 weight rows costs.
+struct RoutedShape { int variant, unit_rows, max_units; double rel_long_k, rel_short_k; };
+constexpr RoutedShape kRoutedShapes[] = {
+    {1, 64, 2, 1.000, 1.000},    // 128 x 256, 2 x 2 wavefronts, three ring slots
+    {11, 32, 5, 1.147, 1.135},   // 160 x 256, 1 x 4, three slots
+    {13, 32, 7, 1.744, 1.709},   // 224 x 256, 1 x 4, two slots
+    {14, 32, 8, 1.794, 1.764},   // 256 x 256, 1 x 4, two slots
+};
+const RoutedShape* routed_shape(int Tn, int k, int E, int El, int col_tiles, int K, int n_cu)
 {
     const double mean = (double)Tn * k / E, sd = sqrt(mean > 1.0 ? mean : 1.0);
-    auto launch_time = [&](int bm, double tile_time) {
-        // E[ceil(rows / bm)] = sum over j >= 0 of P(rows > j * bm): 1 for every j * bm more than 6 sd
-        // below the mean, 0 beyond 6 sd above it, the normal tail in between
+    const RoutedShape* best = &kRoutedShapes[0];
+    double best_cost = 0.0;
+    for (const RoutedShape& sh : kRoutedShapes) {
+        // E[tiles] = sum over j >= 0 of P(rows > j * tile_rows): a group of n rows gets
+        // ceil(ceil(n / unit_rows) / max_units) tiles, i.e. one more tile each time n passes a
+        // multiple of unit_rows * max_units; 1 for every multiple more than 6 sd below the mean,
+        // 0 beyond 6 sd above it, the normal tail in between
+        const double bm = (double)sh.unit_rows * sh.max_units;
         const double lo = (mean - 6.0 * sd) / bm;
         const long long j0 = lo > 0.0 ? (long long)lo : 0;
         double tiles = (double)j0;
-        for (long long j = j0; j * (double)bm < mean + 6.0 * sd; ++j) tiles += 0.5 * erfc((j * (double)bm - mean) / (sd * 1.4142135623730951));
-        return ceil(tiles * El * col_tiles / n_cu - 0.02) * tile_time;
-    };
-    return launch_time(160, 1.15) < launch_time(128, 1.0) ? 11 : 1;
+        for (long long j = j0; j * bm < mean + 6.0 * sd; ++j) tiles += 0.5 * erfc((j * bm - mean) / (sd * 1.4142135623730951));
+        const double cost = ceil(tiles * El * col_tiles / n_cu - 0.02) * (K >= 2048 ? sh.rel_long_k : sh.rel_short_k);
+        if (&sh == &kRoutedShapes[0] || cost < best_cost) { best = &sh; best_cost = cost; }
+    }
+    return best;
+}
+int routed_variant(int Tn, int k, int E, int El, int col_tiles, int K, int n_cu)
+{
+    return routed_shape(Tn, k, E, El, col_tiles, K, n_cu)->variant;
 }
 
 hipEvent_t prof_event(moe_ep_ctx* ctx)
@@ -344,6 +384,7 @@ int moe_ep_create(const moe_ep_config* cfg, moe_ep_ctx** out_ctx)
     char* slab = nullptr;
     if (hipMalloc(reinterpret_cast<void**>(&slab), L.total) != hipSuccess) { delete ctx; return MOE_EP_ENOMEM; }
     bind_workspaces(ctx, slab, L);  // L.tokens == 0: d_tokens is the slab base, freed in destroy
+    ctx->last_variants.assign((size_t)cfg->max_chunks, {-1, -1});
 
     // the chunk events order GPU work against GPU work only, so they skip the system-scope cache
     // write-back a default event record implies (it stalled the other streams' kernels)
@@ -580,7 +621,9 @@ int forward_impl(moe_ep_ctx* ctx, const void* tokens, const float* gate_logits, 
     auto enqueue_inbound = [&](int cidx) -> int {
         int t0, Tn;
         chunk_range(T, r_1, r_2, cidx, &t0, &Tn);
-        const int sp_in = prof_begin(ctx, prof && Tn > 0, ST_COPY_IN, s_in);
+        // no timing events around the runtime's own copies (MOE_EP_LINK_MEMCPY): the one profiled run
+        // that had them ended in a crash inside the profiler's exit handler; the copy kernels are timed
+        const int sp_in = prof_begin(ctx, prof && Tn > 0 && !ctx->memcpy_in, ST_COPY_IN, s_in);
         if (Tn > 0) {
             HIP_TRY(ctx, link_copy(static_cast<char*>(ctx->d_tokens) + (size_t)t0 * M * 2,
                                      h_tokens + (size_t)t0 * M * 2, (size_t)Tn * M * 2, link_grid, s_in));
@@ -653,8 +696,11 @@ int forward_impl(moe_ep_ctx* ctx, const void* tokens, const float* gate_logits, 
         const int nblk = (Tn + kTokPerBlock - 1) / kTokPerBlock;
         // tile shapes of the two routed projections: N = H in tiles of 128 activation columns, N = M in
         // tiles of 256 columns
-        const int v_up = ctx->gemm_variant >= 0 ? ctx->gemm_variant : routed_variant(Tn, k, E, El, (H + 127) / 128, n_cu);
-        const int v_down = ctx->gemm_variant >= 0 ? ctx->gemm_variant : routed_variant(Tn, k, E, El, (M + 255) / 256, n_cu);
+        int v_up = ctx->gemm_variant >= 0 ? ctx->gemm_variant : routed_variant(Tn, k, E, El, (H + 127) / 128, M, n_cu);
+        int v_down = ctx->gemm_variant >= 0 ? ctx->gemm_variant : routed_variant(Tn, k, E, El, (M + 255) / 256, H, n_cu);
+        if (ctx->up_variant >= 0) v_up = ctx->up_variant;
+        if (ctx->down_variant >= 0) v_down = ctx->down_variant;
+        if (cidx < (int)ctx->last_variants.size()) ctx->last_variants[cidx] = {v_up, v_down};
         int32_t* idx = ctx->idx + (size_t)t0 * k;
         float* w = ctx->w + (size_t)t0 * k;
         int32_t* pos = ctx->pos + (size_t)t0 * k;
@@ -686,6 +732,7 @@ int forward_impl(moe_ep_ctx* ctx, const void* tokens, const float* gate_logits, 
         g1.G = El; g1.dense_rows = 0; g1.K = M; g1.N = H; g1.lda = M; g1.ldc = H; g1.ldw = M;
         g1.w_group_stride = (long long)3 * H * M; g1.w_up_offset = (long long)H * M;
         g1.kseg_len = M; g1.w_kseg_stride = 0; g1.c_group_col_stride = 0;
+        g1.max_units = ctx->up_units;
         if (fused) {  // the projection reads the token rows through the row -> assignment map
             g1.A = tok_dev + (size_t)t0 * M; g1.a_row_map = perm; g1.a_row_div = k; g1.a_src_rows = Tn;
         }
@@ -698,6 +745,8 @@ int forward_impl(moe_ep_ctx* ctx, const void* tokens, const float* gate_logits, 
         g2.G = El; g2.dense_rows = 0; g2.K = H; g2.N = M; g2.lda = H; g2.ldc = M; g2.ldw = H;
         g2.w_group_stride = (long long)3 * H * M; g2.w_up_offset = 0;
         g2.kseg_len = H; g2.w_kseg_stride = 0; g2.c_group_col_stride = 0;
+        g2.max_units = ctx->down_units;
+        g2.epi = ctx->y_mode; g2.row_weight = w; g2.row_assignment = perm;
         sp = prof_begin(ctx, prof, ST_GEMM2, s_comp);
         HIP_TRY(ctx, launch_grouped_gemm(g2, false, v_down, n_cu, a_max, s_comp));
         prof_end(ctx, sp, s_comp);
@@ -710,13 +759,13 @@ int forward_impl(moe_ep_ctx* ctx, const void* tokens, const float* gate_logits, 
         if (dep && Ns > 0) HIP_TRY(ctx, hipStreamWaitEvent(s_comp, ctx->ev_shared[cidx / r_2], 0));
 
         sp = prof_begin(ctx, prof, ST_COMBINE, s_comp);
-        HIP_TRY(ctx, launch_combine(ctx->y, pos, w, Tn, k, M, Ns > 0, out_dev + (size_t)t0 * M, bw_grid, s_comp));
+        HIP_TRY(ctx, launch_combine(ctx->y, pos, w, Tn, k, M, Ns > 0, ctx->y_mode, out_dev + (size_t)t0 * M, bw_grid, s_comp));
         prof_end(ctx, sp, s_comp);
 
         if (pinned) {
             HIP_TRY(ctx, hipEventRecord(ctx->ev_comp[cidx], s_comp));
             HIP_TRY(ctx, hipStreamWaitEvent(s_out, ctx->ev_comp[cidx], 0));
-            const int sp_out = prof_begin(ctx, prof, ST_COPY_OUT, s_out);
+            const int sp_out = prof_begin(ctx, prof && !ctx->memcpy_out, ST_COPY_OUT, s_out);
             HIP_TRY(ctx, link_copy(h_out + (size_t)t0 * M * 2,
                                    reinterpret_cast<const char*>(out_dev) + (size_t)t0 * M * 2,
                                    (size_t)Tn * M * 2, link_grid, s_out));
@@ -757,7 +806,31 @@ int32_t moe_ep_routed_tile_rows(const moe_ep_config* cfg, int32_t n_tokens, int3
 {
     if (moe_ep_validate_config(cfg, nullptr) != MOE_EP_OK || n_tokens < 0 || top_k < 1 || n_cu < 1) return MOE_EP_EINVAL;
     const int col_tiles = down ? (cfg->hidden + 255) / 256 : (cfg->inter + 127) / 128;
-    return routed_variant(n_tokens, top_k, cfg->n_experts, cfg->n_local, col_tiles, n_cu) == 11 ? 160 : 128;
+    const RoutedShape* sh = routed_shape(n_tokens, top_k, cfg->n_experts, cfg->n_local, col_tiles,
+                                         down ? cfg->inter : cfg->hidden, n_cu);
+    return sh->unit_rows * sh->max_units;
+}
+
+int moe_ep_last_tile_shape(const moe_ep_ctx* ctx, int32_t chunk, int32_t stage, int32_t* rows, int32_t* cols,
+                           int32_t* k_step, int32_t* ring_slots, int32_t* waves_m, int32_t* waves_n)
+{
+    if (!ctx || stage < ST_GEMM1 || stage > ST_SGEMM2) return MOE_EP_EINVAL;
+    if (ctx->last_T < 0) return MOE_EP_ESTATE;
+    const bool shared = stage == ST_SGEMM1 || stage == ST_SGEMM2, up = stage == ST_GEMM1 || stage == ST_SGEMM1;
+    if (shared && ctx->cfg.n_shared == 0) return MOE_EP_ESTATE;
+    if (!shared && (chunk < 0 || chunk >= ctx->last_r || chunk >= (int)ctx->last_variants.size())) return MOE_EP_EINVAL;
+    const moe_ep_config& c = ctx->cfg;
+    const int variant = shared ? ctx->shared_variant : (up ? ctx->last_variants[chunk].up : ctx->last_variants[chunk].down);
+    const int K = shared ? (up ? c.hidden : c.n_shared * c.shared_inter) : (up ? c.hidden : c.inter);
+    int v[6];
+    if (!grouped_gemm_variant_shape(variant, K, !shared, shared ? 1 : c.n_local, v)) return MOE_EP_ESTATE;
+    if (rows) *rows = v[0];
+    if (cols) *cols = v[1];
+    if (k_step) *k_step = v[2];
+    if (ring_slots) *ring_slots = v[3];
+    if (waves_m) *waves_m = v[4];
+    if (waves_n) *waves_n = v[5];
+    return MOE_EP_OK;
 }
 
 int moe_ep_forward(moe_ep_ctx* ctx, const void* tokens, const float* gate_logits,

@@ -28,6 +28,11 @@ def test_library_exports_every_declared_symbol():
     for n in sorted(names):
         assert hasattr(lib, n), f"{n} declared in moe_ep.h but not exported"
     assert lib.moe_ep_version().decode().count(".") == 1
+    assert not hasattr(lib, "moe_ep_probe_device")   # the benchmark's aid is not in the layer's library
+    probe_header = re.sub(r"/\*.*?\*/", "", open(os.path.join(ROOT, "include", "moe_ep_probe.h")).read(), flags=re.S)
+    probe_names = set(re.findall(r"\b(moe_ep_[a-z_]+)\s*\(", probe_header))
+    assert probe_names == {"moe_ep_probe_device"}
+    assert hasattr(pkg.load_probe_library(), "moe_ep_probe_device")
 
 
 def test_config_struct_matches_header():
@@ -158,14 +163,16 @@ def test_tensor_marshalling_checks():
 
 
 def test_row_tile_of_the_routed_projections():
-    """The tile height follows from expected rounds of tiles x time per tile (a 160-row tile counts 1.15
-    128-row tiles): worked by hand for the benchmark shapes on 256 compute units."""
+    """The tallest row tile follows from expected rounds of tiles x measured time per tile of each shape
+    (128 / 160 / 224 / 256 rows: 1 / 1.15 / 1.74 / 1.79 for a long K): worked by hand for the benchmark
+    shapes on 256 compute units."""
     from paper_2512_21487_amd import routed_tile_rows
     dsv2_eg = _good(hidden=5120, inter=1536, n_experts=160, n_local=20, shared_inter=1536, n_shared=2,
                     max_tokens=16384, max_top_k=6)
-    # 614 rows per expert: 5.15 tiles of 128 or 4.15 of 160; gate/up 12 column tiles: 5 rounds against 4
+    # 614 rows per expert: 5.15 tiles of 128, 4.15 of 160, 3.01 of 224, 3 of 256; gate/up 12 column
+    # tiles: 5, 4, 3, 3 rounds = 5.0, 4.59, 5.23, 5.38 in units of a 128-row tile
     assert routed_tile_rows(dsv2_eg, 16384, 6, False) == 160
-    # down, 20 column tiles: 9 rounds against 7
+    # down, 20 column tiles: 9, 7, 5, 5 rounds = 9.0, 7.95, 8.55, 8.82
     assert routed_tile_rows(dsv2_eg, 16384, 6, True) == 160
     decode = _good(hidden=4096, inter=1536, n_experts=128, n_local=16, n_shared=0, shared_inter=0,
                    max_tokens=4096, max_top_k=8)
@@ -173,10 +180,10 @@ def test_row_tile_of_the_routed_projections():
     assert routed_tile_rows(decode, 4096, 8, False) == 128
     # down, 16 column tiles: 640 tiles = 3 rounds against 512 = 2 rounds
     assert routed_tile_rows(decode, 4096, 8, True) == 160
-    for T in (1, 256, 1024):   # one tile per expert either way: the smaller one
+    for T in (1, 256, 1024):   # one tile per expert with every shape: the cheapest one
         assert routed_tile_rows(decode, T, 8, False) == routed_tile_rows(decode, T, 8, True) == 128
-    assert routed_tile_rows(decode, 0, 8, False) == 128
-    with pytest.raises(ValueError):
-        routed_tile_rows(_good(hidden=100), 16, 2, False)
-    with pytest.raises(ValueError):
-        routed_tile_rows(decode, 16, 0, False)
+    # 180 +- 13 rows per expert, 8 experts x 32 column tiles = 256 columns of tiles: one 224-row tile each
+    # is one round (1.71); two tiles of 128 or 160 rows are two rounds (2.0, 2.27)
+    few = _good(hidden=8192, inter=1536, n_experts=8, n_local=8, n_shared=0, shared_inter=0, max_tokens=1440,
+                max_top_k=1)
+    assert routed_tile_rows(few, 1440, 1, True) == 224

@@ -171,3 +171,87 @@ def test_seeded_random_layers_match_the_oracle(seed):
     out_dep = g.run_forward_dep(ctx, wl, d, r_1, r_2, int(rng.integers(0, 2)), float(rng.choice([0.0, 20.0])))
     assert np.array_equal(out_dep, out)
     ctx.destroy()
+
+
+@pytest.mark.parametrize("dep", [False, True])
+def test_layers_back_to_back_give_the_bits_of_lone_forwards(dep):
+    """Steady state over several layers (Sec. 4.2, the per-layer offset of the multi-layer timeline): L
+    layers with their own weights and gate scores are enqueued back to back on one stream, layer l
+    reading what layer l - 1 wrote, with no host synchronisation in between and one context whose
+    workspaces every layer reuses.  Each layer's output must be the bits of a lone, synchronised forward
+    on the same input; the measured period per layer is held against the schedule model's per-layer
+    term max(G, r_1 F) fed with the task times the timeline shows."""
+    import time
+    import paper_2512_21487_amd as pkg
+    g = _gpu()
+    wl = _wl()
+    L, r_1, r_2, attn_us = 4, 2, 2, 40.0
+    layers = [make_inputs(wl, seed=70 + l) for l in range(L)]
+    ctx = g.make_ctx(wl, max_chunks=r_1 * r_2)
+    d = [g.DeviceInputs(wl, inp) for inp in layers]
+    x0 = d[0].tokens.clone()
+
+    def run_layer(l, x, out):
+        if dep:
+            ctx.forward_dep(x, d[l].logits, d[l].routed, d[l].shared, wl.top_k, r_1, r_2, ASAS, attn_us,
+                            n_tokens=wl.n_tokens, out=out)
+        else:
+            ctx.forward(x, d[l].logits, d[l].routed, d[l].shared, wl.top_k, r_2, 1, n_tokens=wl.n_tokens, out=out)
+
+    # lone forwards, one at a time
+    lone, x = [], x0
+    for l in range(L):
+        out = torch.zeros_like(x0)
+        run_layer(l, x, out)
+        torch.cuda.synchronize()
+        lone.append(out)
+        x = out
+    # the same chain enqueued at once
+    outs = [torch.zeros_like(x0) for _ in range(L)]
+
+    def chain():
+        x = x0
+        for l in range(L):
+            run_layer(l, x, outs[l])
+            x = outs[l]
+
+    chain()
+    torch.cuda.synchronize()
+    for l in range(L):
+        assert torch.equal(outs[l], lone[l]), f"layer {l} of the chain differs from its lone forward"
+    assert any(bool(o.any()) for o in outs)
+    # period per layer against the model: task times from the measured timeline of one lone layer
+    for _ in range(3):
+        chain()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(10):
+        chain()
+    torch.cuda.synchronize()
+    period_ms = (time.perf_counter() - t0) / (10 * L) * 1e3
+    ctx.set_profiling(1)
+    run_layer(0, x0, outs[0])
+    by = {}
+    for n, _, b, e in ctx.get_timeline():
+        by.setdefault(n, []).append((b, e))
+    ctx.get_stage_ms()
+    ctx.set_profiling(0)
+    mean = lambda xs: float(np.mean(xs)) if len(xs) else 0.0
+    t_a = mean([e - b for b, e in by.get("attention", [])])
+    t_s = mean([e2 - b1 for (b1, _), (_, e2) in zip(by["shared_gate_up_gemm"], by["shared_down_gemm"])])
+    t_e = mean([e2 - b1 for (b1, _), (_, e2) in zip(by["router"], by["routed_down_gemm"])]) + \
+        mean([e - b for b, e in by["aggregation"]])
+    lone_ms = by["forward"][0][1] - by["forward"][0][0]
+    mod = pkg.DepModels(t_a, 0.0, t_s, 0.0, t_e, 0.0, 0.0, 0.0)
+    prob = pkg.DepProblem(ag=1, n_experts=wl.n_experts, top_k=wl.top_k, seq_len=1, n_layers=L)
+    rr1 = r_1 if dep else 1
+    span_L = pkg.dep_makespan(mod, prob, 1, rr1, r_2)
+    prob1 = pkg.DepProblem(ag=1, n_experts=wl.n_experts, top_k=wl.top_k, seq_len=1, n_layers=1)
+    per_layer_model = (span_L - pkg.dep_makespan(mod, prob1, 1, rr1, r_2)) / (L - 1)   # (T-1) max(G, r_1 F) / (T-1)
+    print(f"       dep={dep}: period {period_ms:.4f} ms per layer, lone layer {lone_ms:.4f} ms, "
+          f"model per-layer term {per_layer_model:.4f} ms (t_a {t_a:.4f} t_s {t_s:.4f} t_e {t_e:.4f})", flush=True)
+    # layers depend on each other, so the chain cannot beat the model's per-layer term; it also must
+    # not cost more than lone layers do (no hidden synchronisation, no re-allocation)
+    assert period_ms >= 0.5 * per_layer_model
+    assert period_ms <= 1.25 * lone_ms + 0.05
+    ctx.destroy()

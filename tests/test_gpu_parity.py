@@ -69,6 +69,28 @@ def _full_parity(wl, seed=0, r=1, order=0, mutate=None):
     return out, ref
 
 
+class _env:
+    """Environment knobs of the library (read at moe_ep_create) set for a with-block."""
+
+    def __init__(self, **kv):
+        self.kv = kv
+
+    def __enter__(self):
+        self.old = {k: os.environ.get(k) for k in self.kv}
+        for k, v in self.kv.items():
+            if v is None:
+                os.environ.pop(k, None)
+            else:
+                os.environ[k] = str(v)
+
+    def __exit__(self, *exc):
+        for k, v in self.old.items():
+            if v is None:
+                os.environ.pop(k, None)
+            else:
+                os.environ[k] = v
+
+
 # ------------------------------------------------------------------ element by element
 def test_tiny_config_matches_oracle():
     _full_parity(CONFIGS["tiny"])
@@ -170,11 +192,11 @@ def test_maximum_expert_count_and_top_k():
     _full_parity(wl, seed=28)
 
 
-@pytest.mark.parametrize("variant", [0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12])
+@pytest.mark.parametrize("variant", [0, 1, 2, 6, 8, 9, 11, 12, 13, 14])
 @pytest.mark.parametrize("hidden", [64, 128, 192, 320])
 def test_every_tile_variant_matches_oracle(variant, hidden):
-    """Each instantiated tile shape / ring depth of the grouped GEMM (10: tall and short tiles in one
-    launch; 11, 12: 160-row tiles held by 1 x 4 and 1 x 2 wavefronts), for the routed and the shared experts, on K extents of one, two, three and five 64-wide
+    """Each instantiated tile shape / ring depth of the grouped GEMM (11, 12: 160-row tiles held by 1 x 4
+    and 1 x 2 wavefronts; 13, 14: 224- and 256-row tiles held by 1 x 4), for the routed and the shared experts, on K extents of one, two, three and five 64-wide
     steps (shortest pipelines, fallbacks to the 32-wide variants included) with ragged row and column
     tails."""
     wl = tiny_workload(name=f"v{variant}_M{hidden}", n_tokens=333, hidden=hidden, inter=320, n_experts=6,
@@ -219,7 +241,7 @@ def test_tile_shape_does_not_change_a_bit():
     old = os.environ.get("MOE_EP_GEMM_VARIANT")
     outs = {}
     try:
-        for variant in (None, 0, 1, 2, 5, 10, 11, 12):
+        for variant in (None, 0, 1, 2, 6, 11, 12, 13, 14):
             if variant is None:
                 os.environ.pop("MOE_EP_GEMM_VARIANT", None)
             else:
@@ -237,29 +259,58 @@ def test_tile_shape_does_not_change_a_bit():
         assert np.array_equal(out, outs[None]), f"tile variant {variant} changed output bits"
 
 
-def test_tall_and_short_tiles_in_one_launch():
-    """Tile variant 10 on expert loads that need every case of its row split: experts with several
-    256-row tiles, tails longer than 128 rows (one more tall tile), tails of at most 128 rows (a
-    short tile) and an expert without tokens."""
-    wl = tiny_workload(name="two_shapes", n_tokens=1400, hidden=192, inter=320, n_experts=7, n_local=7,
-                       top_k=2, n_shared=1, shared_inter=192, zipf_s=1.0)
+@pytest.mark.parametrize("variant,units", [(14, 0), (14, 7), (14, 3), (14, 1), (2, 0), (2, 3), (2, 1), (13, 5), (11, 2),
+                                           (1, 1)])
+def test_row_tiles_cut_to_fit_the_experts(variant, units):
+    """Row tiles are cut per expert to equal heights in units of 32 rows per row of wavefronts, at most
+    `units` of them (0: as many as the variant holds): expert loads that are empty, one row, exact
+    multiples of a unit and of a full tile, one row more, and several tiles with a remainder must all
+    match the oracle, with 1 x 4 and with 2 x 2 wavefronts, and with the same bits as the default."""
+    g = _gpu()
+    wl = tiny_workload(name=f"cut_v{variant}_u{units}", n_tokens=2400, hidden=192, inter=320, n_experts=12, n_local=12,
+                       top_k=1, n_shared=0)
+    loads = [0, 1, 32, 33, 64, 65, 256, 257, 512, 700, 31, 0]      # rows of the 12 experts
+    loads[-1] = wl.n_tokens - sum(loads)
 
-    def no_tokens_for_expert_3(inp):
-        inp["gate_logits"][:, 3] = -1e9
+    def exact_loads(inp):
+        lg = np.full((wl.n_tokens, 12), -30.0, dtype=np.float32)
+        t = 0
+        for e, n in enumerate(loads):
+            lg[t:t + n, e] = 5.0
+            t += n
+        inp["gate_logits"][:] = lg[np.random.default_rng(7).permutation(wl.n_tokens)]
 
-    old = os.environ.get("MOE_EP_GEMM_VARIANT")
-    os.environ["MOE_EP_GEMM_VARIANT"] = "10"
-    try:
-        _, ref = _full_parity(wl, seed=41, mutate=no_tokens_for_expert_3)
-    finally:
-        if old is None:
-            os.environ.pop("MOE_EP_GEMM_VARIANT", None)
-        else:
-            os.environ["MOE_EP_GEMM_VARIANT"] = old
-    counts = ref["count"][0].tolist()
-    tails = [c % 256 for c in counts]
-    assert max(counts) >= 512 and min(counts) == 0
-    assert any(t > 128 for t in tails) and any(0 < t <= 128 for t in tails)
+    with _env(MOE_EP_GEMM_VARIANT=variant, MOE_EP_UP_UNITS=units or None, MOE_EP_DOWN_UNITS=units or None):
+        out, ref = _full_parity(wl, seed=41, mutate=exact_loads)
+    assert sorted(ref["count"][0].tolist()) == sorted(loads)
+    inp = make_inputs(wl, seed=41)
+    exact_loads(inp)
+    with _env(MOE_EP_GEMM_VARIANT=None, MOE_EP_UP_UNITS=None, MOE_EP_DOWN_UNITS=None):
+        ctx = g.make_ctx(wl)
+        base = g.run_forward(ctx, wl, g.DeviceInputs(wl, inp))
+        ctx.destroy()
+    assert np.array_equal(out, base)
+
+
+@pytest.mark.parametrize("mode", ["fp32", "scaled"])
+@pytest.mark.parametrize("variant", [None, 1, 14])
+def test_other_forms_of_the_expert_outputs_match_the_oracle(mode, variant):
+    """MOE_EP_EXPERT_OUT: the routed experts' outputs reach the aggregation as fp32, or as bf16 already
+    multiplied by the routing weight.  Both move a rounding point, so the bits differ from the default;
+    the oracle bar is the same, and chunking still changes nothing."""
+    g = _gpu()
+    wl = tiny_workload(name=f"y_{mode}", n_tokens=777, hidden=192, inter=320, n_experts=10, local_begin=2,
+                       n_local=6, top_k=3, n_shared=2, shared_inter=192)
+    with _env(MOE_EP_EXPERT_OUT=mode, MOE_EP_GEMM_VARIANT=variant):
+        out, ref = _full_parity(wl, seed=37, r=1)
+        out3, _ = _full_parity(wl, seed=37, r=3, order=1)
+    assert np.array_equal(out, out3)
+    if mode == "fp32":   # one rounding less: never further from the oracle than the default path
+        with _env(MOE_EP_EXPERT_OUT=None, MOE_EP_GEMM_VARIANT=variant):
+            base, _ = _full_parity(wl, seed=37, r=1)
+        e_new = np.abs(bf16_bits_to_f32(out).astype(np.float64) - ref["out"]).mean()
+        e_old = np.abs(bf16_bits_to_f32(base).astype(np.float64) - ref["out"]).mean()
+        assert e_new <= e_old
 
 
 def test_grouped_copy_of_token_rows_matches_too():
@@ -560,31 +611,6 @@ def test_device_probe_reports_plausible_rates():
 
 
 # ------------------------------------------------------------------ full-size configurations
-_ENV_KEYS = ("MOE_EP_GEMM_VARIANT", "MOE_EP_SHARED_VARIANT")
-
-
-class _env:
-    """Environment knobs of the library (read at moe_ep_create) set for a with-block."""
-
-    def __init__(self, **kv):
-        self.kv = kv
-
-    def __enter__(self):
-        self.old = {k: os.environ.get(k) for k in self.kv}
-        for k, v in self.kv.items():
-            if v is None:
-                os.environ.pop(k, None)
-            else:
-                os.environ[k] = str(v)
-
-    def __exit__(self, *exc):
-        for k, v in self.old.items():
-            if v is None:
-                os.environ.pop(k, None)
-            else:
-                os.environ[k] = v
-
-
 def _full_size_parity(name, variants, pinned=False, seed=0, tile_variants=()):
     """At the benchmark's sizes and in the launch configuration bench.py times: the whole layer is
     run once on the CPU oracle and EVERY output element is compared with it (so every expert's first
@@ -677,3 +703,23 @@ def test_qwen3_235b_expert_group_share_decode_pinned(name):
 def test_decode_share_other_seeds_keep_the_margin(seed):
     """The configuration with the least margin against the tolerance, on other draws of the inputs."""
     _full_size_parity("qwen3_235b_eg_4096", [(1, 0)], pinned=False, seed=seed)
+
+
+@pytest.mark.parametrize("name", ["qwen3_235b_eg_256", "qwen3_235b_eg_4096"])
+def test_chosen_chunk_count_is_as_fast_as_the_best_measured(name):
+    """r_chunks = 0 with task models fitted on this GPU (Sec. 4.1), including the second set for tasks
+    that run beside others: the r_2 the library picks must run within 5 % of the fastest r_2 of the
+    measured sweep (Sec. 4.2, "Determine r_2 and m_e")."""
+    g = _gpu()
+    import bench
+    wl = CONFIGS[name]
+    inp = make_inputs(wl)
+    ctx = g.make_ctx(wl, pinned=True, max_chunks=8)
+    d = g.DeviceInputs(wl, inp, pinned=True)
+    stream = torch.cuda.current_stream().cuda_stream
+    res = bench.fit_pipeline(ctx, d.tokens, d.logits, d.routed, d.shared, d.out, wl.n_tokens, wl.top_k, 0, stream)
+    print(f"       chosen r = {res['chosen_r']} (independent resources: {res['chosen_r_independent_resources']}), "
+          f"measured {res['measured_ms']}, predicted {res['predicted_ms']}", flush=True)
+    best = min(res["measured_ms"].values())
+    assert res["measured_ms"][str(res["chosen_r"])] <= 1.05 * best
+    ctx.destroy()

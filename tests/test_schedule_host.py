@@ -4,7 +4,7 @@ import numpy as np
 import pytest
 
 import paper_2512_21487_amd as pkg
-from oracle.pipeline_model import LinearModel, best_r, fit_linear, makespan
+from oracle.pipeline_model import LinearModel, best_r, best_r_overlap, fit_linear, makespan, makespan_overlap
 
 
 def _pm(mi, me, mo):
@@ -56,3 +56,26 @@ def test_choice_bad_arguments():
     assert lib.moe_ep_choose_chunks(pm, 10, 0) < 0
     assert lib.moe_ep_pipeline_makespan(pm, 10, 0) < 0
     assert pkg.choose_chunks(pm, 0, 8) == 1
+
+
+def test_overlap_models_match_oracle_brute_force():
+    """A model with the second set of coefficients (tasks beside other tasks): makespan and chosen r_2
+    against the oracle's two-set closed form and brute force, on random models whose second set is
+    slower, equal, or (for the search's sake) faster than the first."""
+    rng = np.random.default_rng(6)
+    for case in range(1500):
+        alone = tuple(LinearModel(float(rng.uniform(0.0, 0.5)), float(rng.uniform(1e-6, 1e-3))) for _ in range(3))
+        lo, hi = ((1.0, 2.5), (1.0, 1.0), (0.6, 1.4))[case % 3]
+        beside = tuple(LinearModel(m.alpha * float(rng.uniform(lo, hi)) + (1e-9 if case % 3 == 1 else 0.0),
+                                   m.beta * float(rng.uniform(lo, hi))) for m in alone)
+        T = int(rng.integers(1, 70000))
+        r_max = int(rng.choice([1, 2, 3, 8, 64]))
+        pm = pkg.PipelineModel(alone[0].alpha, alone[0].beta, alone[1].alpha, alone[1].beta, alone[2].alpha,
+                               alone[2].beta, beside[0].alpha, beside[0].beta, beside[1].alpha, beside[1].beta,
+                               beside[2].alpha, beside[2].beta)
+        for r in (1, 2, r_max):
+            assert pkg.pipeline_makespan(pm, T, r) == pytest.approx(makespan_overlap(r, T, alone, beside), rel=1e-13)
+        got, want = pkg.choose_chunks(pm, T, r_max), best_r_overlap(T, alone, beside, r_max)
+        if got != want:
+            assert makespan_overlap(got, T, alone, beside) == pytest.approx(makespan_overlap(want, T, alone, beside), rel=1e-12)
+        assert 1 <= got <= r_max
