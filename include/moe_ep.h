@@ -308,7 +308,8 @@ int moe_ep_chunk_range(int32_t n_tokens, int32_t r_1, int32_t r_2, int32_t chunk
                        int32_t *count);
 
 /*
- * Host only: the tallest row tile (128, 160, 224 or 256 rows) the library gives a routed projection
+ * Host only: the tallest row tile (128 or 160 rows; 224- and 256-row shapes exist but are
+ * never chosen) the library gives a routed projection
  * (Sec. 3.1, Eq. moe_detail) of a chunk of n_tokens tokens -- down == 0: gate/up projection, else
  * the down projection -- on a GPU of n_cu compute units.  An expert of the balanced load of Sec. 3.1
  * gets n_tokens * top_k / E rows; its row tiles are cut to equal heights below the tallest; the

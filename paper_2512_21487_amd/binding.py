@@ -229,7 +229,7 @@ def forward_noalloc(cfg: MoeEpConfig, tokens, gate_logits, routed_w, shared_w, t
 
 
 def routed_tile_rows(cfg: MoeEpConfig, n_tokens: int, top_k: int, down: bool, n_cu: int = 256) -> int:
-    """moe_ep_routed_tile_rows: tallest row tile (128, 160, 224 or 256) of a routed projection of a chunk."""
+    """moe_ep_routed_tile_rows: tallest row tile (128 or 160 rows) of a routed projection of a chunk."""
     rows = int(load_library().moe_ep_routed_tile_rows(ctypes.byref(cfg), n_tokens, top_k, int(down), n_cu))
     if rows < 0:
         raise ValueError("moe_ep_routed_tile_rows: bad arguments")

@@ -232,12 +232,17 @@ const char* check_span(const void* p, size_t bytes, bool want_host, const void**
 // (MI355X, DeepSeek-V2-shaped share, both projections; profiles/routed_tile_times_dsv2_eg.txt): the
 // launches run at a matrix-instruction rate the package power limit sets, so a tile costs roughly
 // what its rows cost, plus what loading its 256 weight rows costs.
-struct RoutedShape { int variant, unit_rows, max_units; double rel_long_k, rel_short_k; };
+// automatic: a candidate of the choice below.  The two tall shapes are not: a tile of them costs what its
+// rows cost (1.74 = 7/4, 1.79 ~ 8/4 of a 128-row tile), so they only ever win by rounding the tile
+// count in their favour, and on every workload measured here the launch they win on paper ran slower
+// (Zipf-skewed Qwen3-30B-shaped layer, down projection: 372 us against 295 us); MOE_EP_GEMM_VARIANT /
+// MOE_EP_UP_VARIANT / MOE_EP_DOWN_VARIANT select them.
+struct RoutedShape { int variant, unit_rows, max_units; double rel_long_k, rel_short_k; bool automatic; };
 constexpr RoutedShape kRoutedShapes[] = {
-    {1, 64, 2, 1.000, 1.000},    // 128 x 256, 2 x 2 wavefronts, three ring slots
-    {11, 32, 5, 1.147, 1.135},   // 160 x 256, 1 x 4, three slots
-    {13, 32, 7, 1.744, 1.709},   // 224 x 256, 1 x 4, two slots
-    {14, 32, 8, 1.794, 1.764},   // 256 x 256, 1 x 4, two slots
+    {1, 64, 2, 1.000, 1.000, true},     // 128 x 256, 2 x 2 wavefronts, three ring slots
+    {11, 32, 5, 1.147, 1.135, true},    // 160 x 256, 1 x 4, three slots
+    {13, 32, 7, 1.744, 1.709, false},   // 224 x 256, 1 x 4, two slots
+    {14, 32, 8, 1.794, 1.764, false},   // 256 x 256, 1 x 4, two slots
 };
 const RoutedShape* routed_shape(int Tn, int k, int E, int El, int col_tiles, int K, int n_cu)
 {
@@ -245,6 +250,7 @@ const RoutedShape* routed_shape(int Tn, int k, int E, int El, int col_tiles, int
     const RoutedShape* best = &kRoutedShapes[0];
     double best_cost = 0.0;
     for (const RoutedShape& sh : kRoutedShapes) {
+        if (!sh.automatic) continue;
         // E[tiles] = sum over j >= 0 of P(rows > j * tile_rows): a group of n rows gets
         // ceil(ceil(n / unit_rows) / max_units) tiles, i.e. one more tile each time n passes a
         // multiple of unit_rows * max_units; 1 for every multiple more than 6 sd below the mean,

@@ -183,7 +183,8 @@ def test_row_tile_of_the_routed_projections():
     for T in (1, 256, 1024):   # one tile per expert with every shape: the cheapest one
         assert routed_tile_rows(decode, T, 8, False) == routed_tile_rows(decode, T, 8, True) == 128
     # 180 +- 13 rows per expert, 8 experts x 32 column tiles = 256 columns of tiles: one 224-row tile each
-    # is one round (1.71); two tiles of 128 or 160 rows are two rounds (2.0, 2.27)
+    # would be one round (1.71) against two rounds of 128-row tiles (2.0), but the tall shapes are not
+    # candidates (measured slower wherever they win on paper)
     few = _good(hidden=8192, inter=1536, n_experts=8, n_local=8, n_shared=0, shared_inter=0, max_tokens=1440,
                 max_top_k=1)
-    assert routed_tile_rows(few, 1440, 1, True) == 224
+    assert routed_tile_rows(few, 1440, 1, True) == 128
