@@ -51,9 +51,13 @@ typedef enum {
 /* Where tokens / gate_logits / out live.  Weights are always in device memory. */
 typedef enum {
     MOE_EP_IO_DEVICE = 0,     /* device pointers; no copies are made                        */
-    MOE_EP_IO_PINNED_HOST = 1 /* pinned host pointers; each chunk is copied in and out on
-                                 its own streams, standing in for the A2E / E2A transfers
-                                 (Sec. 2.2; Eq. a2e_detail)                                 */
+    MOE_EP_IO_PINNED_HOST = 1 /* pinned host pointers; each chunk crosses the host link in and
+                                 out, standing in for the A2E / E2A transfers (Sec. 2.2; Eq.
+                                 a2e_detail): inbound as a copy on a stream of the context,
+                                 outbound as the aggregation's own stores into the host buffer
+                                 (moe_ep_forward; the environment variable MOE_EP_FUSED_OUT=0
+                                 makes it a copy on a second stream) or as such a copy
+                                 (moe_ep_forward_dep)                                       */
 } moe_ep_io;
 
 typedef struct {
@@ -112,7 +116,7 @@ int moe_ep_create(const moe_ep_config *cfg, moe_ep_ctx **out_ctx);
  *               projections and each expert's output are rounded to bf16 once.
  *   stream      hipStream_t (NULL = the default stream).  The call only enqueues work: every
  *               kernel runs on `stream`, after what is already there; in pinned-host mode the
- *               chunk copies run on two streams of the context and `stream` is made to wait
+ *               chunk copies run on streams of the context and `stream` is made to wait
  *               for the last of them.  Buffers must stay valid until `stream` reaches that point.
  *               In device mode the call allocates nothing, sets no memory and never waits on the
  *               host, so it may be recorded into a HIP graph (stream capture) and replayed.

@@ -27,7 +27,7 @@ __device__ __forceinline__ void fma8f(float* acc, float ws, const f32x4_t& lo, c
 template <int YMODE>
 __global__ __launch_bounds__(256) void combine_kernel(
     const uint4* __restrict__ y, const int32_t* __restrict__ pos, const float* __restrict__ w, int Tn,
-    int k, int M8, bool accumulate, uint4* out)
+    int k, int M8, bool accumulate, bool all_rows, const uint4* out_src, uint4* out)
 {
     const int lane = threadIdx.x & 63;
     const int gw = (blockIdx.x * 256 + threadIdx.x) >> 6, nw = gridDim.x * 4;
@@ -36,7 +36,9 @@ __global__ __launch_bounds__(256) void combine_kernel(
         const float my_w = (lane < k) ? w[(size_t)t * k + lane] : 0.f;
         // accumulate: the row already holds the shared experts' output; a token with no kept
         // slot keeps it as it is
-        if (accumulate && __ballot(my_pos >= 0) == 0ull) continue;
+        // (all_rows: the rows are written somewhere else than they are read from -- straight to the
+        // caller's host buffer -- so a row that only carries the shared experts' output moves too)
+        if (accumulate && !all_rows && __ballot(my_pos >= 0) == 0ull) continue;
         // the column loop runs the same number of times in every lane: the slot broadcasts below
         // read lanes 0..k-1, which must not have left the loop when a row is shorter than a trip
         for (int c0 = 0; c0 < M8; c0 += 128) {
@@ -66,14 +68,14 @@ __global__ __launch_bounds__(256) void combine_kernel(
                 }
             }
             if (in_a) {
-                if (accumulate) fma8(acc_a, 1.0f, out[(size_t)t * M8 + ca]);
+                if (accumulate) fma8(acc_a, 1.0f, out_src[(size_t)t * M8 + ca]);
                 uint4 o;
                 o.x = pack_bf16x2(acc_a[0], acc_a[1]); o.y = pack_bf16x2(acc_a[2], acc_a[3]);
                 o.z = pack_bf16x2(acc_a[4], acc_a[5]); o.w = pack_bf16x2(acc_a[6], acc_a[7]);
                 out[(size_t)t * M8 + ca] = o;
             }
             if (in_b) {
-                if (accumulate) fma8(acc_b, 1.0f, out[(size_t)t * M8 + cb]);
+                if (accumulate) fma8(acc_b, 1.0f, out_src[(size_t)t * M8 + cb]);
                 uint4 o;
                 o.x = pack_bf16x2(acc_b[0], acc_b[1]); o.y = pack_bf16x2(acc_b[2], acc_b[3]);
                 o.z = pack_bf16x2(acc_b[4], acc_b[5]); o.w = pack_bf16x2(acc_b[6], acc_b[7]);
@@ -84,15 +86,17 @@ __global__ __launch_bounds__(256) void combine_kernel(
 }
 
 hipError_t launch_combine(const void* y, const int32_t* pos, const float* w, int Tn, int k, int M,
-                          bool accumulate, int y_mode, void* out, int grid, hipStream_t s)
+                          bool accumulate, int y_mode, const void* out_src, void* out, int grid, hipStream_t s)
 {
     if (Tn <= 0) return hipSuccess;
     if (y_mode < 0 || y_mode > 2) return hipErrorInvalidValue;
     auto* yy = static_cast<const uint4*>(y);
     auto* oo = static_cast<uint4*>(out);
-    if (y_mode == 0) hipLaunchKernelGGL(combine_kernel<0>, dim3(grid), dim3(256), 0, s, yy, pos, w, Tn, k, M / 8, accumulate, oo);
-    else if (y_mode == 1) hipLaunchKernelGGL(combine_kernel<1>, dim3(grid), dim3(256), 0, s, yy, pos, w, Tn, k, M / 8, accumulate, oo);
-    else hipLaunchKernelGGL(combine_kernel<2>, dim3(grid), dim3(256), 0, s, yy, pos, w, Tn, k, M / 8, accumulate, oo);
+    auto* src = static_cast<const uint4*>(out_src ? out_src : out);
+    const bool all_rows = out_src != nullptr && out_src != out;
+    if (y_mode == 0) hipLaunchKernelGGL(combine_kernel<0>, dim3(grid), dim3(256), 0, s, yy, pos, w, Tn, k, M / 8, accumulate, all_rows, src, oo);
+    else if (y_mode == 1) hipLaunchKernelGGL(combine_kernel<1>, dim3(grid), dim3(256), 0, s, yy, pos, w, Tn, k, M / 8, accumulate, all_rows, src, oo);
+    else hipLaunchKernelGGL(combine_kernel<2>, dim3(grid), dim3(256), 0, s, yy, pos, w, Tn, k, M / 8, accumulate, all_rows, src, oo);
     return hipGetLastError();
 }
 

@@ -24,11 +24,14 @@ hipError_t launch_gather_rows(const void* tokens, const int32_t* perm, const int
 // ---- weighted aggregation (Sec. 2.1)
 // y_mode: 0 bf16 expert outputs, weighted here; 1 fp32 expert outputs, weighted here; 2 bf16 expert
 // outputs that already carry their routing weight
+// accumulate: the rows at out_src already hold the shared experts' output and the sum is added to
+// them.  out_src == NULL or == out: in place (rows with nothing kept are then left alone); else
+// every row is read at out_src and written at out (which may be the caller's pinned host buffer)
 hipError_t launch_combine(const void* y, const int32_t* pos, const float* w, int Tn, int k, int M,
-                          bool accumulate, int y_mode, void* out, int grid, hipStream_t s);
+                          bool accumulate, int y_mode, const void* out_src, void* out, int grid, hipStream_t s);
 
 // ---- chunk transfers over the host link (pinned-host mode); bytes must be a multiple of 4
-hipError_t launch_copy(void* dst, const void* src, size_t bytes, int grid, hipStream_t s);
+hipError_t launch_copy(void* dst, const void* src, size_t bytes, int grid, hipStream_t s, int threads = 256, int unroll = 4);
 // a one-wavefront kernel that lasts about `microseconds` (at most 1 s): stand-in for a task that
 // runs on other hardware
 hipError_t launch_busy(double microseconds, hipStream_t s);

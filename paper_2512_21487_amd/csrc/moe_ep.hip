@@ -37,7 +37,20 @@ struct moe_ep_ctx {
     int shared_variant = 2;  // shared experts: dense rows, 256-row tiles
     bool fused_gather = true;  // the gate/up projection gathers the token rows itself (no grouped copy)
     int y_mode = 0;            // expert outputs: 0 bf16, 1 fp32, 2 bf16 scaled by the routing weight (expert_out_mode)
-    int link_grid = 8;         // workgroups of a host-link copy kernel
+    // pinned-host mode, moe_ep_forward: the aggregation writes its rows straight into the caller's host
+    // buffer and there is no outbound copy.  On this GPU a kernel that starts while another stream's
+    // kernel streams writes to the host does not complete until that stream pauses, so an outbound copy
+    // on a stream of its own overlaps with nothing and only adds a kernel; fused, every size and chunk
+    // count measured 2-10 % faster.  MOE_EP_FUSED_OUT=0 restores the outbound link stream, which
+    // moe_ep_forward_dep, whose point is the schedule of Sec. 2.3, always uses.
+    bool fused_out = true;
+    // a host-link copy kernel: 64 workgroups of one wavefront, two 16-byte loads per lane in flight
+    // (128 KB over the link, enough to fill it).  A copy wavefront holds the vector memory path of its
+    // compute unit with host-link latencies, and a GEMM tile that shares the unit runs at a fraction of
+    // its rate; many thin copy workgroups slow 64 units a little instead of 8 units a lot (the launch
+    // lasts as long as its slowest tile): 4096 decode tokens in 2 chunks 1.53 -> 1.44 ms
+    int link_grid = 64;
+    int link_threads = 64, link_unroll = 2;
     bool memcpy_in = false, memcpy_out = false;  // host-link copies through the runtime instead of kernels
     bool check_spans = true;   // every forward asks the runtime what its pointer arguments point at
     // device workspaces
@@ -155,7 +168,9 @@ void read_knobs(moe_ep_ctx* ctx)
     if (const char* v = getenv("MOE_EP_DOWN_UNITS")) ctx->down_units = atoi(v);
     // workgroups of a copy kernel: ~128 KB in flight fills the host link; more only queues up in the
     // memory fabric in front of the compute kernels
-    if (const char* v = getenv("MOE_EP_LINK_GRID")) ctx->link_grid = atoi(v) > 0 ? atoi(v) : 8;
+    if (const char* v = getenv("MOE_EP_LINK_GRID")) ctx->link_grid = atoi(v) > 0 ? atoi(v) : 64;
+    if (const char* v = getenv("MOE_EP_LINK_THREADS")) ctx->link_threads = (atoi(v) >= 64 && atoi(v) <= 256 && atoi(v) % 64 == 0) ? atoi(v) : 64;
+    if (const char* v = getenv("MOE_EP_LINK_UNROLL")) ctx->link_unroll = atoi(v) >= 1 ? atoi(v) : 2;
     // MOE_EP_LINK_MEMCPY = 1 | in | out: the runtime's asynchronous copies (DMA engines) instead of copy
     // kernels in both / one direction, kept for comparison: inbound they overlap cleanly with compute,
     // but each call costs the host thread 0.2-0.3 ms on this system
@@ -165,6 +180,7 @@ void read_knobs(moe_ep_ctx* ctx)
     }
     ctx->fused_gather = fused_gather_enabled();
     ctx->y_mode = expert_out_mode();
+    if (const char* v = getenv("MOE_EP_FUSED_OUT")) ctx->fused_out = atoi(v) != 0;
     // MOE_EP_CHECK_POINTERS=0 skips the per-forward pointer queries (a few microseconds of host time)
     if (const char* v = getenv("MOE_EP_CHECK_POINTERS")) ctx->check_spans = atoi(v) != 0;
 }
@@ -543,6 +559,7 @@ int forward_impl(moe_ep_ctx* ctx, const void* tokens, const float* gate_logits, 
     const int n_cu = ctx->n_cu;
     hipStream_t s_out = pinned ? ctx->s_out : user;
     const bool prof = ctx->prof_depth > 0 && ctx->prof_recorded < ctx->prof_depth;
+    const bool fused_out = pinned && ctx->fused_out && !dep;   // the aggregation's stores are the outbound transfer
 
     const uint16_t* tok_dev = static_cast<const uint16_t*>(pinned ? ctx->d_tokens : tokens);
     const float* log_dev = pinned ? ctx->d_logits : gate_logits;
@@ -579,7 +596,7 @@ int forward_impl(moe_ep_ctx* ctx, const void* tokens, const float* gate_logits, 
     auto link_copy = [&](void* dst, const void* src, size_t bytes, int grid, hipStream_t st) -> hipError_t {
         if (st == s_in ? ctx->memcpy_in : ctx->memcpy_out)
             return bytes ? hipMemcpyAsync(dst, src, bytes, hipMemcpyDefault, st) : hipSuccess;
-        return launch_copy(dst, src, bytes, grid, st);
+        return launch_copy(dst, src, bytes, grid, st, ctx->link_threads, ctx->link_unroll);
     };
     const int link_grid = ctx->link_grid;
     const int span_total = prof_begin(ctx, prof, ST_TOTAL, user);
@@ -727,7 +744,7 @@ int forward_impl(moe_ep_ctx* ctx, const void* tokens, const float* gate_logits, 
         }
         prof_end(ctx, sp, s_comp);
         if (Tn == 0) {
-            if (pinned) HIP_TRY(ctx, hipEventRecord(ctx->ev_comp[cidx], s_comp));
+            if (pinned && !fused_out) HIP_TRY(ctx, hipEventRecord(ctx->ev_comp[cidx], s_comp));
             continue;
         }
 
@@ -764,11 +781,15 @@ int forward_impl(moe_ep_ctx* ctx, const void* tokens, const float* gate_logits, 
         // the aggregation adds to what the micro-batch's shared experts have written (attention-group stream)
         if (dep && Ns > 0) HIP_TRY(ctx, hipStreamWaitEvent(s_comp, ctx->ev_shared[cidx / r_2], 0));
 
+        // fused outbound transfer: the aggregation reads the shared experts' rows from the device
+        // staging buffer and writes every row of the chunk into the caller's pinned buffer
+        uint16_t* out_rows = out_dev + (size_t)t0 * M;
         sp = prof_begin(ctx, prof, ST_COMBINE, s_comp);
-        HIP_TRY(ctx, launch_combine(ctx->y, pos, w, Tn, k, M, Ns > 0, ctx->y_mode, out_dev + (size_t)t0 * M, bw_grid, s_comp));
+        HIP_TRY(ctx, launch_combine(ctx->y, pos, w, Tn, k, M, Ns > 0, ctx->y_mode, out_rows,
+                                    fused_out ? reinterpret_cast<uint16_t*>(h_out) + (size_t)t0 * M : out_rows, bw_grid, s_comp));
         prof_end(ctx, sp, s_comp);
 
-        if (pinned) {
+        if (pinned && !fused_out) {
             HIP_TRY(ctx, hipEventRecord(ctx->ev_comp[cidx], s_comp));
             HIP_TRY(ctx, hipStreamWaitEvent(s_out, ctx->ev_comp[cidx], 0));
             const int sp_out = prof_begin(ctx, prof && !ctx->memcpy_out, ST_COPY_OUT, s_out);
@@ -778,7 +799,7 @@ int forward_impl(moe_ep_ctx* ctx, const void* tokens, const float* gate_logits, 
             prof_end(ctx, sp_out, s_out);
         }
     }
-    if (pinned) {
+    if (pinned && !fused_out) {
         HIP_TRY(ctx, hipEventRecord(ctx->ev_comp_done, s_comp));
         HIP_TRY(ctx, hipStreamWaitEvent(s_out, ctx->ev_comp_done, 0));
         HIP_TRY(ctx, hipEventRecord(ctx->ev_done, s_out));

@@ -10,27 +10,36 @@
 
 namespace moe_ep {
 
-template <typename V>
+// U independent loads per lane in flight; any block size up to 256
+template <typename V, int U>
 __global__ __launch_bounds__(256) void copy_kernel(const V* __restrict__ src, V* __restrict__ dst, size_t n)
 {
-    const size_t stride = (size_t)gridDim.x * 256;
-    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-    for (; i + 3 * stride < n; i += 4 * stride) {
-        const V a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
-        dst[i] = a; dst[i + stride] = b; dst[i + 2 * stride] = c; dst[i + 3 * stride] = d;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    for (; i + (U - 1) * stride < n; i += U * stride) {
+        V v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) v[u] = src[i + u * stride];
+#pragma unroll
+        for (int u = 0; u < U; ++u) dst[i + u * stride] = v[u];
     }
     for (; i < n; i += stride) dst[i] = src[i];
 }
 
-hipError_t launch_copy(void* dst, const void* src, size_t bytes, int grid, hipStream_t s)
+// grid workgroups of `threads` lanes, `unroll` loads in flight per lane (1, 2 or 4)
+hipError_t launch_copy(void* dst, const void* src, size_t bytes, int grid, hipStream_t s, int threads, int unroll)
 {
     if (bytes == 0) return hipSuccess;
+    if (threads < 64 || threads > 256 || threads % 64) return hipErrorInvalidValue;
     const bool a16 = ((reinterpret_cast<uintptr_t>(dst) | reinterpret_cast<uintptr_t>(src) | bytes) & 15) == 0;
     if (a16) {
-        hipLaunchKernelGGL(copy_kernel<uint4>, dim3(grid), dim3(256), 0, s, static_cast<const uint4*>(src),
-                           static_cast<uint4*>(dst), bytes / 16);
+        auto* sp = static_cast<const uint4*>(src);
+        auto* dp = static_cast<uint4*>(dst);
+        if (unroll >= 4) hipLaunchKernelGGL((copy_kernel<uint4, 4>), dim3(grid), dim3(threads), 0, s, sp, dp, bytes / 16);
+        else if (unroll >= 2) hipLaunchKernelGGL((copy_kernel<uint4, 2>), dim3(grid), dim3(threads), 0, s, sp, dp, bytes / 16);
+        else hipLaunchKernelGGL((copy_kernel<uint4, 1>), dim3(grid), dim3(threads), 0, s, sp, dp, bytes / 16);
     } else {  // 4-byte granularity (gate scores of a chunk need not start on a 16-byte boundary)
-        hipLaunchKernelGGL(copy_kernel<uint32_t>, dim3(grid), dim3(256), 0, s, static_cast<const uint32_t*>(src),
+        hipLaunchKernelGGL((copy_kernel<uint32_t, 4>), dim3(grid), dim3(threads), 0, s, static_cast<const uint32_t*>(src),
                            static_cast<uint32_t*>(dst), bytes / 4);
     }
     return hipGetLastError();

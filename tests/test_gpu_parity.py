@@ -357,7 +357,11 @@ def test_context_reuse_with_fewer_tokens():
     ctx.destroy()
 
 
-def test_pinned_host_pipeline_matches_device_mode():
+@pytest.mark.parametrize("fused_out", [1, 0])
+def test_pinned_host_pipeline_matches_device_mode(fused_out):
+    """Pinned-host I/O, with the outbound transfer fused into the aggregation (default) and as a copy on
+    a link stream of its own: the bits of the device-resident forward, shared experts included (their
+    rows reach the host through the aggregation also where a token keeps no routed expert)."""
     g = _gpu()
     wl = tiny_workload(name="pinned", n_tokens=700, hidden=256, inter=192, n_experts=16,
                        local_begin=4, n_local=8, top_k=4, n_shared=1, shared_inter=128)
@@ -365,10 +369,11 @@ def test_pinned_host_pipeline_matches_device_mode():
     ctx = g.make_ctx(wl)
     base = g.run_forward(ctx, wl, g.DeviceInputs(wl, inp))
     ctx.destroy()
-    pctx = g.make_ctx(wl, pinned=True)
+    with _env(MOE_EP_FUSED_OUT=fused_out):
+        pctx = g.make_ctx(wl, pinned=True)
     pd = g.DeviceInputs(wl, inp, pinned=True)
     for r, order in [(1, 0), (4, 1), (8, 0)]:
-        print(f"[case] pinned r={r} order={order}", flush=True)
+        print(f"[case] pinned r={r} order={order} fused_out={fused_out}", flush=True)
         out = g.run_forward(pctx, wl, pd, r=r, order=order)
         assert np.array_equal(out, base)
     pctx.destroy()
@@ -459,18 +464,22 @@ def test_serialised_launches_give_the_same_bits():
     assert len(set(digests[0])) == 1  # and chunking, order and I/O mode change nothing either
 
 
-def test_measured_timeline_obeys_the_precedence_rules():
+@pytest.mark.parametrize("fused_out", [False, True])
+def test_measured_timeline_obeys_the_precedence_rules(fused_out):
     """The measured schedule of a pinned-host forward with r_2 = 3 (moe_ep_get_timeline): every stage
     appears once per chunk, a chunk's compute starts after its inbound copy ends and its outbound copy
     after its aggregation ends (Sec. 3.2, Eq. limitation, rules 7-8), each resource runs its tasks in
-    chunk order without overlap (rules 3-5)."""
+    chunk order without overlap (rules 3-5).  With the outbound transfer fused into the aggregation (the
+    default of moe_ep_forward) there is no outbound copy and the aggregation is the chunk's last task."""
     g = _gpu()
     wl = tiny_workload(name="timeline", n_tokens=600, hidden=256, inter=192, n_experts=16, n_local=16, top_k=2)
-    pctx = g.make_ctx(wl, pinned=True)
+    with _env(MOE_EP_FUSED_OUT=1 if fused_out else 0):
+        pctx = g.make_ctx(wl, pinned=True)
     pd = g.DeviceInputs(wl, make_inputs(wl, seed=33), pinned=True)
-    g.run_forward(pctx, wl, pd, r=3)
+    base = g.run_forward(pctx, wl, pd, r=3)
     pctx.set_profiling(1)
-    g.run_forward(pctx, wl, pd, r=3)
+    out = g.run_forward(pctx, wl, pd, r=3)
+    assert np.array_equal(out, base)
     tl = pctx.get_timeline()
     pctx.get_stage_ms()
     pctx.set_profiling(0)
@@ -478,16 +487,23 @@ def test_measured_timeline_obeys_the_precedence_rules():
     for name, fwd, b, e in tl:
         assert fwd == 0 and e >= b >= 0.0
         by.setdefault(name, []).append((b, e))
-    for name in ("copy_in", "router", "partition", "routed_gate_up_gemm", "routed_down_gemm", "aggregation", "copy_out"):
+    stages = ["copy_in", "router", "partition", "routed_gate_up_gemm", "routed_down_gemm", "aggregation"]
+    if not fused_out:
+        stages.append("copy_out")
+    else:
+        assert "copy_out" not in by
+    for name in stages:
         assert len(by[name]) == 3, name
         for (b0, e0), (b1, e1) in zip(by[name], by[name][1:]):
             assert b1 >= e0 - 1e-3, f"{name}: chunks overlap on one resource"
     eps = 2e-3  # event timestamps resolve to about a microsecond
     for c in range(3):
         assert by["router"][c][0] >= by["copy_in"][c][1] - eps
-        assert by["copy_out"][c][0] >= by["aggregation"][c][1] - eps
+        if not fused_out:
+            assert by["copy_out"][c][0] >= by["aggregation"][c][1] - eps
         assert by["routed_down_gemm"][c][0] >= by["routed_gate_up_gemm"][c][1] - eps
-    assert len(by["forward"]) == 1 and by["forward"][0][1] >= by["copy_out"][2][1] - eps
+    last = by["aggregation" if fused_out else "copy_out"][2][1]
+    assert len(by["forward"]) == 1 and by["forward"][0][1] >= last - eps
     pctx.destroy()
 
 
