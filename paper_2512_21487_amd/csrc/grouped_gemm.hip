@@ -192,10 +192,9 @@ __device__ __forceinline__ void gemm_tiles(const GemmArgs& a, uint4* lds, const 
     const int total = mt_total * NT;
     // A launch lasts as many tiles as its busiest workgroup works through: rounds = ceil(total /
     // workgroups).  Only as many workgroups as it takes to finish in that many rounds stay: the
-    // others would run one tile less and then wait, and under the package power limit the clock
-    // the remaining ones get is worth more than the idle ones' head start (984 tiles on 256 compute
-    // units are 4 rounds on 248 as well: measured 3 % faster).  The count is a multiple of 8 so that
-    // every XCD (workgroup id mod 8) keeps the same number of workgroups.
+    // others would run one tile less and then wait (984 tiles on 256 compute units are 4 rounds on 248
+    // as well; no measurable change in time, less work for the power budget).  The count is a multiple
+    // of 8 so that every XCD (workgroup id mod 8) keeps the same number of workgroups.
     const int rounds = (total + (int)gridDim.x - 1) / (int)gridDim.x;
     const int active = rounds > 0 ? min((int)gridDim.x, (((total + rounds - 1) / rounds) + 7) & ~7) : 0;
     const int per_xcd = active >> 3;
