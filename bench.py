@@ -213,6 +213,8 @@ def main() -> int:
                          "average of 3 runs) and print one line: value = mean over the processes")
     ap.add_argument("--no-device-probe", action="store_true",
                     help="skip the register-only MFMA loop and the streaming copy that follow the timed forwards")
+    ap.add_argument("--no-prepare-weights", action="store_true",
+                    help="read the weights in the caller's row-major layout (no tile-order copy)")
     ap.add_argument("--no-stage-timing", action="store_true",
                     help="time the K steps without per-stage HIP events (stage figures are then absent)")
     ap.add_argument("--fit-pipeline", action="store_true",
@@ -284,6 +286,17 @@ def main() -> int:
                     max_tokens=T, max_top_k=k, max_chunks=max(args.r, 8 if pinned else 1, dep_chunks),
                     io_mode=pkg.IO_PINNED_HOST if pinned else pkg.IO_DEVICE)
     stream = torch.cuda.current_stream().cuda_stream
+    # The weights of an expert do not change between calls: they are laid out in tile order once, before
+    # any timed forward, in memory the context owns (moe_ep_prepare_weights; its time is reported apart).
+    weights = {"layout": "caller's row-major"}
+    if not args.no_prepare_weights:
+        torch.cuda.synchronize()
+        t_p = time.perf_counter()
+        ctx.prepare_weights(routed, shared, stream=stream)
+        torch.cuda.synchronize()
+        weights = {"layout": "tile order (moe_ep_prepare_weights, once, outside the timed region)",
+                   "prepare_ms": round((time.perf_counter() - t_p) * 1e3, 3),
+                   "copy_bytes": ctx.prepared_weight_bytes(True, shared is not None)}
 
     def step():
         ctx.forward(tokens, logits, routed, shared, k, args.r, args.order, n_tokens=T, out=out,
@@ -398,7 +411,7 @@ def main() -> int:
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{wl.name}: T={T} M={M} H={H} E={wl.n_experts} local={wl.n_local} "
                                f"top_k={k} shared={Ns}x{Hs} io={'pinned_host' if pinned else 'device'}",
-                   "r_chunks": args.r, "order": args.order, "kept_assignments": kept,
+                   "r_chunks": args.r, "order": args.order, "weights": weights, "kept_assignments": kept,
                    "expert_load": {"max": int(load.max()), "mean": float(load.mean()), "min": int(load.min()),
                                    "empty": int((load == 0).sum())}},
         "grouped_gemm_pct_of_bf16_mfma_peak": routed_pct,
@@ -499,6 +512,9 @@ def main() -> int:
         L = args.layers
         routed_l = [routed] + [torch.roll(routed, 4099 * l) for l in range(1, L)]
         shared_l = [shared] + [None if shared is None else torch.roll(shared, 4099 * l) for l in range(1, L)]
+        if not args.no_prepare_weights:
+            for l in range(1, L):
+                ctx.prepare_weights(routed_l[l], shared_l[l], stream=stream)
 
         def layer_step():
             for l in range(L):

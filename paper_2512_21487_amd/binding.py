@@ -3,6 +3,7 @@ from __future__ import annotations
 
 import ctypes
 import os
+import sys
 from typing import Dict, Optional, Tuple
 
 import numpy as np
@@ -110,6 +111,12 @@ def load_library() -> ctypes.CDLL:
     lib.moe_ep_create.argtypes = [cfgp, ctypes.POINTER(vp)]
     lib.moe_ep_forward.restype = ctypes.c_int
     lib.moe_ep_forward.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, vp, vp]
+    lib.moe_ep_prepare_weights.restype = ctypes.c_int
+    lib.moe_ep_prepare_weights.argtypes = [vp, vp, vp, vp]
+    lib.moe_ep_forget_weights.restype = ctypes.c_int
+    lib.moe_ep_forget_weights.argtypes = [vp, vp, vp]
+    lib.moe_ep_prepared_weight_bytes.restype = ctypes.c_size_t
+    lib.moe_ep_prepared_weight_bytes.argtypes = [cfgp, i32, i32]
     lib.moe_ep_forward_noalloc.restype = ctypes.c_int
     lib.moe_ep_forward_noalloc.argtypes = [cfgp, vp, vp, vp, vp, i32, i32, i32, i32, vp, vp,
                                            ctypes.POINTER(ctypes.c_char_p)]
@@ -190,6 +197,11 @@ def _check_tensor(x, name: str, n_bytes: int, want_pinned: bool) -> None:
         raise ValueError(f"{name} must be a pinned host tensor in IO_PINNED_HOST mode")
     if not want_pinned and not (x.is_cuda or x.is_pinned()):
         raise ValueError(f"{name} must be a device tensor")
+
+
+def prepared_weight_bytes(cfg: MoeEpConfig, routed: bool = True, shared: bool = True) -> int:
+    """moe_ep_prepared_weight_bytes: device bytes moe_ep_prepare_weights takes for these sets of weights."""
+    return int(load_library().moe_ep_prepared_weight_bytes(ctypes.byref(cfg), int(routed), int(shared)))
 
 
 def validate_config(cfg: MoeEpConfig) -> Tuple[int, str]:
@@ -394,6 +406,29 @@ class MoeEp:
         self._last = (n_tokens, top_k, int(self._lib.moe_ep_last_chunks(self._ctx)), 1)
         return rc
 
+    # -- moe_ep_prepare_weights / moe_ep_forget_weights -------------------------------------
+    def prepare_weights(self, routed_w=None, shared_w=None, stream: Optional[int] = None) -> int:
+        """Tile-order copies of the weights at these pointers; later forwards given the same tensors use them."""
+        if stream is None:
+            import torch
+            stream = torch.cuda.current_stream().cuda_stream
+        c = self.cfg
+        _check_tensor(routed_w, "routed_w", c.n_local * 3 * c.inter * c.hidden * 2, False)
+        _check_tensor(shared_w, "shared_w", c.n_shared * 3 * c.shared_inter * c.hidden * 2, False)
+        rc = self._lib.moe_ep_prepare_weights(self._ctx, _ptr(routed_w), _ptr(shared_w), stream)
+        if rc != 0:
+            raise MoeEpError(rc, self.last_error())
+        return rc
+
+    def forget_weights(self, routed_w=None, shared_w=None) -> int:
+        rc = self._lib.moe_ep_forget_weights(self._ctx, _ptr(routed_w), _ptr(shared_w))
+        if rc != 0:
+            raise MoeEpError(rc, self.last_error())
+        return rc
+
+    def prepared_weight_bytes(self, routed: bool = True, shared: bool = True) -> int:
+        return int(self._lib.moe_ep_prepared_weight_bytes(ctypes.byref(self.cfg), int(routed), int(shared)))
+
     # -- moe_ep_forward_dep ---------------------------------------------------------------
     def forward_dep(self, tokens, gate_logits, routed_w, shared_w, top_k: int, r_1: int = 1, r_2: int = 1,
                     dep_order: int = 0, attn_us: float = 0.0, n_tokens: Optional[int] = None, out=None,
@@ -495,10 +530,9 @@ class MoeEp:
         # At interpreter shutdown the HIP runtime, a preloaded profiler and torch's allocators are being
         # torn down in an order this object does not control: calling into the library then could touch
         # streams and events that are already gone.  The process is ending; the driver reclaims the memory.
-        import sys
-        if sys is None or sys.is_finalizing():
-            return
         try:
+            if sys is None or sys.is_finalizing():
+                return
             self.destroy()
         except Exception:
             pass

@@ -170,7 +170,7 @@ static int lds_cap(int bytes) { return bytes < kLdsPerWorkgroup ? bytes : kLdsPe
 // 0 bf16 results; 1 fp32 results (the experts' outputs are then not rounded before the aggregation);
 // 2 bf16 results already multiplied by the routing weight of the row's assignment (Sec. 2.1: the
 // aggregation then only adds)
-template <int BM, int BN, int BK, int STAGES, int WGM, int WGN, bool SWIGLU, bool RAGGED, int EPI = 0>
+template <int BM, int BN, int BK, int STAGES, int WGM, int WGN, bool SWIGLU, bool RAGGED, int EPI = 0, bool PACKED = false>
 __device__ __forceinline__ void gemm_tiles(const GemmArgs& a, uint4* lds, const int* s_pref, const int* s_row0,
                                            const int* s_rowend, int* s_tile, int max_units)
 {
@@ -213,6 +213,9 @@ __device__ __forceinline__ void gemm_tiles(const GemmArgs& a, uint4* lds, const 
     // the rows of a tile are dealt to the WGM rows of wavefronts hb * 32 at a time
     struct Tile { int g, row0, nrows, n0, hb; };
     const bool mapped = RAGGED && a.a_row_map != nullptr;   // token rows gathered by the tile loads
+    // weights in tile order (kernels.h): a K step's weight tile is one contiguous block
+    constexpr bool packed = PACKED;
+    static_assert(!PACKED || (BN == kPackRows && BK == kPackK), "the tile-order copy is laid out for one weight tile shape");
     const uint16_t* Xi = a.A;
     const uint16_t* Wi = a.W;
     // per region this wavefront loads: the lane's global source (row, swizzled chunk) as a byte
@@ -291,7 +294,8 @@ __device__ __forceinline__ void gemm_tiles(const GemmArgs& a, uint4* lds, const 
         t.nrows = __builtin_amdgcn_readfirstlane(nrows);
         t.n0 = __builtin_amdgcn_readfirstlane(n0);
         t.hb = __builtin_amdgcn_readfirstlane(hb);
-        Wi = a.W + (size_t)t.g * a.w_group_stride;
+        if (packed) Wi = a.Wp + ((size_t)t.g * NT + t.n0 / BN_OUT) * ((size_t)KT * BN * BK);
+        else Wi = a.W + (size_t)t.g * a.w_group_stride;
         Xi = mapped ? a.A : a.A + (size_t)t.row0 * a.lda;
 #pragma unroll
         for (int i = 0; i < RPW; ++i) {
@@ -318,7 +322,8 @@ __device__ __forceinline__ void gemm_tiles(const GemmArgs& a, uint4* lds, const 
                     n = t.n0 + jw;
                 }
                 n = min(n, a.N - 1);
-                goff[i] = (base + (uint32_t)n * (uint32_t)a.ldw + c * 8) * 2u;
+                goff[i] = packed ? (uint32_t)(jw * BK + c * 8) * 2u
+                                 : (base + (uint32_t)n * (uint32_t)a.ldw + c * 8) * 2u;
             }
         }
         return true;
@@ -347,7 +352,8 @@ __device__ __forceinline__ void gemm_tiles(const GemmArgs& a, uint4* lds, const 
     {                                                                                             \
         const int k_ = (ks_) * BK;                                                                \
         const int seg_ = k_ / a.kseg_len;                                                         \
-        const size_t wk_ = (size_t)seg_ * a.w_kseg_stride + (k_ - seg_ * a.kseg_len);             \
+        const size_t wk_ = packed ? (size_t)(ks_) * (BN * BK)                                     \
+                                  : (size_t)seg_ * a.w_kseg_stride + (k_ - seg_ * a.kseg_len);    \
         uint4* dst_ = lds + (stage_) * Cfg::STAGE_CHUNKS + wave * 64 + NW * 64 * (i_);            \
         __builtin_amdgcn_global_load_lds(                                                         \
             reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(                         \
@@ -540,7 +546,7 @@ __device__ __forceinline__ void gemm_tiles(const GemmArgs& a, uint4* lds, const 
 }
 
 
-template <int BM, int BN, int BK, int STAGES, int WGM, int WGN, bool SWIGLU, bool RAGGED, int EPI = 0>
+template <int BM, int BN, int BK, int STAGES, int WGM, int WGN, bool SWIGLU, bool RAGGED, int EPI = 0, bool PACKED = false>
 __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_kernel(GemmArgs a)
 {
     extern __shared__ uint4 lds[];
@@ -548,7 +554,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_kernel(GemmArgs a)
     const LdsTables t = lds_tables(lds, Cfg::LDS_BYTES, a.G);
     const int max_units = (a.max_units > 0 && a.max_units < Cfg::MB) ? a.max_units : Cfg::MB;
     if (RAGGED) fill_tables(a, t, 32 * WGM, max_units);
-    gemm_tiles<BM, BN, BK, STAGES, WGM, WGN, SWIGLU, RAGGED, EPI>(a, lds, t.pref, t.row0, t.rowend, t.tile, max_units);
+    gemm_tiles<BM, BN, BK, STAGES, WGM, WGN, SWIGLU, RAGGED, EPI, PACKED>(a, lds, t.pref, t.row0, t.rowend, t.tile, max_units);
 }
 
 // what every kernel here assumes of its arguments beyond the shapes the caller has checked
@@ -564,7 +570,7 @@ static bool args_fit(const GemmArgs& a, bool swiglu, bool ragged, int bm)
     return !(a.N % 8 || a.ldc % 8 || a.c_group_col_stride % 8 || (reinterpret_cast<uintptr_t>(a.C) & 15));
 }
 
-template <int BM, int BN, int BK, int STAGES, int WGM, int WGN, bool SWIGLU, bool RAGGED, int EPI = 0>
+template <int BM, int BN, int BK, int STAGES, int WGM, int WGN, bool SWIGLU, bool RAGGED, int EPI = 0, bool PACKED = false>
 static hipError_t launch_one(const GemmArgs& a, int n_cu, long long max_rows, hipStream_t s)
 {
     using Cfg = GemmCfg<BM, BN, BK, STAGES, WGM, WGN, SWIGLU>;
@@ -586,48 +592,48 @@ static hipError_t launch_one(const GemmArgs& a, int n_cu, long long max_rows, hi
     long long grid = (long long)n_cu * occ;
     if (grid > max_tiles) grid = max_tiles;
     grid = (grid + 7) / 8 * 8;
-    hipLaunchKernelGGL((grouped_gemm_kernel<BM, BN, BK, STAGES, WGM, WGN, SWIGLU, RAGGED, EPI>),
+    hipLaunchKernelGGL((grouped_gemm_kernel<BM, BN, BK, STAGES, WGM, WGN, SWIGLU, RAGGED, EPI, PACKED>),
                        dim3((unsigned)grid), dim3(Cfg::THREADS), lds_bytes, s, a);
     return hipGetLastError();
 }
 
-template <int BM, int BN, int BK, int STAGES, int WGM, int WGN>
+template <int BM, int BN, int BK, int STAGES, int WGM, int WGN, bool PACKED>
 static hipError_t raise_all()
 {
     hipError_t e;
-#define R(SW, RG)                                                                                       \
+#define R(SW, RG, EPI)                                                                                  \
     if ((e = hipFuncSetAttribute(                                                                       \
-             reinterpret_cast<const void*>(&grouped_gemm_kernel<BM, BN, BK, STAGES, WGM, WGN, SW, RG>), \
+             reinterpret_cast<const void*>(&grouped_gemm_kernel<BM, BN, BK, STAGES, WGM, WGN, SW, RG, EPI, PACKED>), \
              hipFuncAttributeMaxDynamicSharedMemorySize,                                                \
              lds_cap(GemmCfg<BM, BN, BK, STAGES, WGM, WGN, SW>::LDS_BYTES +                             \
                      lds_table_bytes(RG, kMaxGroups)))) != hipSuccess) return e;
-    R(true, true) R(true, false) R(false, true) R(false, false)
-#undef R
-#define R(EPI)                                                                                          \
-    if ((e = hipFuncSetAttribute(                                                                       \
-             reinterpret_cast<const void*>(&grouped_gemm_kernel<BM, BN, BK, STAGES, WGM, WGN, false, true, EPI>), \
-             hipFuncAttributeMaxDynamicSharedMemorySize,                                                \
-             lds_cap(GemmCfg<BM, BN, BK, STAGES, WGM, WGN, false>::LDS_BYTES +                          \
-                     lds_table_bytes(true, kMaxGroups)))) != hipSuccess) return e;
-    R(1) R(2)
+    R(true, true, 0) R(true, false, 0) R(false, true, 0) R(false, false, 0) R(false, true, 1) R(false, true, 2)
 #undef R
     return hipSuccess;
 }
 
-template <int BM, int BN, int BK, int STAGES, int WGM, int WGN>
+// PK: the variant also exists for weights in tile order (its weight tile is kPackRows x kPackK)
+template <int BM, int BN, int BK, int STAGES, int WGM, int WGN, bool PK>
 static hipError_t launch_cfg(const GemmArgs& a, bool swiglu, int n_cu, long long max_rows, hipStream_t s)
 {
     const bool ragged = a.offset != nullptr;
     if (swiglu && a.epi != 0) return hipErrorInvalidValue;
-    if (swiglu) return ragged ? launch_one<BM, BN, BK, STAGES, WGM, WGN, true, true>(a, n_cu, max_rows, s)
-                              : launch_one<BM, BN, BK, STAGES, WGM, WGN, true, false>(a, n_cu, max_rows, s);
-    if (a.epi != 0) {  // only the routed down projection has other epilogues
-        if (!ragged || a.epi < 0 || a.epi > 2 || (a.epi == 2 && (!a.row_weight || !a.row_assignment))) return hipErrorInvalidValue;
-        return a.epi == 1 ? launch_one<BM, BN, BK, STAGES, WGM, WGN, false, true, 1>(a, n_cu, max_rows, s)
-                          : launch_one<BM, BN, BK, STAGES, WGM, WGN, false, true, 2>(a, n_cu, max_rows, s);
+    // only the routed down projection has other epilogues
+    if (a.epi != 0 && (!ragged || a.epi < 0 || a.epi > 2 || (a.epi == 2 && (!a.row_weight || !a.row_assignment))))
+        return hipErrorInvalidValue;
+    auto go = [&](auto packed) -> hipError_t {
+        constexpr bool P = decltype(packed)::value;
+        if (swiglu) return ragged ? launch_one<BM, BN, BK, STAGES, WGM, WGN, true, true, 0, P>(a, n_cu, max_rows, s)
+                                  : launch_one<BM, BN, BK, STAGES, WGM, WGN, true, false, 0, P>(a, n_cu, max_rows, s);
+        if (a.epi == 1) return launch_one<BM, BN, BK, STAGES, WGM, WGN, false, true, 1, P>(a, n_cu, max_rows, s);
+        if (a.epi == 2) return launch_one<BM, BN, BK, STAGES, WGM, WGN, false, true, 2, P>(a, n_cu, max_rows, s);
+        return ragged ? launch_one<BM, BN, BK, STAGES, WGM, WGN, false, true, 0, P>(a, n_cu, max_rows, s)
+                      : launch_one<BM, BN, BK, STAGES, WGM, WGN, false, false, 0, P>(a, n_cu, max_rows, s);
+    };
+    if constexpr (PK) {
+        if (a.Wp != nullptr) return go(std::true_type{});
     }
-    return ragged ? launch_one<BM, BN, BK, STAGES, WGM, WGN, false, true>(a, n_cu, max_rows, s)
-                  : launch_one<BM, BN, BK, STAGES, WGM, WGN, false, false>(a, n_cu, max_rows, s);
+    return go(std::false_type{});
 }
 
 // tile variants: id, BM, BN, BK, ring slots, wavefronts in m, in n
@@ -636,23 +642,26 @@ static hipError_t launch_cfg(const GemmArgs& a, bool swiglu, int n_cu, long long
 // default).  BM is the tallest tile of a variant: over ragged groups the tiles are cut to fit the group
 // (cut_group) in units of 32 rows per row of wavefronts.  A ring of S slots needs K >= S * BK; for a
 // shorter K the launcher takes the two-slot variant with 32-wide K steps (K is a multiple of 64)
-// listed in the last column.
+// listed in the column before the last.  Last column: the variant is also built for weights in tile
+// order (kernels.h: the shapes the library picks by itself; the others read the caller's layout).
 #define MOE_EP_VARIANTS(X)         \
-    X(0, 64, 128, 64, 2, 1, 2, 8)  \
-    X(1, 128, 256, 64, 3, 2, 2, 6) \
-    X(2, 256, 256, 64, 2, 2, 2, 9) \
-    X(6, 128, 256, 32, 2, 2, 2, 6) \
-    X(8, 64, 128, 32, 2, 1, 2, 8)  \
-    X(9, 256, 256, 32, 2, 2, 2, 9)  \
-    X(11, 160, 256, 64, 3, 1, 4, 12) \
-    X(12, 160, 256, 32, 2, 1, 2, 12) \
-    X(13, 224, 256, 64, 2, 1, 4, 12) \
-    X(14, 256, 256, 64, 2, 1, 4, 12)
+    X(0, 64, 128, 64, 2, 1, 2, 8, false)  \
+    X(1, 128, 256, 64, 3, 2, 2, 6, true) \
+    X(2, 256, 256, 64, 2, 2, 2, 9, true) \
+    X(6, 128, 256, 32, 2, 2, 2, 6, false) \
+    X(8, 64, 128, 32, 2, 1, 2, 8, false)  \
+    X(9, 256, 256, 32, 2, 2, 2, 9, false)  \
+    X(11, 160, 256, 64, 3, 1, 4, 12, true) \
+    X(12, 160, 256, 32, 2, 1, 2, 12, false) \
+    X(13, 224, 256, 64, 2, 1, 4, 12, false) \
+    X(14, 256, 256, 64, 2, 1, 4, 12, false)
 
 hipError_t grouped_gemm_init()
 {
     hipError_t e;
-#define X(id, BM, BN, BK, ST, WGM, WGN, FB) if ((e = raise_all<BM, BN, BK, ST, WGM, WGN>()) != hipSuccess) return e;
+#define X(id, BM, BN, BK, ST, WGM, WGN, FB, PK)                                          \
+    if ((e = raise_all<BM, BN, BK, ST, WGM, WGN, false>()) != hipSuccess) return e;      \
+    if constexpr (PK) if ((e = raise_all<BM, BN, BK, ST, WGM, WGN, PK>()) != hipSuccess) return e;
     MOE_EP_VARIANTS(X)
 #undef X
     return hipSuccess;
@@ -661,7 +670,7 @@ hipError_t grouped_gemm_init()
 bool grouped_gemm_variant_shape(int variant, int K, bool ragged, int G, int shape[6])
 {
     switch (variant) {
-#define X(id, BM, BN, BK, ST, WGM, WGN, FB)                                                          \
+#define X(id, BM, BN, BK, ST, WGM, WGN, FB, PK)                                                      \
         case id:                                                                                    \
             if (K / BK < ST || GemmCfg<BM, BN, BK, ST, WGM, WGN, false>::LDS_BYTES +                \
                                        lds_table_bytes(ragged, G) > kLdsPerWorkgroup) {              \
@@ -682,18 +691,60 @@ hipError_t launch_grouped_gemm(const GemmArgs& a, bool swiglu, int variant, int 
     if (a.K < 64 || a.K % 64) return hipErrorInvalidValue;
     if (a.offset ? max_rows <= 0 : a.dense_rows <= 0) return hipSuccess;
     switch (variant) {
-#define X(id, BM, BN, BK, ST, WGM, WGN, FB)                                                          \
+#define X(id, BM, BN, BK, ST, WGM, WGN, FB, PK)                                                      \
         case id:                                                                                    \
             if (a.K / BK < ST || GemmCfg<BM, BN, BK, ST, WGM, WGN, false>::LDS_BYTES +              \
                                          lds_table_bytes(a.offset != nullptr, a.G) > kLdsPerWorkgroup) { \
                 if (FB == id) return hipErrorInvalidValue;                                          \
                 return launch_grouped_gemm(a, swiglu, FB, n_cu, max_rows, s);                  \
             }                                                                                       \
-            return launch_cfg<BM, BN, BK, ST, WGM, WGN>(a, swiglu, n_cu, max_rows, s);
+            return launch_cfg<BM, BN, BK, ST, WGM, WGN, PK>(a, swiglu, n_cu, max_rows, s);
         MOE_EP_VARIANTS(X)
 #undef X
         default: return hipErrorInvalidValue;
     }
+}
+
+// ---- weights in tile order (kernels.h)
+__global__ __launch_bounds__(256) void pack_weights_kernel(GemmArgs a, bool swiglu, uint4* __restrict__ dst, size_t chunks)
+{
+    const int bn_out = swiglu ? kPackRows / 2 : kPackRows;
+    const int NT = (a.N + bn_out - 1) / bn_out, KT = a.K / kPackK;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < chunks; i += (size_t)gridDim.x * blockDim.x) {
+        const int c = (int)(i % 8);                       // 16-byte chunk of the 128-byte row
+        size_t r = i / 8;
+        const int jw = (int)(r % kPackRows); r /= kPackRows;
+        const int ks = (int)(r % KT); r /= KT;
+        const int nt = (int)(r % NT);
+        const int g = (int)(r / NT);
+        int n = nt * bn_out + jw;
+        long long base = 0;
+        if (swiglu && jw >= kPackRows / 2) { n = nt * bn_out + jw - kPackRows / 2; base = a.w_up_offset; }
+        n = min(n, a.N - 1);
+        const int k = ks * kPackK + c * 8;
+        const int seg = k / a.kseg_len;
+        const uint16_t* src = a.W + (size_t)g * a.w_group_stride + base + (size_t)n * a.ldw +
+                              (size_t)seg * a.w_kseg_stride + (k - seg * a.kseg_len);
+        dst[i] = *reinterpret_cast<const uint4*>(src);
+    }
+}
+
+size_t packed_weight_elems(const GemmArgs& a, bool swiglu)
+{
+    const int bn_out = swiglu ? kPackRows / 2 : kPackRows;
+    const size_t NT = (a.N + bn_out - 1) / bn_out;
+    return (size_t)a.G * NT * kPackRows * (size_t)a.K;
+}
+
+hipError_t launch_pack_weights(const GemmArgs& a, bool swiglu, uint16_t* dst, int grid, hipStream_t s)
+{
+    if (a.K < kPackK || a.K % kPackK || a.kseg_len % 8 || a.ldw % 8 || a.w_group_stride % 8 || a.w_up_offset % 8 ||
+        a.w_kseg_stride % 8 || (reinterpret_cast<uintptr_t>(a.W) & 15) || (reinterpret_cast<uintptr_t>(dst) & 15))
+        return hipErrorInvalidValue;
+    const size_t chunks = packed_weight_elems(a, swiglu) / 8;
+    if (chunks == 0) return hipSuccess;
+    hipLaunchKernelGGL(pack_weights_kernel, dim3(grid), dim3(256), 0, s, a, swiglu, reinterpret_cast<uint4*>(dst), chunks);
+    return hipGetLastError();
 }
 
 }  // namespace moe_ep

@@ -67,7 +67,17 @@ struct GemmArgs {
     int epi;
     const float* row_weight;
     const int32_t* row_assignment;
+    // optional: the same weights in tile order (pack_weights), or NULL.  Used by the variants whose
+    // weight tile is kPackRows rows by kPackK reduction steps; the others read W.
+    const uint16_t* Wp;
 };
+// Weights in tile order: for every group, column tile and K step of kPackK, the kPackRows x kPackK
+// block the GEMM's weight tile holds at that step (SwiGLU: kPackRows / 2 rows of W_gate, then the
+// matching rows of W_up; rows past N repeat row N - 1), contiguous (32 KB), blocks in (group, column
+// tile, K step) order.  a.W etc. describe the source as for a launch; a.Wp is ignored.
+constexpr int kPackRows = 256, kPackK = 64;
+size_t packed_weight_elems(const GemmArgs& a, bool swiglu);
+hipError_t launch_pack_weights(const GemmArgs& a, bool swiglu, uint16_t* dst, int grid, hipStream_t s);
 // variant: index into the tile-shape table of grouped_gemm.hip; max_rows: ragged mode, an upper
 // bound of the rows of all groups together (the kernel cuts them into row tiles itself, from
 // `offset`; the bound only sizes the grid); ignored in dense mode

@@ -53,6 +53,10 @@ struct moe_ep_ctx {
     int link_threads = 64, link_unroll = 2;
     bool memcpy_in = false, memcpy_out = false;  // host-link copies through the runtime instead of kernels
     bool check_spans = true;   // every forward asks the runtime what its pointer arguments point at
+    // Weights in tile order (moe_ep_prepare_weights): copies of the gate/up and of the down weights laid
+    // out the way the GEMM's weight tiles read them, owned by the context, keyed by the caller's pointer
+    struct Prepared { const void* key; uint16_t* up; uint16_t* down; };
+    std::vector<Prepared> prepared_routed, prepared_shared;
     // device workspaces
     void* d_tokens = nullptr; float* d_logits = nullptr; void* d_out = nullptr;  // pinned-host mode staging
     int32_t* idx = nullptr; float* w = nullptr; int32_t* pos = nullptr; int32_t* perm = nullptr;
@@ -382,6 +386,8 @@ int moe_ep_destroy(moe_ep_ctx* ctx)
     if (ctx->s_in) (void)hipStreamDestroy(ctx->s_in);
     if (ctx->s_out) (void)hipStreamDestroy(ctx->s_out);
     if (ctx->d_tokens) (void)hipFree(ctx->d_tokens);  // one slab holds every workspace
+    for (auto* v : {&ctx->prepared_routed, &ctx->prepared_shared})
+        for (const moe_ep_ctx::Prepared& p : *v) { (void)hipFree(p.up); (void)hipFree(p.down); }
     delete ctx;
     return MOE_EP_OK;
 }
@@ -522,6 +528,32 @@ namespace {
 
 // The tokens of a forward are cut into r_1 micro-batches of ceil(T / r_1) tokens and every
 // micro-batch into r_2 chunks of ceil(micro-batch / r_2) tokens (Sec. 2.3); chunk c = i * r_2 + j.
+// the weight side of the four projections' launches: [0] routed gate/up, [1] routed down, [2] shared
+// gate/up, [3] shared down (what a launch and the tile-order copy both need)
+void weight_args(const moe_ep_config& c, const void* routed_w, const void* shared_w, GemmArgs g[4])
+{
+    const int M = c.hidden, H = c.inter, El = c.n_local, Ns = c.n_shared, Hs = c.shared_inter;
+    const uint16_t* rw = static_cast<const uint16_t*>(routed_w);
+    const uint16_t* sw = static_cast<const uint16_t*>(shared_w);
+    for (int i = 0; i < 4; ++i) g[i] = GemmArgs{};
+    g[0].W = rw; g[0].G = El; g[0].K = M; g[0].N = H; g[0].ldw = M;
+    g[0].w_group_stride = (long long)3 * H * M; g[0].w_up_offset = (long long)H * M;
+    g[0].kseg_len = M; g[0].w_kseg_stride = 0;
+    g[1].W = rw ? rw + (size_t)2 * H * M : nullptr; g[1].G = El; g[1].K = H; g[1].N = M; g[1].ldw = H;
+    g[1].w_group_stride = (long long)3 * H * M; g[1].w_up_offset = 0; g[1].kseg_len = H; g[1].w_kseg_stride = 0;
+    g[2].W = sw; g[2].G = Ns; g[2].K = M; g[2].N = Hs; g[2].ldw = M;
+    g[2].w_group_stride = (long long)3 * Hs * M; g[2].w_up_offset = (long long)Hs * M;
+    g[2].kseg_len = M; g[2].w_kseg_stride = 0;
+    g[3].W = sw ? sw + (size_t)2 * Hs * M : nullptr; g[3].G = 1; g[3].K = Ns * Hs; g[3].N = M; g[3].ldw = Hs;
+    g[3].w_group_stride = 0; g[3].w_up_offset = 0; g[3].kseg_len = Hs > 0 ? Hs : 1; g[3].w_kseg_stride = (long long)3 * Hs * M;
+}
+
+const moe_ep_ctx::Prepared* find_prepared(const std::vector<moe_ep_ctx::Prepared>& v, const void* key)
+{
+    for (const moe_ep_ctx::Prepared& p : v) if (p.key == key) return &p;
+    return nullptr;
+}
+
 void chunk_range(int T, int r_1, int r_2, int c, int* t0, int* Tn)
 {
     const int Tm = (T + r_1 - 1) / r_1, i = c / r_2, j = c % r_2;
@@ -609,24 +641,34 @@ int forward_impl(moe_ep_ctx* ctx, const void* tokens, const float* gate_logits, 
     if (dep) HIP_TRY(ctx, hipStreamWaitEvent(s_ag, ctx->ev_start, 0));
     const int bw_grid = n_cu * 8;  // bandwidth kernels: 8 workgroups of 4 wavefronts per CU
 
+    GemmArgs w_args[4];   // the weight side of the four projections
+    weight_args(c, routed_w, shared_w, w_args);
+    auto shared_up_w = [&](GemmArgs& g) { g = w_args[2]; };
+    auto shared_down_w = [&](GemmArgs& g) { g = w_args[3]; };
+    auto routed_up_w = [&](GemmArgs& g) { g = w_args[0]; };
+    auto routed_down_w = [&](GemmArgs& g) { g = w_args[1]; };
+    // weights the caller has had laid out in tile order
+    const moe_ep_ctx::Prepared* prep_r = find_prepared(ctx->prepared_routed, routed_w);
+    const moe_ep_ctx::Prepared* prep_s = Ns > 0 ? find_prepared(ctx->prepared_shared, shared_w) : nullptr;
+
     // shared experts of token range [t0, t0+Tn) -> output rows [t0, t0+Tn); the aggregation adds to them
     auto run_shared = [&](int t0, int Tn, hipStream_t st) -> int {
         if (Tn <= 0) return MOE_EP_OK;
         GemmArgs g1{};
-        g1.A = tok_dev + (size_t)t0 * M; g1.W = sw; g1.C = ctx->hs + (size_t)t0 * Ns * Hs;
-        g1.offset = nullptr; g1.G = Ns; g1.dense_rows = Tn;
-        g1.K = M; g1.N = Hs; g1.lda = M; g1.ldc = Ns * Hs; g1.ldw = M;
-        g1.w_group_stride = (long long)3 * Hs * M; g1.w_up_offset = (long long)Hs * M;
-        g1.kseg_len = M; g1.w_kseg_stride = 0; g1.c_group_col_stride = Hs;
+        shared_up_w(g1);
+        g1.Wp = prep_s ? prep_s->up : nullptr;
+        g1.A = tok_dev + (size_t)t0 * M; g1.C = ctx->hs + (size_t)t0 * Ns * Hs;
+        g1.offset = nullptr; g1.dense_rows = Tn;
+        g1.lda = M; g1.ldc = Ns * Hs; g1.c_group_col_stride = Hs;
         int sp = prof_begin(ctx, prof, ST_SGEMM1, st);
         HIP_TRY(ctx, launch_grouped_gemm(g1, true, ctx->shared_variant, n_cu, 0, st));
         prof_end(ctx, sp, st);
         GemmArgs g2{};
-        g2.A = ctx->hs + (size_t)t0 * Ns * Hs; g2.W = sw + (size_t)2 * Hs * M; g2.C = out_dev + (size_t)t0 * M;
-        g2.offset = nullptr; g2.G = 1; g2.dense_rows = Tn;
-        g2.K = Ns * Hs; g2.N = M; g2.lda = Ns * Hs; g2.ldc = M; g2.ldw = Hs;
-        g2.w_group_stride = 0; g2.w_up_offset = 0;
-        g2.kseg_len = Hs; g2.w_kseg_stride = (long long)3 * Hs * M; g2.c_group_col_stride = 0;
+        shared_down_w(g2);
+        g2.Wp = prep_s ? prep_s->down : nullptr;
+        g2.A = ctx->hs + (size_t)t0 * Ns * Hs; g2.C = out_dev + (size_t)t0 * M;
+        g2.offset = nullptr; g2.dense_rows = Tn;
+        g2.lda = Ns * Hs; g2.ldc = M; g2.c_group_col_stride = 0;
         sp = prof_begin(ctx, prof, ST_SGEMM2, st);
         HIP_TRY(ctx, launch_grouped_gemm(g2, false, ctx->shared_variant, n_cu, 0, st));
         prof_end(ctx, sp, st);
@@ -751,10 +793,10 @@ int forward_impl(moe_ep_ctx* ctx, const void* tokens, const float* gate_logits, 
         const long long a_max = (long long)Tn * k;  // the most rows the routing can keep
 
         GemmArgs g1{};
-        g1.A = ctx->xp; g1.W = rw; g1.C = ctx->h; g1.offset = offset;
-        g1.G = El; g1.dense_rows = 0; g1.K = M; g1.N = H; g1.lda = M; g1.ldc = H; g1.ldw = M;
-        g1.w_group_stride = (long long)3 * H * M; g1.w_up_offset = (long long)H * M;
-        g1.kseg_len = M; g1.w_kseg_stride = 0; g1.c_group_col_stride = 0;
+        routed_up_w(g1);
+        g1.Wp = prep_r ? prep_r->up : nullptr;
+        g1.A = ctx->xp; g1.C = ctx->h; g1.offset = offset;
+        g1.dense_rows = 0; g1.lda = M; g1.ldc = H; g1.c_group_col_stride = 0;
         g1.max_units = ctx->up_units;
         if (fused) {  // the projection reads the token rows through the row -> assignment map
             g1.A = tok_dev + (size_t)t0 * M; g1.a_row_map = perm; g1.a_row_div = k; g1.a_src_rows = Tn;
@@ -764,10 +806,10 @@ int forward_impl(moe_ep_ctx* ctx, const void* tokens, const float* gate_logits, 
         prof_end(ctx, sp, s_comp);
 
         GemmArgs g2{};
-        g2.A = ctx->h; g2.W = rw + (size_t)2 * H * M; g2.C = ctx->y; g2.offset = offset;
-        g2.G = El; g2.dense_rows = 0; g2.K = H; g2.N = M; g2.lda = H; g2.ldc = M; g2.ldw = H;
-        g2.w_group_stride = (long long)3 * H * M; g2.w_up_offset = 0;
-        g2.kseg_len = H; g2.w_kseg_stride = 0; g2.c_group_col_stride = 0;
+        routed_down_w(g2);
+        g2.Wp = prep_r ? prep_r->down : nullptr;
+        g2.A = ctx->h; g2.C = ctx->y; g2.offset = offset;
+        g2.dense_rows = 0; g2.lda = H; g2.ldc = M; g2.c_group_col_stride = 0;
         g2.max_units = ctx->down_units;
         g2.epi = ctx->y_mode; g2.row_weight = w; g2.row_assignment = perm;
         sp = prof_begin(ctx, prof, ST_GEMM2, s_comp);
@@ -876,6 +918,85 @@ int moe_ep_forward(moe_ep_ctx* ctx, const void* tokens, const float* gate_logits
     }
     return forward_impl(ctx, tokens, gate_logits, routed_w, shared_w, top_k, 1, r_chunks, order, false, 0.0,
                         n_tokens, out, stream);
+}
+
+size_t moe_ep_prepared_weight_bytes(const moe_ep_config* cfg, int32_t routed, int32_t shared)
+{
+    if (moe_ep_validate_config(cfg, nullptr) != MOE_EP_OK) return 0;
+    if (cfg->hidden % kPackK || cfg->inter % kPackK || (cfg->n_shared > 0 && cfg->shared_inter % kPackK)) return 0;
+    GemmArgs g[4];
+    weight_args(*cfg, nullptr, nullptr, g);
+    size_t bytes = 0;
+    if (routed) bytes += align256(packed_weight_elems(g[0], true) * 2) + align256(packed_weight_elems(g[1], false) * 2);
+    if (shared && cfg->n_shared > 0)
+        bytes += align256(packed_weight_elems(g[2], true) * 2) + align256(packed_weight_elems(g[3], false) * 2);
+    return bytes;
+}
+
+int moe_ep_prepare_weights(moe_ep_ctx* ctx, const void* routed_w, const void* shared_w, void* stream)
+{
+    if (!ctx) return MOE_EP_EINVAL;
+    const moe_ep_config& c = ctx->cfg;
+    if (!routed_w && !shared_w) return fail(ctx, MOE_EP_EINVAL, "moe_ep_prepare_weights: no weights given");
+    if (shared_w && c.n_shared == 0) return fail(ctx, MOE_EP_EINVAL, "moe_ep_prepare_weights: shared_w without shared experts");
+    if (c.hidden % kPackK || c.inter % kPackK || (c.n_shared > 0 && c.shared_inter % kPackK))
+        return fail(ctx, MOE_EP_EINVAL, "moe_ep_prepare_weights: hidden, inter and shared_inter must be multiples of 64");
+    HIP_TRY(ctx, hipSetDevice(c.device));
+    if (ctx->check_spans) {
+        const size_t rb = (size_t)c.n_local * 3 * c.inter * c.hidden * 2, sb = (size_t)c.n_shared * 3 * c.shared_inter * c.hidden * 2;
+        const void* dev = nullptr;
+        if (routed_w) if (const char* bad = check_span(routed_w, rb, false, &dev)) {
+            snprintf(ctx->err, sizeof ctx->err, "routed_w %s", bad);
+            return MOE_EP_EINVAL;
+        }
+        if (shared_w) if (const char* bad = check_span(shared_w, sb, false, &dev)) {
+            snprintf(ctx->err, sizeof ctx->err, "shared_w %s", bad);
+            return MOE_EP_EINVAL;
+        }
+    }
+    GemmArgs g[4];
+    weight_args(c, routed_w, shared_w, g);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    auto prepare = [&](std::vector<moe_ep_ctx::Prepared>& table, const void* key, const GemmArgs& up, const GemmArgs& down) -> int {
+        moe_ep_ctx::Prepared* p = nullptr;
+        for (moe_ep_ctx::Prepared& q : table) if (q.key == key) p = &q;
+        if (!p) {
+            moe_ep_ctx::Prepared n{key, nullptr, nullptr};
+            if (hipMalloc(reinterpret_cast<void**>(&n.up), packed_weight_elems(up, true) * 2) != hipSuccess ||
+                hipMalloc(reinterpret_cast<void**>(&n.down), packed_weight_elems(down, false) * 2) != hipSuccess) {
+                (void)hipGetLastError();
+                if (n.up) (void)hipFree(n.up);
+                return fail(ctx, MOE_EP_ENOMEM, "moe_ep_prepare_weights: no device memory for the copy");
+            }
+            table.push_back(n);
+            p = &table.back();
+        }
+        HIP_TRY(ctx, launch_pack_weights(up, true, p->up, ctx->n_cu * 8, s));
+        HIP_TRY(ctx, launch_pack_weights(down, false, p->down, ctx->n_cu * 8, s));
+        return MOE_EP_OK;
+    };
+    if (routed_w) { const int rc = prepare(ctx->prepared_routed, routed_w, g[0], g[1]); if (rc != MOE_EP_OK) return rc; }
+    if (shared_w) { const int rc = prepare(ctx->prepared_shared, shared_w, g[2], g[3]); if (rc != MOE_EP_OK) return rc; }
+    return MOE_EP_OK;
+}
+
+int moe_ep_forget_weights(moe_ep_ctx* ctx, const void* routed_w, const void* shared_w)
+{
+    if (!ctx) return MOE_EP_EINVAL;
+    HIP_TRY(ctx, hipSetDevice(ctx->cfg.device));
+    HIP_TRY(ctx, hipDeviceSynchronize());   // no kernel may still be reading a copy
+    const bool all = !routed_w && !shared_w;
+    auto drop = [&](std::vector<moe_ep_ctx::Prepared>& table, const void* key) {
+        for (size_t i = 0; i < table.size();) {
+            if (all || table[i].key == key) {
+                (void)hipFree(table[i].up); (void)hipFree(table[i].down);
+                table.erase(table.begin() + i);
+            } else ++i;
+        }
+    };
+    if (all || routed_w) drop(ctx->prepared_routed, routed_w);
+    if (all || shared_w) drop(ctx->prepared_shared, shared_w);
+    return MOE_EP_OK;
 }
 
 int moe_ep_forward_dep(moe_ep_ctx* ctx, const void* tokens, const float* gate_logits,

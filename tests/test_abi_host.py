@@ -54,6 +54,25 @@ def test_valid_config_and_workspace_size():
     assert pkg.workspace_bytes(_good(hidden=100)) == 0
 
 
+def test_size_of_the_tile_order_weight_copies():
+    """Per expert and projection: output rows rounded up to whole weight tiles (gate/up: 128 activation
+    columns = 256 weight rows per tile; down: 256 rows) times the reduction length, bf16."""
+    from paper_2512_21487_amd.binding import prepared_weight_bytes
+    cfg = _good(hidden=320, inter=192, n_experts=8, n_local=5, n_shared=2, shared_inter=192)
+    up = 5 * 2 * 256 * 320 * 2          # 192 activation columns = 2 tiles of 128
+    down = 5 * 2 * 256 * 192 * 2        # 320 output columns = 2 tiles of 256
+    s_up = 2 * 2 * 256 * 320 * 2
+    s_down = 2 * 256 * (2 * 192) * 2    # one group over the concatenated intermediate
+    assert prepared_weight_bytes(cfg, True, False) == up + down
+    assert prepared_weight_bytes(cfg, False, True) == s_up + s_down
+    assert prepared_weight_bytes(cfg, True, True) == up + down + s_up + s_down
+    assert prepared_weight_bytes(_good(n_shared=0, shared_inter=0), False, True) == 0
+    assert prepared_weight_bytes(_good(hidden=100)) == 0
+    # full tiles: exactly the size of the weights
+    big = _good(hidden=5120, inter=1536, n_experts=160, n_local=20, n_shared=2, shared_inter=1536, max_tokens=16384, max_top_k=6)
+    assert prepared_weight_bytes(big) == (20 + 2) * 3 * 1536 * 5120 * 2
+
+
 @pytest.mark.parametrize("kw,word", [
     (dict(hidden=100), "hidden"), (dict(hidden=0), "hidden"), (dict(inter=96), "inter"),
     (dict(n_experts=0), "n_experts"), (dict(n_experts=513, n_local=8), "n_experts"),

@@ -206,7 +206,9 @@ def test_layers_back_to_back_give_the_bits_of_lone_forwards(dep):
         torch.cuda.synchronize()
         lone.append(out)
         x = out
-    # the same chain enqueued at once
+    # the same chain enqueued at once, every layer's weights now read from a tile-order copy
+    for l in range(L):
+        ctx.prepare_weights(d[l].routed, d[l].shared)
     outs = [torch.zeros_like(x0) for _ in range(L)]
 
     def chain():

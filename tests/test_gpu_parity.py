@@ -49,7 +49,8 @@ def _check_routing(ctx, ref, r, T, k):
             assert np.max(np.abs(got["w"].astype(np.float64) - ref["w"][t0:t0 + Tn])) <= W_TOL
 
 
-def _full_parity(wl, seed=0, r=1, order=0, mutate=None):
+def _full_parity(wl, seed=0, r=1, order=0, mutate=None, prepared=False):
+    """prepared: the forward reads tile-order copies of the weights (moe_ep_prepare_weights)."""
     g = _gpu()
     inp = make_inputs(wl, seed=seed)
     if mutate:
@@ -60,6 +61,8 @@ def _full_parity(wl, seed=0, r=1, order=0, mutate=None):
     ref = _oracle_full(inp, wl, r)
     ctx = g.make_ctx(wl, max_chunks=max(r, 1))
     d = g.DeviceInputs(wl, inp)
+    if prepared:
+        ctx.prepare_weights(d.routed, d.shared)
     out = g.run_forward(ctx, wl, d, r=r, order=order)
     _check_routing(ctx, ref, r, wl.n_tokens, wl.top_k)
     err, err_all = rel_err_rows(bf16_bits_to_f32(out), ref["out"]), rel_err(bf16_bits_to_f32(out), ref["out"])
@@ -192,19 +195,22 @@ def test_maximum_expert_count_and_top_k():
     _full_parity(wl, seed=28)
 
 
+@pytest.mark.parametrize("prepared", [False, True])
 @pytest.mark.parametrize("variant", [0, 1, 2, 6, 8, 9, 11, 12, 13, 14])
 @pytest.mark.parametrize("hidden", [64, 128, 192, 320])
-def test_every_tile_variant_matches_oracle(variant, hidden):
+def test_every_tile_variant_matches_oracle(variant, hidden, prepared):
     """Each instantiated tile shape / ring depth of the grouped GEMM (11, 12: 160-row tiles held by 1 x 4
     and 1 x 2 wavefronts; 13, 14: 224- and 256-row tiles held by 1 x 4), for the routed and the shared experts, on K extents of one, two, three and five 64-wide
     steps (shortest pipelines, fallbacks to the 32-wide variants included) with ragged row and column
-    tails."""
+    tails.  prepared: with tile-order copies of the weights, which variants 1, 2 and 11 read (with a
+    column tail: 320 and 192 output columns in tiles of 128 and 256) and the others, and every fallback
+    for a short K, ignore."""
     wl = tiny_workload(name=f"v{variant}_M{hidden}", n_tokens=333, hidden=hidden, inter=320, n_experts=6,
                        n_local=6, top_k=2, n_shared=1, shared_inter=192)
     old = {k: os.environ.get(k) for k in ("MOE_EP_GEMM_VARIANT", "MOE_EP_SHARED_VARIANT")}
     os.environ["MOE_EP_GEMM_VARIANT"] = os.environ["MOE_EP_SHARED_VARIANT"] = str(variant)
     try:
-        _full_parity(wl, seed=29)
+        _full_parity(wl, seed=29, prepared=prepared)
     finally:
         for k, v in old.items():
             if v is None:
@@ -257,6 +263,56 @@ def test_tile_shape_does_not_change_a_bit():
     assert outs[None].any()
     for variant, out in outs.items():
         assert np.array_equal(out, outs[None]), f"tile variant {variant} changed output bits"
+
+
+def test_weights_in_tile_order_give_the_same_bits():
+    """moe_ep_prepare_weights: the copy only changes where the weight tiles are read from, so the bits are
+    those of the forward that reads the caller's layout -- routed weights alone, shared alone, both, a
+    second set of weights beside the first, a refresh after the caller has rewritten the weights in
+    place, and after moe_ep_forget_weights."""
+    g = _gpu()
+    wl = tiny_workload(name="tile_order", n_tokens=900, hidden=320, inter=192, n_experts=10, local_begin=3,
+                       n_local=5, top_k=3, n_shared=2, shared_inter=192)
+    inp = make_inputs(wl, seed=51)
+    d = g.DeviceInputs(wl, inp)
+    ctx = g.make_ctx(wl, max_chunks=4)
+    base = g.run_forward(ctx, wl, d)
+    ref = _oracle_full(inp, wl)
+    assert rel_err_rows(bf16_bits_to_f32(base), ref["out"]) <= TOL
+    assert ctx.prepared_weight_bytes() > 0
+    for what in ("routed", "shared", "both"):
+        ctx.prepare_weights(d.routed if what != "shared" else None, d.shared if what != "routed" else None)
+        for r, order in ((1, 0), (3, 1)):
+            assert np.array_equal(g.run_forward(ctx, wl, d, r=r, order=order), base), f"{what} r={r} changed the bits"
+        assert np.array_equal(g.run_forward_dep(ctx, wl, d, r_1=2, r_2=2, dep_order=0, attn_us=20.0), base)
+        ctx.forget_weights()
+    # a second set of weights prepared beside the first: each forward reads the copy of its own pointer
+    inp2 = make_inputs(wl, seed=52)
+    d2 = g.DeviceInputs(wl, inp2)
+    base2 = g.run_forward(ctx, wl, d2)
+    assert not np.array_equal(base2, base)
+    ctx.prepare_weights(d.routed, d.shared)
+    ctx.prepare_weights(d2.routed, d2.shared)
+    assert np.array_equal(g.run_forward(ctx, wl, d), base)
+    assert np.array_equal(g.run_forward(ctx, wl, d2), base2)
+    # the caller rewrites the first set in place and prepares it again: the copy follows
+    d.routed.copy_(d2.routed)
+    d.shared.copy_(d2.shared)
+    ctx.prepare_weights(d.routed, d.shared)
+    d.tokens.copy_(d2.tokens)
+    d.logits.copy_(d2.logits)
+    assert np.array_equal(g.run_forward(ctx, wl, d), base2)
+    ctx.forget_weights(d.routed, d.shared)
+    assert np.array_equal(g.run_forward(ctx, wl, d), base2)
+    assert np.array_equal(g.run_forward(ctx, wl, d2), base2)
+    with pytest.raises(pkg_error()):               # nothing to prepare
+        ctx.prepare_weights(None, None)
+    ctx.destroy()
+
+
+def pkg_error():
+    import paper_2512_21487_amd as pkg
+    return pkg.MoeEpError
 
 
 @pytest.mark.parametrize("variant,units", [(14, 0), (14, 7), (14, 3), (14, 1), (2, 0), (2, 3), (2, 1), (13, 5), (11, 2),
@@ -628,7 +684,8 @@ def test_device_probe_reports_plausible_rates():
 
 # ------------------------------------------------------------------ full-size configurations
 def _full_size_parity(name, variants, pinned=False, seed=0, tile_variants=()):
-    """At the benchmark's sizes and in the launch configuration bench.py times: the whole layer is
+    """At the benchmark's sizes and in the launch configuration bench.py times (weights prepared in tile
+    order): the whole layer is
     run once on the CPU oracle and EVERY output element is compared with it (so every expert's first
     and last row and every row-tile edge is covered, whatever tile the library picks); routing of
     every token and chunk bit-exact; every (r, order) variant and every listed tile variant
@@ -644,6 +701,7 @@ def _full_size_parity(name, variants, pinned=False, seed=0, tile_variants=()):
     assert int(ref["offset"][0][-1]) == int(local.sum())
     ctx = g.make_ctx(wl, pinned=pinned)
     d = g.DeviceInputs(wl, inp, pinned=pinned)
+    ctx.prepare_weights(d.routed, d.shared)        # as bench.py does: the weights are read in tile order
     first = None
     for r, order in variants:
         print(f"[case] {name} r={r} order={order} pinned={pinned}", flush=True)
@@ -678,6 +736,9 @@ def _full_size_parity(name, variants, pinned=False, seed=0, tile_variants=()):
             first = out
         else:
             assert np.array_equal(out, first), f"r={r} order={order} changed the output bits"
+    ctx.forget_weights()                           # the weights read where the caller keeps them: the same bits
+    print(f"[case] {name} weights in the caller's layout", flush=True)
+    assert np.array_equal(g.run_forward(ctx, wl, d, r=variants[0][0], order=variants[0][1]), first)
     ctx.destroy()
     for tv in tile_variants:                       # told to use one tile shape: the same bits
         print(f"[case] {name} tile variant {tv}", flush=True)
