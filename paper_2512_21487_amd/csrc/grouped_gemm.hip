@@ -667,7 +667,7 @@ hipError_t grouped_gemm_init()
     return hipSuccess;
 }
 
-bool grouped_gemm_variant_shape(int variant, int K, bool ragged, int G, int shape[6])
+bool grouped_gemm_variant_shape(int variant, int K, bool ragged, int G, int shape[7])
 {
     switch (variant) {
 #define X(id, BM, BN, BK, ST, WGM, WGN, FB, PK)                                                      \
@@ -678,6 +678,7 @@ bool grouped_gemm_variant_shape(int variant, int K, bool ragged, int G, int shap
                 return grouped_gemm_variant_shape(FB, K, ragged, G, shape);                         \
             }                                                                                       \
             shape[0] = BM; shape[1] = BN; shape[2] = BK; shape[3] = ST; shape[4] = WGM; shape[5] = WGN; \
+            shape[6] = PK;                                                                          \
             return true;
         MOE_EP_VARIANTS(X)
 #undef X

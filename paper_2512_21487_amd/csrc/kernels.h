@@ -85,8 +85,9 @@ hipError_t launch_grouped_gemm(const GemmArgs& a, bool swiglu, int variant, int 
                                long long max_rows, hipStream_t s);
 hipError_t grouped_gemm_init();   // raises the dynamic-LDS limit of every instantiation once
 // the shape a launch of `variant` really runs (after the fall-backs for a short K or many groups):
-// shape[] = tallest tile rows, weight rows per tile, K step, ring slots, wavefronts in m, in n;
-// false for an unknown variant
-bool grouped_gemm_variant_shape(int variant, int K, bool ragged, int G, int shape[6]);
+// shape[] = tallest tile rows, weight rows per tile, K step, ring slots, wavefronts in m, in n, and
+// whether it reads weights in tile order when the launch has them (GemmArgs::Wp); false for an
+// unknown variant
+bool grouped_gemm_variant_shape(int variant, int K, bool ragged, int G, int shape[7]);
 
 }  // namespace moe_ep

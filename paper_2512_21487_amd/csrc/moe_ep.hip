@@ -75,6 +75,7 @@ struct moe_ep_ctx {
     std::vector<hipEvent_t> ev_attn, ev_shared;
     // last forward (for moe_ep_get_routing): tokens, top_k, chunks = micro-batches x chunks of each
     int last_T = -1, last_k = 0, last_r = 0, last_r1 = 1;
+    bool last_prepared_routed = false, last_prepared_shared = false;  // it read tile-order copies of the weights
     struct ChunkVariants { int up, down; };
     std::vector<ChunkVariants> last_variants;  // per chunk of the last forward: tile variants of the routed projections
     // stage profiling
@@ -650,6 +651,8 @@ int forward_impl(moe_ep_ctx* ctx, const void* tokens, const float* gate_logits, 
     // weights the caller has had laid out in tile order
     const moe_ep_ctx::Prepared* prep_r = find_prepared(ctx->prepared_routed, routed_w);
     const moe_ep_ctx::Prepared* prep_s = Ns > 0 ? find_prepared(ctx->prepared_shared, shared_w) : nullptr;
+    ctx->last_prepared_routed = prep_r != nullptr;
+    ctx->last_prepared_shared = prep_s != nullptr;
 
     // shared experts of token range [t0, t0+Tn) -> output rows [t0, t0+Tn); the aggregation adds to them
     auto run_shared = [&](int t0, int Tn, hipStream_t st) -> int {
@@ -881,7 +884,8 @@ int32_t moe_ep_routed_tile_rows(const moe_ep_config* cfg, int32_t n_tokens, int3
 }
 
 int moe_ep_last_tile_shape(const moe_ep_ctx* ctx, int32_t chunk, int32_t stage, int32_t* rows, int32_t* cols,
-                           int32_t* k_step, int32_t* ring_slots, int32_t* waves_m, int32_t* waves_n)
+                           int32_t* k_step, int32_t* ring_slots, int32_t* waves_m, int32_t* waves_n,
+                           int32_t* tile_order)
 {
     if (!ctx || stage < ST_GEMM1 || stage > ST_SGEMM2) return MOE_EP_EINVAL;
     if (ctx->last_T < 0) return MOE_EP_ESTATE;
@@ -891,8 +895,9 @@ int moe_ep_last_tile_shape(const moe_ep_ctx* ctx, int32_t chunk, int32_t stage, 
     const moe_ep_config& c = ctx->cfg;
     const int variant = shared ? ctx->shared_variant : (up ? ctx->last_variants[chunk].up : ctx->last_variants[chunk].down);
     const int K = shared ? (up ? c.hidden : c.n_shared * c.shared_inter) : (up ? c.hidden : c.inter);
-    int v[6];
+    int v[7];
     if (!grouped_gemm_variant_shape(variant, K, !shared, shared ? 1 : c.n_local, v)) return MOE_EP_ESTATE;
+    if (tile_order) *tile_order = v[6] && (shared ? ctx->last_prepared_shared : ctx->last_prepared_routed);
     if (rows) *rows = v[0];
     if (cols) *cols = v[1];
     if (k_step) *k_step = v[2];

@@ -279,11 +279,13 @@ def test_weights_in_tile_order_give_the_same_bits():
     base = g.run_forward(ctx, wl, d)
     ref = _oracle_full(inp, wl)
     assert rel_err_rows(bf16_bits_to_f32(base), ref["out"]) <= TOL
-    assert ctx.prepared_weight_bytes() > 0
+    assert ctx.prepared_weight_bytes() > 0 and ctx.last_tile_shape("routed_gate_up_gemm")["tile_order"] == 0
     for what in ("routed", "shared", "both"):
         ctx.prepare_weights(d.routed if what != "shared" else None, d.shared if what != "routed" else None)
         for r, order in ((1, 0), (3, 1)):
             assert np.array_equal(g.run_forward(ctx, wl, d, r=r, order=order), base), f"{what} r={r} changed the bits"
+        assert ctx.last_tile_shape("routed_down_gemm")["tile_order"] == (what != "shared")
+        assert ctx.last_tile_shape("shared_gate_up_gemm")["tile_order"] == (what != "routed")
         assert np.array_equal(g.run_forward_dep(ctx, wl, d, r_1=2, r_2=2, dep_order=0, attn_us=20.0), base)
         ctx.forget_weights()
     # a second set of weights prepared beside the first: each forward reads the copy of its own pointer
