@@ -297,21 +297,35 @@ __device__ __forceinline__ void gemm_tiles(const GemmArgs& a, uint4* lds, const 
         if (packed) Wi = a.Wp + ((size_t)t.g * NT + t.n0 / BN_OUT) * ((size_t)KT * BN * BK);
         else Wi = a.W + (size_t)t.g * a.w_group_stride;
         Xi = mapped ? a.A : a.A + (size_t)t.row0 * a.lda;
+        // activation regions first: the tile row each lane fetches, and with gathered token rows the
+        // row map's entries for all of them in one go (the loads are independent; one wait for the lot
+        // instead of one memory round trip per region in the middle of a K loop)
+        int src_row[XRPW > 0 ? XRPW : 1];
+#pragma unroll
+        for (int i = 0; i < XRPW; ++i) {
+            const int r = (wave + NW * i) * RPR + ld_row;
+            // LDS row r belongs to wavefront row r / WTM, which holds tile rows
+            // [(r / WTM) * hb * 32, +hb * 32); blocks the tile does not have and rows past its
+            // end re-read the last valid row (one cache line for the whole region)
+            const int within = r % Cfg::WTM;
+            int rr = (RAGGED && WGM > 1) ? (r / Cfg::WTM) * t.hb * 32 + within : r;
+            if (RAGGED && within >= t.hb * 32) rr = t.nrows - 1;
+            src_row[i] = min(rr, t.nrows - 1);
+        }
+        if (mapped) {
+#pragma unroll
+            for (int i = 0; i < XRPW; ++i) src_row[i] = a.a_row_map[t.row0 + src_row[i]];
+            asm volatile("" ::: "memory");   // all of them are in flight before the first is used
+#pragma unroll
+            for (int i = 0; i < XRPW; ++i) src_row[i] /= a.a_row_div;
+        }
 #pragma unroll
         for (int i = 0; i < RPW; ++i) {
             const int j = wave + NW * i;                 // region index inside a stage
             const int r = j * RPR + ld_row;              // row in the stacked [activations; weights] tile
             const int c = ld_p ^ ((r / RP) % CPR);       // logical chunk stored at physical slot ld_p
             if (i < XRPW) {
-                // LDS row r belongs to wavefront row r / WTM, which holds tile rows
-                // [(r / WTM) * hb * 32, +hb * 32); blocks the tile does not have and rows past its
-                // end re-read the last valid row (one cache line for the whole region)
-                const int within = r % Cfg::WTM;
-                int rr = (RAGGED && WGM > 1) ? (r / Cfg::WTM) * t.hb * 32 + within : r;
-                if (RAGGED && within >= t.hb * 32) rr = t.nrows - 1;
-                rr = min(rr, t.nrows - 1);
-                if (mapped) rr = a.a_row_map[t.row0 + rr] / a.a_row_div;
-                goff[i] = ((uint32_t)rr * (uint32_t)a.lda + c * 8) * 2u;
+                goff[i] = ((uint32_t)src_row[i < XRPW ? i : 0] * (uint32_t)a.lda + c * 8) * 2u;
             } else {
                 const int jw = r - BM;                   // row of the weight tile
                 int n;
