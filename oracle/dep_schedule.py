@@ -16,6 +16,13 @@ tokens per expert and chunk, r_2 chunks, T layers, ag attention-group size, S se
     a resource takes its tasks is fixed: links and expert group by (layer, micro-batch, chunk); the
     attention group by layer and inside a layer ASAS (a_0 s_0 a_1 s_1 ...) or AASS (a_0 a_1 ... s_0
     s_1 ...), Sec. 4.2 "Determine the order of Attention and Shared Expert";
+  * `replay_one_gpu` is NOT in the paper: it is the same set of rules plus one more, for the stand-in
+    in which the attention group's shared experts and the expert group's routed experts run on the
+    compute units of one GPU (a shared-expert task and an expert task do not overlap).  The rules then
+    no longer fix the schedule (which of two waiting tasks takes the compute units first is a
+    choice), so it is defined by a procedure: of the next unscheduled task of each of the four task
+    sequences, those whose predecessors have been placed are candidates; the one that can start
+    earliest (ties: attention group, A2E, experts, E2A) is placed at that time; repeat;
   * `layer0_times` are the layer-0 start times Sec. 4.2 prints for ASAS, with
     X = t_a + t_s,  Y = max(t_e, t_a2e),  F = max(X, r_2 Y);
   * `objective` is the denominator of Eq. simplify-objective / Eq. solver_r2 for ASAS:
@@ -131,9 +138,79 @@ def replay(mod: TaskModels, p: Problem, m_a: int, r_1: int, r_2: int, order: int
             "makespan": makespan, "t": (t_a, t_s, t_e, t_c)}
 
 
-def check_schedule(sch: Dict[str, object], r_1: int, r_2: int, T: int, tol: float = 1e-9) -> List[str]:
+def ag_sequence(r_1: int, order: int) -> List[Tuple[str, int]]:
+    """One layer of the attention group's fixed task order: ("a" | "s", micro-batch)."""
+    if order == ASAS:
+        return [(kind, i) for i in range(r_1) for kind in ("a", "s")]
+    return [("a", i) for i in range(r_1)] + [("s", i) for i in range(r_1)]
+
+
+def replay_one_gpu(mod: TaskModels, p: Problem, m_a: int, r_1: int, r_2: int, order: int) -> Dict[str, object]:
+    """The schedule of `replay` with one rule more -- shared-expert and expert tasks share one GPU's
+    compute units and do not overlap -- built by the procedure the module header states."""
+    m_e = tokens_per_expert(p, m_a, r_2)
+    t_a, t_s, t_e, t_c = mod.a(m_a), mod.s(m_a), mod.e(m_e), mod.c(m_e)
+    T = p.n_layers
+    seq_ag = [(t, kind, i) for t in range(T) for kind, i in ag_sequence(r_1, order)]
+    seq_ch = [(t, i, j) for t in range(T) for i in range(r_1) for j in range(r_2)]
+    start: Dict[Tuple, float] = {}          # ("a" | "s", t, i) and ("a2e" | "e" | "e2a", t, i, j) -> start time
+    dur = {"a": t_a, "s": t_s, "a2e": t_c, "e": t_e, "e2a": t_c}
+    end = lambda key: start[key] + dur[key[0]]
+    cursor = {"ag": 0, "a2e": 0, "e": 0, "e2a": 0}
+    free = {"ag": 0.0, "a2e": 0.0, "e": 0.0, "e2a": 0.0}
+    free_cu = 0.0                           # the compute units: shared-expert and expert tasks
+
+    def candidate(res: str):
+        """(earliest start, key) of the next task of a sequence, or None if it is exhausted or a
+        predecessor has not been placed."""
+        if res == "ag":
+            if cursor["ag"] == len(seq_ag):
+                return None
+            t, kind, i = seq_ag[cursor["ag"]]
+            if kind == "a":
+                before = [] if t == 0 else [("s", t - 1, i)] + [("e2a", t - 1, i, j) for j in range(r_2)]
+            else:
+                before = [("a", t, i)]
+            key = (kind, t, i)
+        else:
+            if cursor[res] == len(seq_ch):
+                return None
+            t, i, j = seq_ch[cursor[res]]
+            before = {"a2e": [("a", t, i)], "e": [("a2e", t, i, j)], "e2a": [("e", t, i, j)]}[res]
+            key = (res, t, i, j)
+        if any(b not in start for b in before):
+            return None
+        at = max([free[res]] + [end(b) for b in before])
+        if key[0] in ("s", "e"):
+            at = max(at, free_cu)
+        return at, key
+
+    n_tasks = len(seq_ag) + 3 * len(seq_ch)
+    while len(start) < n_tasks:
+        best = None
+        for res in ("ag", "a2e", "e", "e2a"):       # this order breaks ties
+            c = candidate(res)
+            if c is not None and (best is None or c[0] < best[0][0]):
+                best = (c, res)
+        (at, key), res = best
+        start[key] = at
+        free[res] = at + dur[key[0]]
+        if key[0] in ("s", "e"):
+            free_cu = at + dur[key[0]]
+        cursor[res] += 1
+    grid2 = lambda kind: [[start[(kind, t, i)] for i in range(r_1)] for t in range(T)]
+    grid3 = lambda kind: [[[start[(kind, t, i, j)] for j in range(r_2)] for i in range(r_1)] for t in range(T)]
+    out = {"tau_a": grid2("a"), "tau_s": grid2("s"), "tau_a2e": grid3("a2e"), "tau_e": grid3("e"),
+           "tau_e2a": grid3("e2a"), "t": (t_a, t_s, t_e, t_c)}
+    out["makespan"] = max(out["tau_s"][T - 1][r_1 - 1] + t_s, out["tau_e2a"][T - 1][r_1 - 1][r_2 - 1] + t_c)
+    return out
+
+
+def check_schedule(sch: Dict[str, object], r_1: int, r_2: int, T: int, tol: float = 1e-9,
+                   one_gpu: bool = False) -> List[str]:
     """Every rule of Eq. limitation, checked directly on a set of start times (no knowledge of how
-    they were produced).  Returns the list of violated rules (empty = valid)."""
+    they were produced).  one_gpu: also that no shared-expert task overlaps an expert task.
+    Returns the list of violated rules (empty = valid)."""
     t_a, t_s, t_e, t_c = sch["t"]
     bad: List[str] = []
 
@@ -150,6 +227,10 @@ def check_schedule(sch: Dict[str, object], r_1: int, r_2: int, T: int, tol: floa
     exclusive("rule 3 (A2E)", [(sch["tau_a2e"][t][i][j], sch["tau_a2e"][t][i][j] + t_c) for t, i, j in idx])
     exclusive("rule 4 (E2A)", [(sch["tau_e2a"][t][i][j], sch["tau_e2a"][t][i][j] + t_c) for t, i, j in idx])
     exclusive("rule 5 (expert group)", [(sch["tau_e"][t][i][j], sch["tau_e"][t][i][j] + t_e) for t, i, j in idx])
+    if one_gpu:
+        exclusive("one GPU (shared experts / experts)",
+                  [(sch["tau_e"][t][i][j], sch["tau_e"][t][i][j] + t_e) for t, i, j in idx] +
+                  [(sch["tau_s"][t][i], sch["tau_s"][t][i] + t_s) for t in range(T) for i in range(r_1)])
     for t in range(T):
         for i in range(r_1):
             end_a = sch["tau_a"][t][i] + t_a

@@ -66,6 +66,81 @@ def test_replay_obeys_every_rule_and_never_idles_without_cause():
                             assert round(s[k][t][i][j], 9) in ends
 
 
+# ---------------------------------------------------------------- one GPU: shared experts and experts share the compute units
+def test_one_gpu_replay_worked_example():
+    """t_a = 1, t_s = 0.5, t_e = 0.7, t_c = 0.3, two micro-batches of two chunks, one layer, placed by hand
+    with the procedure of the module header."""
+    mod = D.TaskModels(D.Linear(1, 0), D.Linear(0.5, 0), D.Linear(0.7, 0), D.Linear(0.3, 0))
+    p = D.Problem(ag=1, n_experts=8, top_k=1, seq_len=1, n_layers=1)
+    s = D.replay_one_gpu(mod, p, 1, 2, 2, D.ASAS)
+    # a0 0-1, s0 1-1.5 (the experts of chunk (0,0), ready at 1.3, wait for it), a1 1.5-2.5, e(0,0) 1.5-2.2,
+    # e(0,1) 2.2-2.9, s1 waits for it: 2.9-3.4, e(1,0) 3.4-4.1, e(1,1) 4.1-4.8, its E2A ends at 5.1
+    assert s["tau_a"] == [[0.0, 1.5]]
+    assert s["tau_s"][0] == pytest.approx([1.0, 2.9])
+    assert s["tau_a2e"][0] == [pytest.approx([1.0, 1.3]), pytest.approx([2.5, 2.8])]
+    assert s["tau_e"][0] == [pytest.approx([1.5, 2.2]), pytest.approx([3.4, 4.1])]
+    assert s["makespan"] == pytest.approx(5.1)
+    assert D.replay(mod, p, 1, 2, 2, D.ASAS)["makespan"] == pytest.approx(4.5)     # two GPUs: 0.6 less
+    s = D.replay_one_gpu(mod, p, 1, 2, 2, D.AASS)
+    # a0 0-1, a1 1-2, e(0,0) 1.3-2.0, s0 2.0-2.5, s1 2.5-3.0 (the attention group wins ties), e(0,1) 3.0-3.7,
+    # e(1,0) 3.7-4.4, e(1,1) 4.4-5.1, its E2A ends at 5.4
+    assert s["tau_a"] == [[0.0, 1.0]]
+    assert s["tau_s"][0] == pytest.approx([2.0, 2.5])
+    assert s["tau_e"][0] == [pytest.approx([1.3, 3.0]), pytest.approx([3.7, 4.4])]
+    assert s["makespan"] == pytest.approx(5.4)
+
+
+def test_one_gpu_replay_is_valid_late_and_never_idles_without_cause():
+    hit = same = 0
+    for mod, p, m_a, r_1, r_2 in _cases(5, 300, max_layers=4):
+        for order in (D.ASAS, D.AASS):
+            two = D.replay(mod, p, m_a, r_1, r_2, order)
+            one = D.replay_one_gpu(mod, p, m_a, r_1, r_2, order)
+            T = p.n_layers
+            assert D.check_schedule(one, r_1, r_2, T, one_gpu=True) == []
+            # the same task orders under one rule more: nothing starts earlier than with two GPUs
+            t_a, t_s, t_e, t_c = one["t"]
+            ends = {0.0}
+            for t in range(T):
+                for i in range(r_1):
+                    assert one["tau_a"][t][i] >= two["tau_a"][t][i] - 1e-9 and one["tau_s"][t][i] >= two["tau_s"][t][i] - 1e-9
+                    ends.add(round(one["tau_a"][t][i] + t_a, 9)); ends.add(round(one["tau_s"][t][i] + t_s, 9))
+                    for j in range(r_2):
+                        for k in ("tau_a2e", "tau_e", "tau_e2a"):
+                            assert one[k][t][i][j] >= two[k][t][i][j] - 1e-9
+                        ends.add(round(one["tau_a2e"][t][i][j] + t_c, 9)); ends.add(round(one["tau_e"][t][i][j] + t_e, 9))
+                        ends.add(round(one["tau_e2a"][t][i][j] + t_c, 9))
+            for t in range(T):
+                for i in range(r_1):
+                    assert round(one["tau_a"][t][i], 9) in ends and round(one["tau_s"][t][i], 9) in ends
+                    for j in range(r_2):
+                        for k in ("tau_a2e", "tau_e", "tau_e2a"):
+                            assert round(one[k][t][i][j], 9) in ends
+            # all shared-expert and expert work on one set of compute units, after the first attention
+            assert one["makespan"] >= t_a + T * r_1 * (t_s + r_2 * t_e) - 1e-9
+            # where the two-GPU schedule never runs the two kinds at once, the extra rule changes nothing
+            if D.check_schedule(two, r_1, r_2, T, one_gpu=True) == []:
+                same += 1
+                for k in ("tau_a", "tau_s", "tau_a2e", "tau_e", "tau_e2a"):
+                    assert one[k] == two[k]
+            else:
+                hit += 1
+    assert hit > 100 and same > 5
+
+
+def test_one_gpu_single_micro_batch_closed_form():
+    """One micro-batch, one layer: the shared experts start with the first transfer; the experts
+    follow whichever of the two ends later, then run back to back when a chunk's transfer is the
+    shorter task."""
+    p = D.Problem(ag=1, n_experts=8, top_k=1, seq_len=1, n_layers=1)
+    for t_a, t_s, t_e, t_c, r_2 in [(1.0, 0.5, 0.7, 0.3, 3), (1.0, 0.2, 0.7, 0.3, 3), (0.4, 0.9, 0.5, 0.5, 4), (0.0, 2.0, 0.1, 0.1, 2)]:
+        mod = D.TaskModels(D.Linear(t_a, 0), D.Linear(t_s, 0), D.Linear(t_e, 0), D.Linear(t_c, 0))
+        for order in (D.ASAS, D.AASS):
+            s = D.replay_one_gpu(mod, p, 1, 1, r_2, order)
+            assert t_e >= t_c
+            assert s["makespan"] == pytest.approx(t_a + max(t_s, t_c) + r_2 * t_e + t_c)
+
+
 def test_validator_catches_planted_violations():
     mod, p = D.TaskModels(D.Linear(1, 0), D.Linear(0.5, 0), D.Linear(0.7, 0), D.Linear(0.3, 0)), \
         D.Problem(ag=1, n_experts=8, top_k=1, seq_len=8, n_layers=2)
