@@ -475,7 +475,22 @@ def main() -> int:
         # timeline shows, and what the earliest-start replay of Eq. limitation predicts from them
         r_1, r_2, attn_us = dep
         res = {"r_1": r_1, "r_2": r_2, "attn_us": attn_us, "io": "pinned" if pinned else "device",
-               "measured_ms": {}, "model_ms": {}, "tasks_ms": {}}
+               "measured_ms": {}, "model_ms": {}, "bounds_ms": {}, "tasks_ms": {}}
+        # durations of the shared-expert and expert tasks running alone: one micro-batch through the
+        # plain forward (shared experts first, then its r_2 chunks one after the other)
+        T_mb = -(-T // r_1)
+        ctx.set_profiling_stages(None)
+        for _ in range(3):
+            ctx.forward(tokens, logits, routed, shared, k, r_2, 0, n_tokens=T_mb, out=out, stream=stream)
+        ctx.set_profiling(10)
+        for _ in range(10):
+            ctx.forward(tokens, logits, routed, shared, k, r_2, 0, n_tokens=T_mb, out=out, stream=stream)
+        st_mb = ctx.get_stage_ms()
+        ctx.set_profiling(0)
+        alone_ms = {"shared": st_mb["shared_gate_up_gemm"] + st_mb["shared_down_gemm"],
+                    "experts_per_chunk": sum(st_mb[n] for n in ("router", "partition", "routed_gate_up_gemm",
+                                                                 "routed_down_gemm", "aggregation")) / r_2}
+        res["tasks_alone_ms"] = alone_ms
         for name, order in (("ASAS", 0), ("AASS", 1)):
             def dep_step():
                 ctx.forward_dep(tokens, logits, routed, shared, k, r_1, r_2, order, attn_us, n_tokens=T, out=out,
@@ -506,6 +521,15 @@ def main() -> int:
             mod = pkg.DepModels(t_a, 0.0, t_s, 0.0, t_e, 0.0, t_c, 0.0)
             prob = pkg.DepProblem(ag=1, n_experts=wl.n_experts, top_k=k, seq_len=1, n_layers=1)
             res["model_ms"][name] = pkg.dep_replay(mod, prob, 1, r_1, r_2, order)[0]
+            # the same rules plus "shared experts and experts share the compute units", fed with what
+            # the tasks take alone (a plain forward over one micro-batch, chunk by chunk)
+            # two-sided: the replay fed with what the tasks take alone is a lower bound when the groups are
+            # taken as independent (the paper's case) and an upper bound under the extra rule "shared
+            # experts and experts share the compute units and never overlap" (moe_ep_dep_replay_one_gpu);
+            # on one GPU they do overlap, each slower, and the measured makespan lies between the two
+            alone = pkg.DepModels(t_a, 0.0, alone_ms["shared"], 0.0, alone_ms["experts_per_chunk"], 0.0, t_c, 0.0)
+            res["bounds_ms"][name] = {"independent_groups": pkg.dep_replay(alone, prob, 1, r_1, r_2, order)[0],
+                                      "one_gpu_no_overlap": pkg.dep_replay(alone, prob, 1, r_1, r_2, order, one_gpu=True)[0]}
         line["dep_layer"] = res
     if args.layers > 1:
         # layer l > 0 uses a rolled copy of layer 0's weights: distinct memory, same distribution, so no

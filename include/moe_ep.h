@@ -401,6 +401,19 @@ int moe_ep_dep_replay(const moe_ep_dep_models *m, const moe_ep_dep_problem *p, i
                       int32_t r_2, int32_t order, double *makespan, double *tau_a, double *tau_s,
                       double *tau_a2e, double *tau_e, double *tau_e2a);
 
+/*
+ * The same replay for the stand-in in which both groups share one GPU (moe_ep_forward_dep): the rules
+ * of Eq. limitation plus one the paper does not need -- a shared-expert task and an expert task do not
+ * overlap, they run on the same compute units.  The rules then leave open which of two waiting tasks
+ * goes first, so the schedule is the result of a procedure: of the next task of each of the four
+ * sequences, those whose predecessors have been placed are candidates; the one that can start earliest
+ * is placed at that time (ties: attention group, A2E, experts, E2A); repeat.  Arguments and outputs as
+ * for moe_ep_dep_replay; the models' durations are those of the tasks running alone.
+ */
+int moe_ep_dep_replay_one_gpu(const moe_ep_dep_models *m, const moe_ep_dep_problem *p, int32_t m_a, int32_t r_1,
+                      int32_t r_2, int32_t order, double *makespan, double *tau_a, double *tau_s,
+                      double *tau_a2e, double *tau_e, double *tau_e2a);
+
 /* Makespan model of the ASAS order over T layers (Sec. 4.2, denominator of Eq. simplify-objective):
  * (T-1) max(G, r_1 F) + max(X, G) + (r_1 - 1) F.  Negative on bad arguments. */
 double moe_ep_dep_makespan(const moe_ep_dep_models *m, const moe_ep_dep_problem *p, int32_t m_a,

@@ -156,6 +156,8 @@ def load_library() -> ctypes.CDLL:
     lib.moe_ep_dep_tokens_per_expert.argtypes = [pp, i32, i32]
     lib.moe_ep_dep_replay.restype = ctypes.c_int
     lib.moe_ep_dep_replay.argtypes = [mp, pp, i32, i32, i32, i32, dp, dp, dp, dp, dp, dp]
+    lib.moe_ep_dep_replay_one_gpu.restype = ctypes.c_int
+    lib.moe_ep_dep_replay_one_gpu.argtypes = [mp, pp, i32, i32, i32, i32, dp, dp, dp, dp, dp, dp]
     lib.moe_ep_dep_makespan.restype = ctypes.c_double
     lib.moe_ep_dep_makespan.argtypes = [mp, pp, i32, i32, i32]
     lib.moe_ep_dep_solve_r2.restype = ctypes.c_int
@@ -316,14 +318,17 @@ def dep_tokens_per_expert(problem: DepProblem, m_a: int, r_2: int) -> float:
     return float(load_library().moe_ep_dep_tokens_per_expert(ctypes.byref(problem), m_a, r_2))
 
 
-def dep_replay(models: DepModels, problem: DepProblem, m_a: int, r_1: int, r_2: int, order: int):
-    """moe_ep_dep_replay: (makespan, dict of start-time arrays shaped [T, r_1] / [T, r_1, r_2])."""
+def dep_replay(models: DepModels, problem: DepProblem, m_a: int, r_1: int, r_2: int, order: int,
+               one_gpu: bool = False):
+    """moe_ep_dep_replay (one_gpu: moe_ep_dep_replay_one_gpu): (makespan, dict of start-time arrays
+    shaped [T, r_1] / [T, r_1, r_2])."""
     T = problem.n_layers
     tau = {"tau_a": np.empty((T, r_1)), "tau_s": np.empty((T, r_1)), "tau_a2e": np.empty((T, r_1, r_2)),
            "tau_e": np.empty((T, r_1, r_2)), "tau_e2a": np.empty((T, r_1, r_2))}
     span = ctypes.c_double()
     dp = ctypes.POINTER(ctypes.c_double)
-    rc = load_library().moe_ep_dep_replay(
+    fn = load_library().moe_ep_dep_replay_one_gpu if one_gpu else load_library().moe_ep_dep_replay
+    rc = fn(
         ctypes.byref(models), ctypes.byref(problem), m_a, r_1, r_2, order, ctypes.byref(span),
         *(tau[k].ctypes.data_as(dp) for k in ("tau_a", "tau_s", "tau_a2e", "tau_e", "tau_e2a")))
     if rc != 0:

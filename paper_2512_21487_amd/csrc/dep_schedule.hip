@@ -122,6 +122,86 @@ struct Replay {
     }
 };
 
+// The same rules with one more: shared-expert and expert tasks run on one GPU's compute units and do not
+// overlap (the stand-in of moe_ep_forward_dep; not a case the paper treats).  Which of two waiting tasks
+// takes the compute units first is then a choice, so the schedule is defined by a procedure: among the
+// next task of each of the four sequences whose predecessors are placed, the one that can start earliest
+// is placed (ties: attention group, A2E, experts, E2A).  Kept as end times; a task not yet placed has
+// end < 0.
+struct OneGpuReplay {
+    int T, r1, r2;
+    Durations d;
+    std::vector<double> a, s, a2e, e, e2a;   // start times, layouts as in Replay
+
+    double run(int order)
+    {
+        const int n2 = T * r1, n3 = n2 * r2;
+        a.assign(n2, -1.0); s.assign(n2, -1.0); a2e.assign(n3, -1.0); e.assign(n3, -1.0); e2a.assign(n3, -1.0);
+        // position k of a layer's attention-group sequence -> (is shared expert, micro-batch)
+        auto ag_task = [&](int k, bool* shared, int* i) {
+            if (order == MOE_EP_DEP_ASAS) { *shared = (k & 1) != 0; *i = k >> 1; }
+            else { *shared = k >= r1; *i = k % r1; }
+        };
+        const double never = -1.0;
+        int c_ag = 0, c_a2e = 0, c_e = 0, c_e2a = 0;                  // next task of each sequence
+        double f_ag = 0, f_a2e = 0, f_e = 0, f_e2a = 0, f_cu = 0;   // when each resource falls free
+        // earliest start of the next task of each sequence, or `never`
+        auto next_ag = [&]() -> double {
+            if (c_ag == 2 * n2) return never;
+            const int t = c_ag / (2 * r1);
+            bool shared; int i;
+            ag_task(c_ag % (2 * r1), &shared, &i);
+            double at = f_ag;
+            if (shared) {
+                if (a[t * r1 + i] < 0) return never;
+                at = std::fmax(at, a[t * r1 + i] + d.a);
+                at = std::fmax(at, f_cu);
+            } else if (t > 0) {
+                const int q = (t - 1) * r1 + i;
+                if (s[q] < 0 || e2a[q * r2 + r2 - 1] < 0) return never;
+                at = std::fmax(at, s[q] + d.s);
+                for (int j = 0; j < r2; ++j) at = std::fmax(at, e2a[q * r2 + j] + d.c);
+            }
+            return at;
+        };
+        auto next_a2e = [&]() -> double {
+            if (c_a2e == n3 || a[c_a2e / r2] < 0) return never;
+            return std::fmax(f_a2e, a[c_a2e / r2] + d.a);
+        };
+        auto next_e = [&]() -> double {
+            if (c_e == n3 || a2e[c_e] < 0) return never;
+            return std::fmax(std::fmax(f_e, f_cu), a2e[c_e] + d.c);
+        };
+        auto next_e2a = [&]() -> double {
+            if (c_e2a == n3 || e[c_e2a] < 0) return never;
+            return std::fmax(f_e2a, e[c_e2a] + d.e);
+        };
+        for (int placed = 0; placed < 2 * n2 + 3 * n3; ++placed) {
+            const double at[4] = {next_ag(), next_a2e(), next_e(), next_e2a()};
+            int pick = -1;
+            for (int q = 0; q < 4; ++q)
+                if (at[q] >= 0 && (pick < 0 || at[q] < at[pick])) pick = q;
+            if (pick < 0) return -1.0;   // cannot happen: the first unplaced task of some sequence is always ready
+            const double t0 = at[pick];
+            if (pick == 0) {
+                const int t = c_ag / (2 * r1);
+                bool shared; int i;
+                ag_task(c_ag % (2 * r1), &shared, &i);
+                if (shared) { s[t * r1 + i] = t0; f_ag = f_cu = t0 + d.s; }
+                else { a[t * r1 + i] = t0; f_ag = t0 + d.a; }
+                ++c_ag;
+            } else if (pick == 1) {
+                a2e[c_a2e++] = t0; f_a2e = t0 + d.c;
+            } else if (pick == 2) {
+                e[c_e++] = t0; f_e = f_cu = t0 + d.e;
+            } else {
+                e2a[c_e2a++] = t0; f_e2a = t0 + d.c;
+            }
+        }
+        return std::fmax(s[n2 - 1] + d.s, e2a[n3 - 1] + d.c);
+    }
+};
+
 double replay_span(const moe_ep_dep_models& m, const moe_ep_dep_problem& p, int m_a, int r_1, int r_2, int order,
                    Replay* keep = nullptr)
 {
@@ -210,6 +290,24 @@ int moe_ep_dep_replay(const moe_ep_dep_models* m, const moe_ep_dep_problem* p, i
     if ((long long)p->n_layers * r_1 * r_2 > (1ll << 26)) return MOE_EP_EINVAL;
     Replay R;
     const double span = replay_span(*m, *p, m_a, r_1, r_2, order, &R);
+    if (makespan) *makespan = span;
+    auto put = [](double* dst, const std::vector<double>& v) { if (dst) for (size_t i = 0; i < v.size(); ++i) dst[i] = v[i]; };
+    put(tau_a, R.a); put(tau_s, R.s); put(tau_a2e, R.a2e); put(tau_e, R.e); put(tau_e2a, R.e2a);
+    return MOE_EP_OK;
+}
+
+int moe_ep_dep_replay_one_gpu(const moe_ep_dep_models* m, const moe_ep_dep_problem* p, int32_t m_a, int32_t r_1,
+                              int32_t r_2, int32_t order, double* makespan, double* tau_a, double* tau_s,
+                              double* tau_a2e, double* tau_e, double* tau_e2a)
+{
+    if (!m || !problem_ok(p) || m_a < 1 || r_1 < 1 || r_2 < 1 || (order != MOE_EP_DEP_ASAS && order != MOE_EP_DEP_AASS))
+        return MOE_EP_EINVAL;
+    if ((long long)p->n_layers * r_1 * r_2 > (1ll << 24)) return MOE_EP_EINVAL;
+    OneGpuReplay R;
+    R.T = p->n_layers; R.r1 = r_1; R.r2 = r_2;
+    R.d = durations(*m, *p, m_a, r_2);
+    const double span = R.run(order);
+    if (span < 0) return MOE_EP_ESTATE;
     if (makespan) *makespan = span;
     auto put = [](double* dst, const std::vector<double>& v) { if (dst) for (size_t i = 0; i < v.size(); ++i) dst[i] = v[i]; };
     put(tau_a, R.a); put(tau_s, R.s); put(tau_a2e, R.a2e); put(tau_e, R.e); put(tau_e2a, R.e2a);

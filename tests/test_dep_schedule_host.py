@@ -48,6 +48,22 @@ def test_replay_start_times_match_the_oracle():
             assert D.check_schedule(sch, r_1, r_2, prob_o.n_layers) == []
 
 
+def test_one_gpu_replay_matches_the_oracle():
+    rng = random.Random(27)
+    for _ in range(300):
+        mod_o, mod_p, prob_o, prob_p = _pair(rng, max_layers=4)
+        m_a, r_1, r_2 = rng.randint(1, 8), rng.randint(1, 5), rng.randint(1, 6)
+        for order in (D.ASAS, D.AASS):
+            ref = D.replay_one_gpu(mod_o, prob_o, m_a, r_1, r_2, order)
+            span, tau = P.dep_replay(mod_p, prob_p, m_a, r_1, r_2, order, one_gpu=True)
+            assert span == pytest.approx(ref["makespan"], rel=1e-12)
+            for k in ("tau_a", "tau_s", "tau_a2e", "tau_e", "tau_e2a"):
+                np.testing.assert_allclose(tau[k], np.asarray(ref[k]), rtol=1e-12, atol=1e-12)
+            sch = {k: tau[k].tolist() for k in tau}
+            sch["t"] = ref["t"]
+            assert D.check_schedule(sch, r_1, r_2, prob_o.n_layers, one_gpu=True) == []
+
+
 def test_makespan_model_matches():
     rng = random.Random(22)
     for _ in range(500):

@@ -173,6 +173,56 @@ def test_seeded_random_layers_match_the_oracle(seed):
     ctx.destroy()
 
 
+@pytest.mark.parametrize("order", [ASAS, AASS])
+def test_measured_makespan_lies_between_the_replay_for_two_groups_and_the_replay_for_one_gpu(order):
+    """The schedule model against the GPU, both ways (DeepSeek-V2-Lite-shaped layer, two micro-batches of two
+    chunks, 100 us attention stand-ins).  Fed with what the shared-expert and expert tasks take alone, the
+    replay of Eq. limitation is a lower bound of the measured makespan -- its two groups do not slow each
+    other down -- and the replay with the rule "shared experts and experts never overlap"
+    (moe_ep_dep_replay_one_gpu) an upper bound: on one GPU they do overlap, each at a part of the rate."""
+    import time
+    import paper_2512_21487_amd as pkg
+    g = _gpu()
+    wl = CONFIGS["dsv2_lite"]
+    r_1, r_2, attn_us = 2, 2, 100.0
+    ctx = g.make_ctx(wl, max_chunks=r_1 * r_2)
+    d = g.DeviceInputs(wl, make_inputs(wl))
+    T_mb = -(-wl.n_tokens // r_1)
+    # the tasks alone: one micro-batch through the plain forward, shared experts first, then its chunks
+    plain = lambda: ctx.forward(d.tokens, d.logits, d.routed, d.shared, wl.top_k, r_2, 0, n_tokens=T_mb, out=d.out)
+    for _ in range(3):
+        plain()
+    ctx.set_profiling(10)
+    for _ in range(10):
+        plain()
+    st = ctx.get_stage_ms()
+    ctx.set_profiling(0)
+    t_s = st["shared_gate_up_gemm"] + st["shared_down_gemm"]
+    t_e = sum(st[n] for n in ("router", "partition", "routed_gate_up_gemm", "routed_down_gemm", "aggregation")) / r_2
+    run = lambda: ctx.forward_dep(d.tokens, d.logits, d.routed, d.shared, wl.top_k, r_1, r_2, order, attn_us,
+                                  n_tokens=wl.n_tokens, out=d.out)
+    for _ in range(3):
+        run()
+    spans = []
+    for _ in range(5):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(10):
+            run()
+        torch.cuda.synchronize()
+        spans.append((time.perf_counter() - t0) / 10 * 1e3)
+    measured = float(np.median(spans))
+    mod = pkg.DepModels(attn_us * 1e-3, 0.0, t_s, 0.0, t_e, 0.0, 0.0, 0.0)
+    prob = pkg.DepProblem(ag=1, n_experts=wl.n_experts, top_k=wl.top_k, seq_len=1, n_layers=1)
+    lower = pkg.dep_replay(mod, prob, 1, r_1, r_2, order)[0]
+    upper = pkg.dep_replay(mod, prob, 1, r_1, r_2, order, one_gpu=True)[0]
+    print(f"       order={order}: tasks alone t_s {t_s:.4f} t_e {t_e:.4f} ms; two groups {lower:.4f} <= measured "
+          f"{measured:.4f} <= one GPU without overlap {upper:.4f} ms", flush=True)
+    assert lower <= upper
+    assert 0.93 * lower <= measured <= 1.07 * upper
+    ctx.destroy()
+
+
 @pytest.mark.parametrize("dep", [False, True])
 def test_layers_back_to_back_give_the_bits_of_lone_forwards(dep):
     """Steady state over several layers (Sec. 4.2, the per-layer offset of the multi-layer timeline): L
