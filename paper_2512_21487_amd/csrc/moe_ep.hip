@@ -250,9 +250,8 @@ const char* check_span(const void* p, size_t bytes, bool want_host, const void**
 // all experts and column tiles over the n_cu workgroups, rounded up, with an expert's row count
 // taken as normal around the balanced share Tn * k / E of Sec. 3.1 with a Poisson spread (the host
 // never learns the real counts).  Time per tile, relative to the 128-row shape, is a measurement
-// (MI355X, DeepSeek-V2-shaped share, both projections; profiles/routed_tile_times_dsv2_eg.txt): the
-// launches run at a matrix-instruction rate the package power limit sets, so a tile costs roughly
-// what its rows cost, plus what loading its 256 weight rows costs.
+// (MI355X, DeepSeek-V2-shaped share, both projections; profiles/routed_tile_times_dsv2_eg.txt):
+// a tile costs roughly what its rows cost, plus what loading its 256 weight rows costs.
 // automatic: a candidate of the choice below.  The two tall shapes are not: a tile of them costs what its
 // rows cost (1.74 = 7/4, 1.79 ~ 8/4 of a 128-row tile), so they only ever win by rounding the tile
 // count in their favour, and on every workload measured here the launch they win on paper ran slower
