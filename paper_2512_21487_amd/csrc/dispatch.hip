@@ -1,46 +1,56 @@
 // Partition of the kept assignments by local expert (Sec. 2.1; Sec. 3.1 "The MoE Part"):
-// a deterministic, stable counting sort in three steps.
-//   scan     per expert, exclusive prefix over the 64-token workgroups of the router's
-//            bit-mask populations -> first row of every (workgroup, expert) pair, the
-//            per-expert counts and their prefix sum
-//   permute  every assignment finds its row: expert base + workgroup base + number of
-//            earlier tokens of the workgroup with the same expert (a popcount)
-//   gather   the token rows are copied into expert-grouped order, 16 bytes per lane
+// a deterministic, stable counting sort.
+//   permute  from the router's per-workgroup bit masks (one bit per token and expert) every
+//            64-token workgroup derives the per-expert counts, their prefix sum and the rows its
+//            own tokens start at; every assignment then finds its row: expert base + rows of
+//            earlier workgroups + number of earlier tokens of the workgroup with the same expert
+//            (a popcount)
+//   gather   the token rows are copied into expert-grouped order, 16 bytes per lane (only when
+//            the gate/up projection does not gather them itself)
 #include "common.h"
 #include "kernels.h"
 
 namespace moe_ep {
 
-__global__ __launch_bounds__(1024) void dispatch_scan_kernel(
-    const unsigned long long* __restrict__ blk_mask, int nblk, int El,
-    int32_t* __restrict__ blk_off, int32_t* __restrict__ count, int32_t* __restrict__ offset)
+// One launch: every workgroup (64 tokens) sums the populations of all workgroups' masks itself --
+// per expert the total and the part that lies before it -- instead of waiting for a scan kernel
+// (nblk * El popcounts per workgroup, from L2; a launch boundary costs more).  Workgroup 0 also
+// writes the per-expert counts and their prefix sum for the GEMMs.
+__global__ __launch_bounds__(256) void dispatch_permute_kernel(
+    const int32_t* __restrict__ idx, const unsigned long long* __restrict__ blk_mask, int nblk, int Tn, int k,
+    int e0, int El, int32_t* __restrict__ count, int32_t* __restrict__ offset, int32_t* __restrict__ pos,
+    int32_t* __restrict__ perm)
 {
-    __shared__ int s_count[512];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    for (int e = wave; e < El; e += 16) {
-        int carry = 0;
+    extern __shared__ unsigned long long smem[];
+    unsigned long long* smask = smem;
+    int* sbase = reinterpret_cast<int*>(smem + El);   // rows of this workgroup's tokens before it, then the row base
+    int* stotal = sbase + El;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, blk = blockIdx.x;
+    for (int e = wave; e < El; e += 4) {
+        int total = 0, before = 0;
         for (int b0 = 0; b0 < nblk; b0 += 64) {
             const int b = b0 + lane;
-            const int c = (b < nblk) ? __popcll(blk_mask[(size_t)b * El + e]) : 0;
-            int x = c;
-#pragma unroll
-            for (int d = 1; d < 64; d <<= 1) {
-                const int y = __shfl_up(x, d, 64);
-                if (lane >= d) x += y;
-            }
-            if (b < nblk) blk_off[(size_t)b * El + e] = carry + x - c;
-            carry += __shfl(x, 63, 64);
+            const unsigned long long m = (b < nblk) ? blk_mask[(size_t)b * El + e] : 0ull;
+            const int c = __popcll(m);
+            total += c;
+            before += (b < blk) ? c : 0;
+            if (b == blk) smask[e] = m;
         }
-        if (lane == 0) s_count[e] = carry;
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) {
+            total += __shfl_xor(total, d, 64);
+            before += __shfl_xor(before, d, 64);
+        }
+        if (lane == 0) { stotal[e] = total; sbase[e] = before; }
     }
     __syncthreads();
     if (wave == 0) {
-        // El <= 512: lane owns 8 consecutive experts
+        // exclusive prefix of the totals over the experts; El <= 512: a lane owns 8 consecutive experts
         int c[8], rows = 0;
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             const int e = lane * 8 + i;
-            c[i] = (e < El) ? s_count[e] : 0;
+            c[i] = (e < El) ? stotal[e] : 0;
             rows += c[i];
         }
         int xr = rows;
@@ -53,26 +63,14 @@ __global__ __launch_bounds__(1024) void dispatch_scan_kernel(
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             const int e = lane * 8 + i;
-            if (e < El) { count[e] = c[i]; offset[e] = r; }
-            if (e == El) offset[e] = r;
+            if (e < El) {
+                sbase[e] += r;
+                if (blk == 0) { count[e] = c[i]; offset[e] = r; }
+            }
+            if (e == El && blk == 0) offset[e] = r;
             r += c[i];
         }
-        if (El == 512 && lane == 63) offset[El] = r;
-    }
-}
-
-__global__ __launch_bounds__(256) void dispatch_permute_kernel(
-    const int32_t* __restrict__ idx, const unsigned long long* __restrict__ blk_mask,
-    const int32_t* __restrict__ blk_off, const int32_t* __restrict__ offset, int Tn, int k, int e0,
-    int El, int32_t* __restrict__ pos, int32_t* __restrict__ perm)
-{
-    extern __shared__ unsigned long long smem[];
-    unsigned long long* smask = smem;
-    int* sbase = reinterpret_cast<int*>(smem + El);
-    const int tid = threadIdx.x, blk = blockIdx.x;
-    for (int i = tid; i < El; i += 256) {
-        smask[i] = blk_mask[(size_t)blk * El + i];
-        sbase[i] = offset[i] + blk_off[(size_t)blk * El + i];
+        if (El == 512 && lane == 63 && blk == 0) offset[El] = r;
     }
     __syncthreads();
     const int t_begin = blk * kTokPerBlock;
@@ -87,6 +85,15 @@ __global__ __launch_bounds__(256) void dispatch_permute_kernel(
             perm[p] = (int32_t)ga;
         }
         pos[ga] = p;
+    }
+}
+
+// no tokens: the counts and their prefix sum are zeros
+__global__ void dispatch_empty_kernel(int El, int32_t* __restrict__ count, int32_t* __restrict__ offset)
+{
+    for (int e = threadIdx.x; e <= El; e += blockDim.x) {
+        if (e < El) count[e] = 0;
+        offset[e] = 0;
     }
 }
 
@@ -110,23 +117,17 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(
     }
 }
 
-hipError_t launch_dispatch_scan(const unsigned long long* blk_mask, int nblk, int El,
-                                int32_t* blk_off, int32_t* count, int32_t* offset, hipStream_t s)
+hipError_t launch_dispatch(const int32_t* idx, const unsigned long long* blk_mask, int Tn, int k, int e0, int El,
+                           int32_t* count, int32_t* offset, int32_t* pos, int32_t* perm, hipStream_t s)
 {
-    hipLaunchKernelGGL(dispatch_scan_kernel, dim3(1), dim3(1024), 0, s, blk_mask, nblk, El,
-                       blk_off, count, offset);
-    return hipGetLastError();
-}
-
-hipError_t launch_dispatch_permute(const int32_t* idx, const unsigned long long* blk_mask,
-                                   const int32_t* blk_off, const int32_t* offset, int Tn, int k,
-                                   int e0, int El, int32_t* pos, int32_t* perm, hipStream_t s)
-{
-    if (Tn <= 0) return hipSuccess;
+    if (Tn <= 0) {
+        hipLaunchKernelGGL(dispatch_empty_kernel, dim3(1), dim3(256), 0, s, El, count, offset);
+        return hipGetLastError();
+    }
     const int nblk = (Tn + kTokPerBlock - 1) / kTokPerBlock;
     hipLaunchKernelGGL(dispatch_permute_kernel, dim3(nblk), dim3(256),
-                       El * (sizeof(unsigned long long) + sizeof(int)), s, idx, blk_mask, blk_off,
-                       offset, Tn, k, e0, El, pos, perm);
+                       El * (sizeof(unsigned long long) + 2 * sizeof(int)), s, idx, blk_mask, nblk, Tn, k, e0, El,
+                       count, offset, pos, perm);
     return hipGetLastError();
 }
 

@@ -13,11 +13,9 @@ hipError_t launch_router(const float* logits, int Tn, int E, int k, int e0, int 
                          float* w, unsigned long long* blk_mask, hipStream_t s);
 
 // ---- partition by expert (Sec. 2.1; Sec. 3.1 "The MoE Part")
-hipError_t launch_dispatch_scan(const unsigned long long* blk_mask, int nblk, int El,
-                                int32_t* blk_off, int32_t* count, int32_t* offset, hipStream_t s);
-hipError_t launch_dispatch_permute(const int32_t* idx, const unsigned long long* blk_mask,
-                                   const int32_t* blk_off, const int32_t* offset, int Tn, int k,
-                                   int e0, int El, int32_t* pos, int32_t* perm, hipStream_t s);
+// count [El], offset [El + 1], pos [Tn * k] (row of an assignment or -1), perm [rows] (row -> assignment)
+hipError_t launch_dispatch(const int32_t* idx, const unsigned long long* blk_mask, int Tn, int k, int e0, int El,
+                           int32_t* count, int32_t* offset, int32_t* pos, int32_t* perm, hipStream_t s);
 hipError_t launch_gather_rows(const void* tokens, const int32_t* perm, const int32_t* n_rows_ptr,
                               int k, int M, void* xp, int grid, hipStream_t s);
 

@@ -60,7 +60,7 @@ struct moe_ep_ctx {
     // device workspaces
     void* d_tokens = nullptr; float* d_logits = nullptr; void* d_out = nullptr;  // pinned-host mode staging
     int32_t* idx = nullptr; float* w = nullptr; int32_t* pos = nullptr; int32_t* perm = nullptr;
-    unsigned long long* blk_mask = nullptr; int32_t* blk_off = nullptr;
+    unsigned long long* blk_mask = nullptr;
     int32_t* count = nullptr; int32_t* offset = nullptr;
     uint16_t* xp = nullptr; uint16_t* h = nullptr; uint16_t* y = nullptr;
     uint16_t* hs = nullptr;
@@ -96,7 +96,7 @@ const char* set_why(const char** why, const char* msg) { if (why) *why = msg; re
 size_t align256(size_t b) { return (b + 255) & ~(size_t)255; }
 
 struct WsLayout {
-    size_t tokens, logits, out, idx, w, pos, perm, blk_mask, blk_off, count, offset, xp, h, y, hs, total;
+    size_t tokens, logits, out, idx, w, pos, perm, blk_mask, count, offset, xp, h, y, hs, total;
 };
 
 // MOE_EP_FUSED_GATHER=0 brings back the grouped copy of the token rows (for comparison)
@@ -130,7 +130,7 @@ WsLayout ws_layout(const moe_ep_config& c)
     L.logits = take(pinned ? T * (size_t)c.n_experts * 4 : 0);
     L.out = take(pinned ? T * M * 2 : 0);
     L.idx = take(A * 4); L.w = take(A * 4); L.pos = take(A * 4); L.perm = take(A * 4);
-    L.blk_mask = take(nblk * El * 8); L.blk_off = take(nblk * El * 4);
+    L.blk_mask = take(nblk * El * 8);
     L.count = take(R * El * 4); L.offset = take(R * (El + 1) * 4);
     // the grouped copy of the token rows exists only when the gate/up projection cannot gather them
     // itself: switched off, or a chunk of 4 GB and more (its lanes hold 32-bit byte offsets)
@@ -152,7 +152,6 @@ void bind_workspaces(moe_ep_ctx* ctx, char* slab, const WsLayout& L)
     ctx->pos = reinterpret_cast<int32_t*>(slab + L.pos);
     ctx->perm = reinterpret_cast<int32_t*>(slab + L.perm);
     ctx->blk_mask = reinterpret_cast<unsigned long long*>(slab + L.blk_mask);
-    ctx->blk_off = reinterpret_cast<int32_t*>(slab + L.blk_off);
     ctx->count = reinterpret_cast<int32_t*>(slab + L.count);
     ctx->offset = reinterpret_cast<int32_t*>(slab + L.offset);
     ctx->xp = reinterpret_cast<uint16_t*>(slab + L.xp);
@@ -760,7 +759,6 @@ int forward_impl(moe_ep_ctx* ctx, const void* tokens, const float* gate_logits, 
         int32_t* offset = ctx->offset + (size_t)cidx * (El + 1);
         if (pinned) HIP_TRY(ctx, hipStreamWaitEvent(s_comp, ctx->ev_in[cidx], 0));
         else if (dep && cidx % r_2 == 0) HIP_TRY(ctx, hipStreamWaitEvent(s_comp, ctx->ev_attn[cidx / r_2], 0));
-        const int nblk = (Tn + kTokPerBlock - 1) / kTokPerBlock;
         // tile shapes of the two routed projections: N = H in tiles of 128 activation columns, N = M in
         // tiles of 256 columns
         int v_up = ctx->gemm_variant >= 0 ? ctx->gemm_variant : routed_variant(Tn, k, E, El, (H + 127) / 128, M, n_cu);
@@ -780,12 +778,9 @@ int forward_impl(moe_ep_ctx* ctx, const void* tokens, const float* gate_logits, 
         // the fused gather addresses a chunk's token rows with 32-bit byte offsets
         const bool fused = ctx->fused_gather && (unsigned long long)Tn * M * 2 < (1ull << 32);
         sp = prof_begin(ctx, prof, ST_PARTITION, s_comp);
-        HIP_TRY(ctx, launch_dispatch_scan(ctx->blk_mask, nblk, El, ctx->blk_off, count, offset, s_comp));
-        if (Tn > 0) {
-            HIP_TRY(ctx, launch_dispatch_permute(idx, ctx->blk_mask, ctx->blk_off, offset, Tn, k, e0, El, pos, perm, s_comp));
-            if (!fused)
-                HIP_TRY(ctx, launch_gather_rows(tok_dev + (size_t)t0 * M, perm, offset + El, k, M, ctx->xp, bw_grid, s_comp));
-        }
+        HIP_TRY(ctx, launch_dispatch(idx, ctx->blk_mask, Tn, k, e0, El, count, offset, pos, perm, s_comp));
+        if (Tn > 0 && !fused)
+            HIP_TRY(ctx, launch_gather_rows(tok_dev + (size_t)t0 * M, perm, offset + El, k, M, ctx->xp, bw_grid, s_comp));
         prof_end(ctx, sp, s_comp);
         if (Tn == 0) {
             if (pinned && !fused_out) HIP_TRY(ctx, hipEventRecord(ctx->ev_comp[cidx], s_comp));
