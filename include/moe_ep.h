@@ -216,7 +216,7 @@ int moe_ep_get_routing(moe_ep_ctx *ctx, int32_t chunk, int32_t *idx, float *w, i
  * record an event before and after every stage; this serialises nothing.
  * moe_ep_get_stage_ms synchronises, returns the per-forward AVERAGE over the forwards recorded
  * since the last call, and opens a new window of `depth` forwards:
- *   ms[0] gate  ms[1] partition (scan + permute + row gather)  ms[2] routed gate/up GEMM
+ *   ms[0] gate  ms[1] partition (permute + row gather)  ms[2] routed gate/up GEMM
  *   ms[3] routed down GEMM  ms[4] shared gate/up GEMM  ms[5] shared down GEMM
  *   ms[6] aggregation  ms[7] whole forward (first enqueue to last completion)
  *   ms[8] inbound copies  ms[9] outbound copies (MOE_EP_IO_PINNED_HOST only, else 0)
