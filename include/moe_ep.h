@@ -103,6 +103,8 @@ int moe_ep_create(const moe_ep_config *cfg, moe_ep_ctx **out_ctx);
  *               NaN / Inf scores are not supported.
  *   routed_w    bf16, device: for each local expert, contiguous, W_gate [H, M],
  *               W_up [H, M], W_down [M, H], all row-major (Sec. 3.1); experts contiguous.
+ *               (A pointer that moe_ep_prepare_weights has seen is read from the context's
+ *               tile-order copy instead; the same holds for shared_w.)
  *   shared_w    bf16, device: the same triple for each shared expert with H = shared_inter;
  *               NULL exactly when n_shared == 0.
  *   top_k       1..min(E, max_top_k);   r_chunks 1..max_chunks (0 = chosen from the context's
