@@ -75,8 +75,10 @@ typedef struct {
     int32_t device;       /* HIP device ordinal                                             */
 } moe_ep_config;
 
-/* Pure host checks, usable without a GPU.  Return MOE_EP_OK or MOE_EP_EINVAL; if
- * `why` is not NULL it receives a static string naming the first violated rule. */
+/* Pure host checks of a layer's shape (the quantities of the paper's notation table: M, H, E, the
+ * E / eg experts of a device, top_k, N_shared) and of a forward's arguments, usable without a GPU.
+ * Return MOE_EP_OK or MOE_EP_EINVAL; if `why` is not NULL it receives a static string naming the
+ * first violated rule. */
 int moe_ep_validate_config(const moe_ep_config *cfg, const char **why);
 int moe_ep_validate_forward(const moe_ep_config *cfg, const void *tokens,
                             const float *gate_logits, const void *routed_w,
@@ -214,7 +216,7 @@ int moe_ep_get_routing(moe_ep_ctx *ctx, int32_t chunk, int32_t *idx, float *w, i
 
 /*
  * Per-stage device time, in milliseconds, measured with HIP events on the streams the stages
- * run on.  moe_ep_set_profiling(ctx, depth) makes the next `depth` forwards (0..256; 0 = off)
+ * run on (the task times t_e, t_s, t_a2e that Sec. 4.1 fits its linear models to).  moe_ep_set_profiling(ctx, depth) makes the next `depth` forwards (0..256; 0 = off)
  * record an event before and after every stage; this serialises nothing.
  * moe_ep_get_stage_ms synchronises, returns the per-forward AVERAGE over the forwards recorded
  * since the last call, and opens a new window of `depth` forwards:
