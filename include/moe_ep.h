@@ -53,7 +53,9 @@ typedef enum {
     MOE_EP_IO_DEVICE = 0,     /* device pointers; no copies are made                        */
     MOE_EP_IO_PINNED_HOST = 1 /* pinned host pointers; each chunk crosses the host link in and
                                  out, standing in for the A2E / E2A transfers (Sec. 2.2; Eq.
-                                 a2e_detail): inbound as a copy on a stream of the context,
+                                 a2e_detail): inbound as a copy on a stream of the context
+                                 (a chunk's gate scores first: gate and partition run while its
+                                 token rows are still on the link),
                                  outbound as the aggregation's own stores into the host buffer
                                  (moe_ep_forward; the environment variable MOE_EP_FUSED_OUT=0
                                  makes it a copy on a second stream) or as such a copy

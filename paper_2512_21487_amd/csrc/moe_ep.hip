@@ -68,6 +68,9 @@ struct moe_ep_ctx {
     hipStream_t s_in = nullptr, s_out = nullptr;  // the two link directions (pinned-host mode)
     hipEvent_t ev_start = nullptr, ev_done = nullptr, ev_comp_done = nullptr;
     std::vector<hipEvent_t> ev_in, ev_comp;
+    // pinned-host mode: a chunk's gate scores have arrived (they travel first: gate and partition need
+    // nothing else and run while the chunk's token rows are still on the link)
+    std::vector<hipEvent_t> ev_scores;
     // attention-group side of moe_ep_forward_dep, created at its first call: the stream the attention
     // stand-ins and the shared experts run on, and per micro-batch "attention done" / "shared done"
     hipStream_t s_ag = nullptr;
@@ -373,6 +376,7 @@ int moe_ep_destroy(moe_ep_ctx* ctx)
     (void)hipSetDevice(ctx->cfg.device);
     (void)hipDeviceSynchronize();  // forwards still in flight on the caller's streams use the workspaces
     for (hipEvent_t e : ctx->ev_in) (void)hipEventDestroy(e);
+    for (hipEvent_t e : ctx->ev_scores) (void)hipEventDestroy(e);
     for (hipEvent_t e : ctx->ev_comp) (void)hipEventDestroy(e);
     for (hipEvent_t e : ctx->ev_attn) (void)hipEventDestroy(e);
     for (hipEvent_t e : ctx->ev_shared) (void)hipEventDestroy(e);
@@ -428,6 +432,11 @@ int moe_ep_create(const moe_ep_config* cfg, moe_ep_ctx** out_ctx)
         hipEvent_t a = nullptr, b = nullptr;
         ok = ok && hipEventCreateWithFlags(&a, ev_flags) == hipSuccess;
         if (a) ctx->ev_in.push_back(a);
+        if (cfg->io_mode == MOE_EP_IO_PINNED_HOST) {
+            hipEvent_t c = nullptr;
+            ok = ok && hipEventCreateWithFlags(&c, ev_flags) == hipSuccess;
+            if (c) ctx->ev_scores.push_back(c);
+        }
         ok = ok && hipEventCreateWithFlags(&b, ev_flags) == hipSuccess;
         if (b) ctx->ev_comp.push_back(b);
     }
@@ -690,12 +699,13 @@ int forward_impl(moe_ep_ctx* ctx, const void* tokens, const float* gate_logits, 
         // no timing events around the runtime's own copies (MOE_EP_LINK_MEMCPY): the one profiled run
         // that had them ended in a crash inside the profiler's exit handler; the copy kernels are timed
         const int sp_in = prof_begin(ctx, prof && Tn > 0 && !ctx->memcpy_in, ST_COPY_IN, s_in);
-        if (Tn > 0) {
-            HIP_TRY(ctx, link_copy(static_cast<char*>(ctx->d_tokens) + (size_t)t0 * M * 2,
-                                     h_tokens + (size_t)t0 * M * 2, (size_t)Tn * M * 2, link_grid, s_in));
+        if (Tn > 0)
             HIP_TRY(ctx, link_copy(ctx->d_logits + (size_t)t0 * E, h_logits + (size_t)t0 * E * 4,
                                      (size_t)Tn * E * 4, link_grid, s_in));
-        }
+        HIP_TRY(ctx, hipEventRecord(ctx->ev_scores[cidx], s_in));
+        if (Tn > 0)
+            HIP_TRY(ctx, link_copy(static_cast<char*>(ctx->d_tokens) + (size_t)t0 * M * 2,
+                                     h_tokens + (size_t)t0 * M * 2, (size_t)Tn * M * 2, link_grid, s_in));
         prof_end(ctx, sp_in, s_in);
         HIP_TRY(ctx, hipEventRecord(ctx->ev_in[cidx], s_in));
         return MOE_EP_OK;
@@ -757,7 +767,8 @@ int forward_impl(moe_ep_ctx* ctx, const void* tokens, const float* gate_logits, 
         chunk_range(T, r_1, r_2, cidx, &t0, &Tn);
         int32_t* count = ctx->count + (size_t)cidx * El;
         int32_t* offset = ctx->offset + (size_t)cidx * (El + 1);
-        if (pinned) HIP_TRY(ctx, hipStreamWaitEvent(s_comp, ctx->ev_in[cidx], 0));
+        // gate and partition need the chunk's gate scores only, which travel first
+        if (pinned) HIP_TRY(ctx, hipStreamWaitEvent(s_comp, ctx->ev_scores[cidx], 0));
         else if (dep && cidx % r_2 == 0) HIP_TRY(ctx, hipStreamWaitEvent(s_comp, ctx->ev_attn[cidx / r_2], 0));
         // tile shapes of the two routed projections: N = H in tiles of 128 activation columns, N = M in
         // tiles of 256 columns
@@ -779,9 +790,12 @@ int forward_impl(moe_ep_ctx* ctx, const void* tokens, const float* gate_logits, 
         const bool fused = ctx->fused_gather && (unsigned long long)Tn * M * 2 < (1ull << 32);
         sp = prof_begin(ctx, prof, ST_PARTITION, s_comp);
         HIP_TRY(ctx, launch_dispatch(idx, ctx->blk_mask, Tn, k, e0, El, count, offset, pos, perm, s_comp));
-        if (Tn > 0 && !fused)
+        if (Tn > 0 && !fused) {   // the grouped copy reads the token rows
+            if (pinned) HIP_TRY(ctx, hipStreamWaitEvent(s_comp, ctx->ev_in[cidx], 0));
             HIP_TRY(ctx, launch_gather_rows(tok_dev + (size_t)t0 * M, perm, offset + El, k, M, ctx->xp, bw_grid, s_comp));
+        }
         prof_end(ctx, sp, s_comp);
+        if (pinned) HIP_TRY(ctx, hipStreamWaitEvent(s_comp, ctx->ev_in[cidx], 0));   // the token rows
         if (Tn == 0) {
             if (pinned && !fused_out) HIP_TRY(ctx, hipEventRecord(ctx->ev_comp[cidx], s_comp));
             continue;

@@ -128,7 +128,10 @@ def test_measured_timeline_obeys_the_rules(order):
         for j in range(r_2):
             c = i * r_2 + j
             assert by["copy_in"][c][0] >= by["attention"][i][1] - eps            # rule 6
-            assert by["router"][c][0] >= by["copy_in"][c][1] - eps               # rule 7
+            # rule 7: the experts wait for the chunk's token rows; gate and partition only for its gate
+            # scores, which head the transfer
+            assert by["routed_gate_up_gemm"][c][0] >= by["copy_in"][c][1] - eps
+            assert by["router"][c][0] >= by["copy_in"][c][0] - eps
             assert by["aggregation"][c][0] >= by["shared_down_gemm"][i][1] - eps
             assert by["copy_out"][c][0] >= by["aggregation"][c][1] - eps         # rule 8
     assert by["forward"][0][1] >= max(by["copy_out"][-1][1], by["shared_down_gemm"][-1][1]) - eps
