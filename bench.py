@@ -214,6 +214,10 @@ def main() -> int:
                          "average of 3 runs) and print one line: value = mean over the processes")
     ap.add_argument("--no-device-probe", action="store_true",
                     help="skip the register-only MFMA loop and the streaming copy that follow the timed forwards")
+    ap.add_argument("--zero-operands", action="store_true",
+                    help="time the same launches on all-zero tokens and weights (the routing stays): the matrix "
+                         "units then switch almost nothing and the clock stays at its maximum, which separates what "
+                         "the package power limit costs from what the kernels cost (a diagnostic, not a result)")
     ap.add_argument("--no-prepare-weights", action="store_true",
                     help="read the weights in the caller's row-major layout (no tile-order copy)")
     ap.add_argument("--no-stage-timing", action="store_true",
@@ -273,6 +277,11 @@ def main() -> int:
     tokens, logits = put(inp["tokens"], pinned), put(inp["gate_logits"], pinned)
     routed = put(inp["routed_w"])
     shared = put(inp["shared_w"]) if inp["shared_w"] is not None else None
+    if args.zero_operands:
+        tokens.zero_()
+        routed.zero_()
+        if shared is not None:
+            shared.zero_()
     if pinned:
         out = torch.zeros((T, M), dtype=torch.int16, pin_memory=True)
     else:
@@ -409,7 +418,8 @@ def main() -> int:
         "metric": "expert-layer tokens/sec at 1 GPU; grouped-GEMM % of bf16 MFMA peak",
         "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic" if not args.zero_operands else "all-zero tokens and weights (power diagnostic, not a result)",
         "config": {"workload": f"{wl.name}: T={T} M={M} H={H} E={wl.n_experts} local={wl.n_local} "
                                f"top_k={k} shared={Ns}x{Hs} io={'pinned_host' if pinned else 'device'}",
                    "r_chunks": args.r, "order": args.order, "weights": weights, "kept_assignments": kept,
