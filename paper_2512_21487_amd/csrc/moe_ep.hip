@@ -317,7 +317,7 @@ void prof_end(moe_ep_ctx* ctx, int span, hipStream_t s)
 
 extern "C" {
 
-const char* moe_ep_version(void) { return "0.1"; }
+const char* moe_ep_version(void) { return "0.2"; }
 
 int moe_ep_validate_config(const moe_ep_config* c, const char** why)
 {
