@@ -21,6 +21,9 @@ HIPCC_FLAGS = [
     # packed-fp32 code generation is switched off on purpose (silent wrong results were seen
     # with some of its forms on this hardware generation)
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # the GEMM's K step is one fully unrolled sequence of up to 128 matrix instructions with their loads and
+    # fragment reads; past the default threshold the compiler keeps a loop and the accumulators go to scratch memory
+    "-mllvm", "-pragma-unroll-threshold=200000",
     "-I", INCLUDE, "-I", CSRC,
 ]
 

@@ -72,6 +72,16 @@ struct GemmCfg {
         const int l = (p * RPW + WINDOW - 1) / WINDOW;
         return (l < RPW && (l * WINDOW) / RPW == p) ? l : -1;
     }
+    // The same K step out of v_mfma_f32_16x16x32_bf16 (MI == 16 below): a wavefront's tile is MB16 x NB16
+    // blocks of 16 x 16, a K step is KK32 steps of 32, the hand-over sits three quarters through the
+    // K step's SLOTS16 MFMAs and the loads are spread over the three quarters that follow it.
+    static constexpr int MB16 = WTM / 16, NB16 = WTN / 16, KK32 = BK / 32;
+    static constexpr int SLOTS16 = KK32 * MB16 * NB16, HO16 = SLOTS16 - SLOTS16 / 4, WINDOW16 = HO16;
+    static constexpr int load_at16(int p)
+    {
+        const int l = (p * RPW + WINDOW16 - 1) / WINDOW16;
+        return (l < RPW && (l * WINDOW16) / RPW == p) ? l : -1;
+    }
 };
 
 // g * sigmoid(g) from the hardware's exp2 and reciprocal (about 1 ulp each: far below the bf16
@@ -170,7 +180,7 @@ static int lds_cap(int bytes) { return bytes < kLdsPerWorkgroup ? bytes : kLdsPe
 // 0 bf16 results; 1 fp32 results (the experts' outputs are then not rounded before the aggregation);
 // 2 bf16 results already multiplied by the routing weight of the row's assignment (Sec. 2.1: the
 // aggregation then only adds)
-template <int BM, int BN, int BK, int STAGES, int WGM, int WGN, bool SWIGLU, bool RAGGED, int EPI = 0, bool PACKED = false>
+template <int BM, int BN, int BK, int STAGES, int WGM, int WGN, bool SWIGLU, bool RAGGED, int EPI = 0, bool PACKED = false, int MI = 32>
 __device__ __forceinline__ void gemm_tiles(const GemmArgs& a, uint4* lds, const int* s_pref, const int* s_row0,
                                            const int* s_rowend, int* s_tile, int max_units)
 {
@@ -178,6 +188,12 @@ __device__ __forceinline__ void gemm_tiles(const GemmArgs& a, uint4* lds, const 
     constexpr int MB = Cfg::MB, NB = Cfg::NB, RPW = Cfg::RPW, XRPW = Cfg::XRPW, NW = Cfg::NW;
     constexpr int THREADS = Cfg::THREADS, BN_OUT = Cfg::BN_OUT, CPR = Cfg::CPR, RP = Cfg::RP;
     constexpr int RPR = Cfg::RPR, KKW = Cfg::KKW;
+    constexpr int MB16 = Cfg::MB16, NB16 = Cfg::NB16, KK32 = Cfg::KK32, SLOTS16 = Cfg::SLOTS16, HO16 = Cfg::HO16;
+    static_assert(MI == 32 || MI == 16, "v_mfma_f32_32x32x16_bf16 or v_mfma_f32_16x16x32_bf16");
+    static_assert(MI == 32 || (BK == 64 && Cfg::RPW <= Cfg::WINDOW16 && MB16 + NB16 <= SLOTS16 / 4 && NB16 % 2 == 0 &&
+                               (!SWIGLU || NB16 % 4 == 0)),
+                  "16 x 16 blocks: a K step is two steps of 32 (fragment sets 0 and 1), its loads and the next K step's "
+                  "first fragment reads fit their windows, column blocks pair up for the stores");
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform: LDS destinations stay scalar
     const int wn = wave % WGN, wm = wave / WGN;
@@ -202,7 +218,8 @@ __device__ __forceinline__ void gemm_tiles(const GemmArgs& a, uint4* lds, const 
     if (slot >= per_xcd) return;   // the whole workgroup leaves, before any barrier of the tile pass
     const int KT = a.K / BK;
     // fragment geometry of this lane: row inside a 32-row block, swizzle term, k half
-    const int fr_row = lane & 31, fr_sw = ((lane & 31) / RP) % CPR, fr_kh = lane >> 5;
+    // (16 x 16 blocks: row inside a 16-row block, swizzle term, which 8 of a step's 32 k values)
+    const int fr_row = MI == 16 ? lane & 15 : lane & 31, fr_sw = (fr_row / RP) % CPR, fr_kh = MI == 16 ? lane >> 4 : lane >> 5;
     // load geometry of this lane: row inside a 1 KB region, physical chunk slot
     const int ld_row = lane / CPR, ld_p = lane % CPR;
 
@@ -349,8 +366,27 @@ __device__ __forceinline__ void gemm_tiles(const GemmArgs& a, uint4* lds, const 
                                                : BN / 2 + wn * (Cfg::WTN / 2) + (nb - NB / 2) * 32);
         return BM + wn * Cfg::WTN + nb * 32;
     };
-    f32x16_t acc[MB][NB];
-    bf16x8_t xf[2][MB], wf[2][NB];
+    f32x16_t acc[MI == 32 ? MB : 1][MI == 32 ? NB : 1];
+    bf16x8_t xf[2][MI == 32 ? MB : 1], wf[2][MI == 32 ? NB : 1];
+    // 16 x 16 blocks (MI == 16): a lane's four accumulators of a block are four consecutive output columns of
+    // one token row; fragments are 16 rows by 32 k, 8 k per lane
+    auto w_row_base16 = [&](int nb) -> int {
+        if (SWIGLU) return BM + ((nb < NB16 / 2) ? wn * (Cfg::WTN / 2) + nb * 16
+                                                 : BN / 2 + wn * (Cfg::WTN / 2) + (nb - NB16 / 2) * 16);
+        return BM + wn * Cfg::WTN + nb * 16;
+    };
+    f32x4_t acc16[MI == 16 ? MB16 : 1][MI == 16 ? NB16 : 1];
+    bf16x8_t xf16[2][MI == 16 ? MB16 : 1], wf16[2][MI == 16 ? NB16 : 1];
+    // one LDS fragment read of a 16-row block from ring slot base sT_, step kk_ of 32: f < MB16 an activation
+    // block, f >= MB16 a weight block
+#define MOE_EP_FRAG16(sT_, kk_, set_, f_)                                                         \
+    {                                                                                             \
+        const int csw_ = ((kk_) * 4 + fr_kh) ^ fr_sw;                                             \
+        if ((f_) < MB16) xf16[set_][(f_) < MB16 ? (f_) : 0] = __builtin_bit_cast(bf16x8_t,        \
+            (sT_)[(wm * Cfg::WTM + (f_) * 16 + fr_row) * CPR + csw_]);                            \
+        else wf16[set_][(f_) >= MB16 ? (f_) - MB16 : 0] = __builtin_bit_cast(bf16x8_t,            \
+            (sT_)[(w_row_base16((f_) >= MB16 ? (f_) - MB16 : 0) + fr_row) * CPR + csw_]);         \
+    }
     // one LDS fragment read from ring slot base sT_: index f < MB is an activation block,
     // f >= MB a weight block
 #define MOE_EP_FRAG1(sT_, kk_, set_, f_)                                                          \
@@ -437,6 +473,59 @@ __device__ __forceinline__ void gemm_tiles(const GemmArgs& a, uint4* lds, const 
         stage = st_next;                                                                          \
     }
 
+    // The same K step out of 16 x 16 x 32 MFMAs: KK32 steps of 32, step j out of fragment set j & 1 while the
+    // reads of step j + 1 are slipped behind every second of its first MFMAs.  The hand-over sits in front of
+    // MFMA HO16 (three quarters through the K step); the next K step's first fragments are read behind the
+    // MFMAs that follow it, the loads of the K step STAGES ahead start there and carry on over the first three
+    // quarters of the following K step (GemmCfg::load_at16).
+#define MOE_EP_FRAG_ORDER16(f_) ((f_) == 0 ? MB16 : (f_) <= MB16 ? (f_) - 1 : (f_))
+#define MOE_EP_STEP16(prefetch_)                                                                  \
+    {                                                                                             \
+        const uint4* sT = lds + stage * Cfg::STAGE_CHUNKS;                                        \
+        const int st_next = stage == STAGES - 1 ? 0 : stage + 1;                                  \
+        const uint4* sN = lds + st_next * Cfg::STAGE_CHUNKS;                                      \
+        const int st_prev = stage == 0 ? STAGES - 1 : stage - 1;                                  \
+        constexpr int RS_ = (SLOTS16 / 4) / (MB16 + NB16);   /* MFMAs per prefetch read */        \
+        _Pragma("unroll") for (int j = 0; j < KK32; ++j) {                                        \
+            _Pragma("unroll") for (int q = 0; q < MB16 * NB16; ++q) {                             \
+                const int m_ = j * MB16 * NB16 + q;                                               \
+                if (m_ == HO16) {                                                                 \
+                    if (ki == KT) {                                                               \
+                        if (!issue_end) {                                                         \
+                            has_nxt = setup_tile(it_issue + 1, nxt);                              \
+                            if (has_nxt) ++it_issue; else issue_end = true;                       \
+                        }                                                                         \
+                        ki = 0;                                                                   \
+                    }                                                                             \
+                    MOE_EP_HANDOVER((STAGES - 2) * RPW)                                           \
+                }                                                                                 \
+                const int nb = q / MB16, mb = (nb & 1) ? MB16 - 1 - q % MB16 : q % MB16;          \
+                /* written out so that the block is updated in place, in accumulator registers: through the  \
+                   builtin the register allocator moves blocks between two K steps and through vector registers */ \
+                asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0"                             \
+                             : "+a"(acc16[mb][nb]) : "v"(wf16[j & 1][nb]), "v"(xf16[j & 1][mb])); \
+                if (j + 1 < KK32) {                                                               \
+                    if (q % 2 == 0 && q / 2 < MB16 + NB16)                                        \
+                        MOE_EP_FRAG16(sT, j + 1, (j + 1) & 1, MOE_EP_FRAG_ORDER16(q / 2))         \
+                } else if (prefetch_) {                                                           \
+                    const int f_ = m_ - HO16;                                                     \
+                    if (f_ >= 0 && f_ % RS_ == 0 && f_ / RS_ < MB16 + NB16)                       \
+                        MOE_EP_FRAG16(sN, 0, 0, MOE_EP_FRAG_ORDER16(f_ / RS_))                    \
+                }                                                                                 \
+                if (m_ >= HO16) {                                                                 \
+                    const int l_ = Cfg::load_at16(m_ - HO16);                                     \
+                    if (l_ >= 0) MOE_EP_ISSUE1(ki, stage, l_ < 0 ? 0 : l_)                        \
+                } else {  /* the rest of the load group that started a K step ago */              \
+                    const int l_ = Cfg::load_at16(m_ + SLOTS16 - HO16);                           \
+                    if (l_ >= 0) MOE_EP_ISSUE1(ki - 1, st_prev, l_ < 0 ? 0 : l_)                  \
+                }                                                                                 \
+                SB();                                                                             \
+            }                                                                                     \
+        }                                                                                         \
+        ++ki;                                                                                     \
+        stage = st_next;                                                                          \
+    }
+
     Tile cur, nxt;
     if (!setup_tile(0, cur)) return;
     // The ring never drains between tiles: the issue side runs STAGES K steps ahead of the MFMAs and
@@ -453,27 +542,57 @@ __device__ __forceinline__ void gemm_tiles(const GemmArgs& a, uint4* lds, const 
 #pragma unroll
         for (int i = 0; i < RPW; ++i) MOE_EP_ISSUE1(p, p, i)
     MOE_EP_HANDOVER((STAGES - 2) * RPW)
+    if constexpr (MI == 32) {
 #pragma unroll
-    for (int p = 0; p < MB * NB; ++p)
-        if (Cfg::load_at(p) >= 0) MOE_EP_ISSUE1(STAGES - 1, STAGES - 1, Cfg::load_at(p) < 0 ? 0 : Cfg::load_at(p))
+        for (int p = 0; p < MB * NB; ++p)
+            if (Cfg::load_at(p) >= 0) MOE_EP_ISSUE1(STAGES - 1, STAGES - 1, Cfg::load_at(p) < 0 ? 0 : Cfg::load_at(p))
+    } else {
+#pragma unroll
+        for (int p = 0; p < SLOTS16 - HO16; ++p)
+            if (Cfg::load_at16(p) >= 0) MOE_EP_ISSUE1(STAGES - 1, STAGES - 1, Cfg::load_at16(p) < 0 ? 0 : Cfg::load_at16(p))
+    }
     int ki = STAGES;  // K step of the issue-side tile whose loads start at the next hand-over
     {   // the first tile's first K step has been handed over: its first fragments.  Every later K
         // step, the first of a following tile included, gets them from the step before it.
         const uint4* s0 = lds + stage * Cfg::STAGE_CHUNKS;
+        if constexpr (MI == 32) {
 #pragma unroll
-        for (int f = 0; f < MB + NB; ++f) MOE_EP_FRAG1(s0, 0, 0, MOE_EP_FRAG_ORDER(f))
+            for (int f = 0; f < MB + NB; ++f) MOE_EP_FRAG1(s0, 0, 0, MOE_EP_FRAG_ORDER(f))
+        } else {
+#pragma unroll
+            for (int f = 0; f < MB16 + NB16; ++f) MOE_EP_FRAG16(s0, 0, 0, MOE_EP_FRAG_ORDER16(f))
+        }
         SB();
     }
     for (;;) {
-#pragma unroll
-        for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc[mb][nb][r] = 0.f;
         // one loop shape for every K step: the last one of a tile hands the next tile's first K
         // step over and reads its first fragments, which wait in registers through the epilogue
-        for (int kt = 0; kt < KT; ++kt) MOE_EP_STEP(true)
+        if constexpr (MI == 32) {
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) acc[mb][nb][r] = 0.f;
+            for (int kt = 0; kt < KT; ++kt) MOE_EP_STEP(true)
+        } else {
+#pragma unroll
+            for (int mb = 0; mb < MB16; ++mb)
+#pragma unroll
+                for (int nb = 0; nb < NB16; ++nb)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) acc16[mb][nb][r] = 0.f;
+            // the compiler does not know the hand-written MFMAs' latencies: wait states between the zeroing moves
+            // and the first MFMA that reads them, and between the last MFMAs and the epilogue's accumulator reads
+            SB();
+            asm volatile("s_nop 7");
+            SB();
+            for (int kt = 0; kt < KT; ++kt) MOE_EP_STEP16(true)
+            SB();
+            asm volatile("s_nop 15");
+            asm volatile("s_nop 15");
+            SB();
+        }
 
         // epilogue: a lane holds token row (lane & 31) of each block and, per register quad q,
         // output columns 8q + 4*(lane >> 5) + {0..3} of the block.  Two quads are exchanged between
@@ -482,7 +601,68 @@ __device__ __forceinline__ void gemm_tiles(const GemmArgs& a, uint4* lds, const 
         // 16, and the store path of the CU, which is what the epilogue waits for, sees half the
         // requests.  A tile whose columns all lie inside N (the usual case, decided once per tile)
         // stores without per-store column tests.
-        {
+        if constexpr (MI == 16) {
+            // 16 x 16 blocks: a lane holds token row (lane & 15) of each block and output columns
+            // 4 * (lane >> 4) + {0..3} of it.  Two neighbouring column blocks exchange halves between the
+            // rows of 16 lanes (v_permlane16_swap: rows 1 and 3 of the first operand against rows 0 and 2 of
+            // the second), after which a lane holds 8 consecutive columns of one of the two blocks and a
+            // store instruction carries 64 contiguous bytes per token row.
+            const int g4 = fr_kh;
+            const int n_wave = cur.n0 + wn * (SWIGLU ? Cfg::WTN / 2 : Cfg::WTN);
+            uint16_t* Cg = a.C + (size_t)cur.g * a.c_group_col_stride + n_wave;
+            auto store_tile16 = [&](auto guard_n) {
+                constexpr bool GUARD_N = decltype(guard_n)::value;
+#pragma unroll
+                for (int mb = 0; mb < MB16; ++mb) {
+                    // a row of blocks is pinned in its accumulator registers right before its turn
+                    if constexpr (NB16 == 8)
+                        asm volatile("; accumulator row %8" : "+a"(acc16[mb][0]), "+a"(acc16[mb][1]), "+a"(acc16[mb][2]), "+a"(acc16[mb][3]),
+                                     "+a"(acc16[mb][NB16 > 4 ? 4 : 0]), "+a"(acc16[mb][NB16 > 5 ? 5 : 1]), "+a"(acc16[mb][NB16 > 6 ? 6 : 2]), "+a"(acc16[mb][NB16 > 7 ? 7 : 3]) : "n"(mb));
+                    else if constexpr (NB16 == 4)
+                        asm volatile("; accumulator row %4" : "+a"(acc16[mb][0]), "+a"(acc16[mb][1]), "+a"(acc16[mb][2]), "+a"(acc16[mb][3]) : "n"(mb));
+                    if (RAGGED && mb >= 2 * cur.hb) continue;
+                    const int m = (RAGGED ? wm * cur.hb * 32 : wm * Cfg::WTM) + mb * 16 + fr_row;
+                    if (m >= cur.nrows) continue;  // the same for the lanes of an exchange (they share lane & 15)
+                    if (EPI == 1) {
+                        float* frow = reinterpret_cast<float*>(a.C) + (size_t)cur.g * a.c_group_col_stride +
+                                      (size_t)(cur.row0 + m) * a.ldc + cur.n0 + wn * Cfg::WTN + g4 * 4;
+#pragma unroll
+                        for (int nb = 0; nb < NB16; ++nb) {
+                            if (GUARD_N && cur.n0 + wn * Cfg::WTN + g4 * 4 + nb * 16 >= a.N) continue;
+                            *reinterpret_cast<f32x4_t*>(frow + nb * 16) = acc16[mb][nb];
+                        }
+                        continue;
+                    }
+                    const float rw = EPI == 2 ? a.row_weight[a.row_assignment[cur.row0 + m]] : 1.0f;
+                    uint16_t* crow = Cg + (size_t)(cur.row0 + m) * a.ldc;
+#pragma unroll
+                    for (int nb = 0; nb < (SWIGLU ? NB16 / 2 : NB16); nb += 2) {
+                        uint32_t pk[2][2];  // [block nb, nb + 1][column pair]
+#pragma unroll
+                        for (int j = 0; j < 2; ++j) {
+                            float h[4];
+#pragma unroll
+                            for (int i = 0; i < 4; ++i)
+                                h[i] = SWIGLU ? silu_f(acc16[mb][nb + j][i]) * acc16[mb][nb + j + NB16 / 2][i]
+                                     : EPI == 2 ? rw * acc16[mb][nb + j][i]
+                                                : acc16[mb][nb + j][i];
+                            pk[j][0] = pack_bf16x2(h[0], h[1]);
+                            pk[j][1] = pack_bf16x2(h[2], h[3]);
+                        }
+                        const auto s0 = __builtin_amdgcn_permlane16_swap(pk[0][0], pk[1][0], false, false);
+                        const auto s1 = __builtin_amdgcn_permlane16_swap(pk[0][1], pk[1][1], false, false);
+                        // rows of lanes 0 / 2 now hold columns 0..7 / 8..15 of block nb, rows 1 / 3 those of block nb + 1
+                        const int col = (nb + (g4 & 1)) * 16 + (g4 >> 1) * 8;
+                        if (GUARD_N && n_wave + col >= a.N) continue;
+                        uint4 o;
+                        o.x = s0[0]; o.y = s1[0]; o.z = s0[1]; o.w = s1[1];
+                        *reinterpret_cast<uint4*>(crow + col) = o;
+                    }
+                }
+            };
+            if (cur.n0 + Cfg::BN_OUT <= a.N) store_tile16(std::false_type{});
+            else store_tile16(std::true_type{});
+        } else {
             const int n_lane = cur.n0 + wn * (SWIGLU ? Cfg::WTN / 2 : Cfg::WTN) + fr_kh * 8;
             uint16_t* Cg = a.C + (size_t)cur.g * a.c_group_col_stride + n_lane;
             auto store_tile = [&](auto guard_n) {
@@ -553,14 +733,17 @@ __device__ __forceinline__ void gemm_tiles(const GemmArgs& a, uint4* lds, const 
     MOE_EP_WAIT_VMCNT_LGKM0(0);
 #undef MOE_EP_HANDOVER
 #undef MOE_EP_STEP
+#undef MOE_EP_STEP16
 #undef MOE_EP_FRAG_ORDER
+#undef MOE_EP_FRAG_ORDER16
+#undef MOE_EP_FRAG16
 #undef SB
 #undef MOE_EP_ISSUE1
 #undef MOE_EP_FRAG1
 }
 
 
-template <int BM, int BN, int BK, int STAGES, int WGM, int WGN, bool SWIGLU, bool RAGGED, int EPI = 0, bool PACKED = false>
+template <int BM, int BN, int BK, int STAGES, int WGM, int WGN, bool SWIGLU, bool RAGGED, int EPI = 0, bool PACKED = false, int MI = 32>
 __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_kernel(GemmArgs a)
 {
     extern __shared__ uint4 lds[];
@@ -568,7 +751,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void grouped_gemm_kernel(GemmArgs a)
     const LdsTables t = lds_tables(lds, Cfg::LDS_BYTES, a.G);
     const int max_units = (a.max_units > 0 && a.max_units < Cfg::MB) ? a.max_units : Cfg::MB;
     if (RAGGED) fill_tables(a, t, 32 * WGM, max_units);
-    gemm_tiles<BM, BN, BK, STAGES, WGM, WGN, SWIGLU, RAGGED, EPI, PACKED>(a, lds, t.pref, t.row0, t.rowend, t.tile, max_units);
+    gemm_tiles<BM, BN, BK, STAGES, WGM, WGN, SWIGLU, RAGGED, EPI, PACKED, MI>(a, lds, t.pref, t.row0, t.rowend, t.tile, max_units);
 }
 
 // what every kernel here assumes of its arguments beyond the shapes the caller has checked
@@ -584,7 +767,7 @@ static bool args_fit(const GemmArgs& a, bool swiglu, bool ragged, int bm)
     return !(a.N % 8 || a.ldc % 8 || a.c_group_col_stride % 8 || (reinterpret_cast<uintptr_t>(a.C) & 15));
 }
 
-template <int BM, int BN, int BK, int STAGES, int WGM, int WGN, bool SWIGLU, bool RAGGED, int EPI = 0, bool PACKED = false>
+template <int BM, int BN, int BK, int STAGES, int WGM, int WGN, bool SWIGLU, bool RAGGED, int EPI = 0, bool PACKED = false, int MI = 32>
 static hipError_t launch_one(const GemmArgs& a, int n_cu, long long max_rows, hipStream_t s)
 {
     using Cfg = GemmCfg<BM, BN, BK, STAGES, WGM, WGN, SWIGLU>;
@@ -606,18 +789,18 @@ static hipError_t launch_one(const GemmArgs& a, int n_cu, long long max_rows, hi
     long long grid = (long long)n_cu * occ;
     if (grid > max_tiles) grid = max_tiles;
     grid = (grid + 7) / 8 * 8;
-    hipLaunchKernelGGL((grouped_gemm_kernel<BM, BN, BK, STAGES, WGM, WGN, SWIGLU, RAGGED, EPI, PACKED>),
+    hipLaunchKernelGGL((grouped_gemm_kernel<BM, BN, BK, STAGES, WGM, WGN, SWIGLU, RAGGED, EPI, PACKED, MI>),
                        dim3((unsigned)grid), dim3(Cfg::THREADS), lds_bytes, s, a);
     return hipGetLastError();
 }
 
-template <int BM, int BN, int BK, int STAGES, int WGM, int WGN, bool PACKED>
+template <int BM, int BN, int BK, int STAGES, int WGM, int WGN, bool PACKED, int MI>
 static hipError_t raise_all()
 {
     hipError_t e;
 #define R(SW, RG, EPI)                                                                                  \
     if ((e = hipFuncSetAttribute(                                                                       \
-             reinterpret_cast<const void*>(&grouped_gemm_kernel<BM, BN, BK, STAGES, WGM, WGN, SW, RG, EPI, PACKED>), \
+             reinterpret_cast<const void*>(&grouped_gemm_kernel<BM, BN, BK, STAGES, WGM, WGN, SW, RG, EPI, PACKED, MI>), \
              hipFuncAttributeMaxDynamicSharedMemorySize,                                                \
              lds_cap(GemmCfg<BM, BN, BK, STAGES, WGM, WGN, SW>::LDS_BYTES +                             \
                      lds_table_bytes(RG, kMaxGroups)))) != hipSuccess) return e;
@@ -627,7 +810,7 @@ static hipError_t raise_all()
 }
 
 // PK: the variant also exists for weights in tile order (its weight tile is kPackRows x kPackK)
-template <int BM, int BN, int BK, int STAGES, int WGM, int WGN, bool PK>
+template <int BM, int BN, int BK, int STAGES, int WGM, int WGN, bool PK, int MI>
 static hipError_t launch_cfg(const GemmArgs& a, bool swiglu, int n_cu, long long max_rows, hipStream_t s)
 {
     const bool ragged = a.offset != nullptr;
@@ -637,12 +820,12 @@ static hipError_t launch_cfg(const GemmArgs& a, bool swiglu, int n_cu, long long
         return hipErrorInvalidValue;
     auto go = [&](auto packed) -> hipError_t {
         constexpr bool P = decltype(packed)::value;
-        if (swiglu) return ragged ? launch_one<BM, BN, BK, STAGES, WGM, WGN, true, true, 0, P>(a, n_cu, max_rows, s)
-                                  : launch_one<BM, BN, BK, STAGES, WGM, WGN, true, false, 0, P>(a, n_cu, max_rows, s);
-        if (a.epi == 1) return launch_one<BM, BN, BK, STAGES, WGM, WGN, false, true, 1, P>(a, n_cu, max_rows, s);
-        if (a.epi == 2) return launch_one<BM, BN, BK, STAGES, WGM, WGN, false, true, 2, P>(a, n_cu, max_rows, s);
-        return ragged ? launch_one<BM, BN, BK, STAGES, WGM, WGN, false, true, 0, P>(a, n_cu, max_rows, s)
-                      : launch_one<BM, BN, BK, STAGES, WGM, WGN, false, false, 0, P>(a, n_cu, max_rows, s);
+        if (swiglu) return ragged ? launch_one<BM, BN, BK, STAGES, WGM, WGN, true, true, 0, P, MI>(a, n_cu, max_rows, s)
+                                  : launch_one<BM, BN, BK, STAGES, WGM, WGN, true, false, 0, P, MI>(a, n_cu, max_rows, s);
+        if (a.epi == 1) return launch_one<BM, BN, BK, STAGES, WGM, WGN, false, true, 1, P, MI>(a, n_cu, max_rows, s);
+        if (a.epi == 2) return launch_one<BM, BN, BK, STAGES, WGM, WGN, false, true, 2, P, MI>(a, n_cu, max_rows, s);
+        return ragged ? launch_one<BM, BN, BK, STAGES, WGM, WGN, false, true, 0, P, MI>(a, n_cu, max_rows, s)
+                      : launch_one<BM, BN, BK, STAGES, WGM, WGN, false, false, 0, P, MI>(a, n_cu, max_rows, s);
     };
     if constexpr (PK) {
         if (a.Wp != nullptr) return go(std::true_type{});
@@ -659,23 +842,26 @@ static hipError_t launch_cfg(const GemmArgs& a, bool swiglu, int n_cu, long long
 // listed in the column before the last.  Last column: the variant is also built for weights in tile
 // order (kernels.h: the shapes the library picks by itself; the others read the caller's layout).
 #define MOE_EP_VARIANTS(X)         \
-    X(0, 64, 128, 64, 2, 1, 2, 8, false)  \
-    X(1, 128, 256, 64, 3, 2, 2, 6, true) \
-    X(2, 256, 256, 64, 2, 2, 2, 9, true) \
-    X(6, 128, 256, 32, 2, 2, 2, 6, false) \
-    X(8, 64, 128, 32, 2, 1, 2, 8, false)  \
-    X(9, 256, 256, 32, 2, 2, 2, 9, false)  \
-    X(11, 160, 256, 64, 3, 1, 4, 12, true) \
-    X(12, 160, 256, 32, 2, 1, 2, 12, false) \
-    X(13, 224, 256, 64, 2, 1, 4, 12, false) \
-    X(14, 256, 256, 64, 2, 1, 4, 12, false)
+    X(0, 64, 128, 64, 2, 1, 2, 8, false, 32)  \
+    X(1, 128, 256, 64, 3, 2, 2, 6, true, 32) \
+    X(2, 256, 256, 64, 2, 2, 2, 9, true, 32) \
+    X(6, 128, 256, 32, 2, 2, 2, 6, false, 32) \
+    X(8, 64, 128, 32, 2, 1, 2, 8, false, 32)  \
+    X(9, 256, 256, 32, 2, 2, 2, 9, false, 32)  \
+    X(11, 160, 256, 64, 3, 1, 4, 12, true, 32) \
+    X(12, 160, 256, 32, 2, 1, 2, 12, false, 32) \
+    X(13, 224, 256, 64, 2, 1, 4, 12, false, 32) \
+    X(14, 256, 256, 64, 2, 1, 4, 12, false, 32) \
+    X(21, 128, 256, 64, 3, 2, 2, 6, true, 16) \
+    X(22, 256, 256, 64, 2, 2, 2, 9, true, 16) \
+    X(31, 160, 256, 64, 3, 1, 4, 12, true, 16)
 
 hipError_t grouped_gemm_init()
 {
     hipError_t e;
-#define X(id, BM, BN, BK, ST, WGM, WGN, FB, PK)                                          \
-    if ((e = raise_all<BM, BN, BK, ST, WGM, WGN, false>()) != hipSuccess) return e;      \
-    if constexpr (PK) if ((e = raise_all<BM, BN, BK, ST, WGM, WGN, PK>()) != hipSuccess) return e;
+#define X(id, BM, BN, BK, ST, WGM, WGN, FB, PK, MI)                                      \
+    if ((e = raise_all<BM, BN, BK, ST, WGM, WGN, false, MI>()) != hipSuccess) return e;  \
+    if constexpr (PK) if ((e = raise_all<BM, BN, BK, ST, WGM, WGN, PK, MI>()) != hipSuccess) return e;
     MOE_EP_VARIANTS(X)
 #undef X
     return hipSuccess;
@@ -684,7 +870,7 @@ hipError_t grouped_gemm_init()
 bool grouped_gemm_variant_shape(int variant, int K, bool ragged, int G, int shape[7])
 {
     switch (variant) {
-#define X(id, BM, BN, BK, ST, WGM, WGN, FB, PK)                                                      \
+#define X(id, BM, BN, BK, ST, WGM, WGN, FB, PK, MI)                                                  \
         case id:                                                                                    \
             if (K / BK < ST || GemmCfg<BM, BN, BK, ST, WGM, WGN, false>::LDS_BYTES +                \
                                        lds_table_bytes(ragged, G) > kLdsPerWorkgroup) {              \
@@ -706,14 +892,14 @@ hipError_t launch_grouped_gemm(const GemmArgs& a, bool swiglu, int variant, int 
     if (a.K < 64 || a.K % 64) return hipErrorInvalidValue;
     if (a.offset ? max_rows <= 0 : a.dense_rows <= 0) return hipSuccess;
     switch (variant) {
-#define X(id, BM, BN, BK, ST, WGM, WGN, FB, PK)                                                      \
+#define X(id, BM, BN, BK, ST, WGM, WGN, FB, PK, MI)                                                  \
         case id:                                                                                    \
             if (a.K / BK < ST || GemmCfg<BM, BN, BK, ST, WGM, WGN, false>::LDS_BYTES +              \
                                          lds_table_bytes(a.offset != nullptr, a.G) > kLdsPerWorkgroup) { \
                 if (FB == id) return hipErrorInvalidValue;                                          \
                 return launch_grouped_gemm(a, swiglu, FB, n_cu, max_rows, s);                  \
             }                                                                                       \
-            return launch_cfg<BM, BN, BK, ST, WGM, WGN, PK>(a, swiglu, n_cu, max_rows, s);
+            return launch_cfg<BM, BN, BK, ST, WGM, WGN, PK, MI>(a, swiglu, n_cu, max_rows, s);
         MOE_EP_VARIANTS(X)
 #undef X
         default: return hipErrorInvalidValue;

@@ -196,7 +196,7 @@ def test_maximum_expert_count_and_top_k():
 
 
 @pytest.mark.parametrize("prepared", [False, True])
-@pytest.mark.parametrize("variant", [0, 1, 2, 6, 8, 9, 11, 12, 13, 14])
+@pytest.mark.parametrize("variant", [0, 1, 2, 6, 8, 9, 11, 12, 13, 14, 21, 22, 31])
 @pytest.mark.parametrize("hidden", [64, 128, 192, 320])
 def test_every_tile_variant_matches_oracle(variant, hidden, prepared):
     """Each instantiated tile shape / ring depth of the grouped GEMM (11, 12: 160-row tiles held by 1 x 4
@@ -247,7 +247,7 @@ def test_tile_shape_does_not_change_a_bit():
     old = os.environ.get("MOE_EP_GEMM_VARIANT")
     outs = {}
     try:
-        for variant in (None, 0, 1, 2, 6, 11, 12, 13, 14):
+        for variant in (None, 0, 1, 2, 6, 11, 12, 13, 14, 21, 22, 31):
             if variant is None:
                 os.environ.pop("MOE_EP_GEMM_VARIANT", None)
             else:
@@ -318,7 +318,7 @@ def pkg_error():
 
 
 @pytest.mark.parametrize("variant,units", [(14, 0), (14, 7), (14, 3), (14, 1), (2, 0), (2, 3), (2, 1), (13, 5), (11, 2),
-                                           (1, 1)])
+                                           (1, 1), (31, 0), (31, 2), (22, 0), (22, 3), (21, 1)])
 def test_row_tiles_cut_to_fit_the_experts(variant, units):
     """Row tiles are cut per expert to equal heights in units of 32 rows per row of wavefronts, at most
     `units` of them (0: as many as the variant holds): expert loads that are empty, one row, exact
