@@ -40,7 +40,8 @@ def kernel_name(ctx, stage):
     epi = {"f": 1, "s": 2}.get(os.environ.get("MOE_EP_EXPERT_OUT", " ")[0], 0) if stage == "routed_down_gemm" else 0
     # and whether the weights are read from a tile-order copy (moe_ep_prepare_weights)
     return (f"grouped_gemm_kernel<{sh['rows']}, {sh['cols']}, {sh['k_step']}, {sh['ring_slots']}, "
-            f"{sh['waves_m']}, {sh['waves_n']}, {swiglu}, {ragged}, {epi}, {'true' if sh['tile_order'] else 'false'}>")
+            f"{sh['waves_m']}, {sh['waves_n']}, {swiglu}, {ragged}, {epi}, {'true' if sh['tile_order'] else 'false'}, "
+            f"{sh['mfma_rows']}>")
 
 
 def measured_traffic(workload, r_chunks, stage, kernel):

@@ -361,13 +361,14 @@ int32_t moe_ep_routed_tile_rows(const moe_ep_config *cfg, int32_t n_tokens, int3
  * (2 routed gate/up, 3 routed down, 4 shared gate/up, 5 shared down; Sec. 3.1, Eq. moe_detail and
  * Eq. shared_detail), chunk = the chunk of that forward (ignored for the shared experts).  Receives
  * the kernel's tile shape -- tallest tile rows, weight rows per tile, K step, LDS ring slots,
- * wavefronts along rows and along columns -- and whether it read the weights from a tile-order copy
- * (moe_ep_prepare_weights; 1 or 0), so that a measurement can name the kernel it timed.
- * Any pointer may be NULL.  MOE_EP_ESTATE before any forward or for a stage the layer does not have.
+ * wavefronts along rows and along columns --, whether it read the weights from a tile-order copy
+ * (moe_ep_prepare_weights; 1 or 0), and the rows of the block its matrix instruction multiplies (16:
+ * v_mfma_f32_16x16x32_bf16, 32: v_mfma_f32_32x32x16_bf16), so that a measurement can name the kernel it
+ * timed.  Any pointer may be NULL.  MOE_EP_ESTATE before any forward or for a stage the layer does not have.
  */
 int moe_ep_last_tile_shape(const moe_ep_ctx *ctx, int32_t chunk, int32_t stage, int32_t *rows,
                            int32_t *cols, int32_t *k_step, int32_t *ring_slots, int32_t *waves_m,
-                           int32_t *waves_n, int32_t *tile_order);
+                           int32_t *waves_n, int32_t *tile_order, int32_t *mfma_rows);
 
 int moe_ep_forward_dep(moe_ep_ctx *ctx, const void *tokens, const float *gate_logits,
                        const void *routed_w, const void *shared_w, int32_t top_k, int32_t r_1,

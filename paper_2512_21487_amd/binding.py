@@ -127,7 +127,7 @@ def load_library() -> ctypes.CDLL:
     lib.moe_ep_routed_tile_rows.restype = i32
     lib.moe_ep_routed_tile_rows.argtypes = [cfgp, i32, i32, i32, i32]
     lib.moe_ep_last_tile_shape.restype = ctypes.c_int
-    lib.moe_ep_last_tile_shape.argtypes = [vp, i32, i32] + [ctypes.POINTER(i32)] * 7
+    lib.moe_ep_last_tile_shape.argtypes = [vp, i32, i32] + [ctypes.POINTER(i32)] * 8
     lib.moe_ep_get_routing.restype = ctypes.c_int
     lib.moe_ep_get_routing.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp]
     lib.moe_ep_set_profiling.restype = ctypes.c_int
@@ -474,13 +474,13 @@ class MoeEp:
     def last_tile_shape(self, stage: str, chunk: int = 0) -> Optional[Dict[str, int]]:
         """Tile shape of the kernel the last forward launched for `stage` (an entry of STAGES naming a
         projection); None if the layer has no such stage."""
-        v = [ctypes.c_int32() for _ in range(7)]
+        v = [ctypes.c_int32() for _ in range(8)]
         rc = self._lib.moe_ep_last_tile_shape(self._ctx, chunk, STAGES.index(stage), *[ctypes.byref(x) for x in v])
         if rc == -4:
             return None
         if rc != 0:
             raise MoeEpError(rc, "moe_ep_last_tile_shape: bad arguments")
-        return dict(zip(("rows", "cols", "k_step", "ring_slots", "waves_m", "waves_n", "tile_order"),
+        return dict(zip(("rows", "cols", "k_step", "ring_slots", "waves_m", "waves_n", "tile_order", "mfma_rows"),
                         (x.value for x in v)))
 
     # -- timing model ---------------------------------------------------------------------

@@ -76,7 +76,22 @@ struct GemmCfg {
     // blocks of 16 x 16, a K step is KK32 steps of 32, the hand-over sits three quarters through the
     // K step's SLOTS16 MFMAs and the loads are spread over the three quarters that follow it.
     static constexpr int MB16 = WTM / 16, NB16 = WTN / 16, KK32 = BK / 32;
-    static constexpr int SLOTS16 = KK32 * MB16 * NB16, HO16 = SLOTS16 - SLOTS16 / 4, WINDOW16 = HO16;
+#ifndef MOE_EP_TAIL16_DEN   /* tuning: the part of a K step's MFMAs behind the hand-over, the part the loads are spread over */
+#define MOE_EP_TAIL16_NUM 1
+#define MOE_EP_TAIL16_DEN 4
+#endif
+#ifndef MOE_EP_WIN16_DEN
+#define MOE_EP_WIN16_NUM 3
+#define MOE_EP_WIN16_DEN 4
+#endif
+#ifndef MOE_EP_RD16_STRIDE
+#define MOE_EP_RD16_STRIDE 2
+#endif
+    static constexpr int SLOTS16 = KK32 * MB16 * NB16;
+    static constexpr int TAIL16 = SLOTS16 * MOE_EP_TAIL16_NUM / MOE_EP_TAIL16_DEN > MB16 + NB16 ? SLOTS16 * MOE_EP_TAIL16_NUM / MOE_EP_TAIL16_DEN : MB16 + NB16;
+    static constexpr int HO16 = SLOTS16 - TAIL16;
+    static constexpr int WINDOW16 = SLOTS16 * MOE_EP_WIN16_NUM / MOE_EP_WIN16_DEN > RPW ? SLOTS16 * MOE_EP_WIN16_NUM / MOE_EP_WIN16_DEN : RPW;
+    static constexpr int RD16 = MOE_EP_RD16_STRIDE * (MB16 + NB16) <= MB16 * NB16 ? MOE_EP_RD16_STRIDE : MB16 * NB16 / (MB16 + NB16);
     static constexpr int load_at16(int p)
     {
         const int l = (p * RPW + WINDOW16 - 1) / WINDOW16;
@@ -190,7 +205,7 @@ __device__ __forceinline__ void gemm_tiles(const GemmArgs& a, uint4* lds, const 
     constexpr int RPR = Cfg::RPR, KKW = Cfg::KKW;
     constexpr int MB16 = Cfg::MB16, NB16 = Cfg::NB16, KK32 = Cfg::KK32, SLOTS16 = Cfg::SLOTS16, HO16 = Cfg::HO16;
     static_assert(MI == 32 || MI == 16, "v_mfma_f32_32x32x16_bf16 or v_mfma_f32_16x16x32_bf16");
-    static_assert(MI == 32 || (BK == 64 && Cfg::RPW <= Cfg::WINDOW16 && MB16 + NB16 <= SLOTS16 / 4 && NB16 % 2 == 0 &&
+    static_assert(MI == 32 || (BK == 64 && Cfg::RPW <= Cfg::WINDOW16 && Cfg::WINDOW16 <= SLOTS16 && MB16 + NB16 <= Cfg::TAIL16 && NB16 % 2 == 0 &&
                                (!SWIGLU || NB16 % 4 == 0)),
                   "16 x 16 blocks: a K step is two steps of 32 (fragment sets 0 and 1), its loads and the next K step's "
                   "first fragment reads fit their windows, column blocks pair up for the stores");
@@ -485,7 +500,7 @@ __device__ __forceinline__ void gemm_tiles(const GemmArgs& a, uint4* lds, const 
         const int st_next = stage == STAGES - 1 ? 0 : stage + 1;                                  \
         const uint4* sN = lds + st_next * Cfg::STAGE_CHUNKS;                                      \
         const int st_prev = stage == 0 ? STAGES - 1 : stage - 1;                                  \
-        constexpr int RS_ = (SLOTS16 / 4) / (MB16 + NB16);   /* MFMAs per prefetch read */        \
+        constexpr int RS_ = Cfg::TAIL16 / (MB16 + NB16);   /* MFMAs per prefetch read */          \
         _Pragma("unroll") for (int j = 0; j < KK32; ++j) {                                        \
             _Pragma("unroll") for (int q = 0; q < MB16 * NB16; ++q) {                             \
                 const int m_ = j * MB16 * NB16 + q;                                               \
@@ -505,8 +520,8 @@ __device__ __forceinline__ void gemm_tiles(const GemmArgs& a, uint4* lds, const 
                 asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0"                             \
                              : "+a"(acc16[mb][nb]) : "v"(wf16[j & 1][nb]), "v"(xf16[j & 1][mb])); \
                 if (j + 1 < KK32) {                                                               \
-                    if (q % 2 == 0 && q / 2 < MB16 + NB16)                                        \
-                        MOE_EP_FRAG16(sT, j + 1, (j + 1) & 1, MOE_EP_FRAG_ORDER16(q / 2))         \
+                    if (q % Cfg::RD16 == 0 && q / Cfg::RD16 < MB16 + NB16)                        \
+                        MOE_EP_FRAG16(sT, j + 1, (j + 1) & 1, MOE_EP_FRAG_ORDER16(q / Cfg::RD16)) \
                 } else if (prefetch_) {                                                           \
                     const int f_ = m_ - HO16;                                                     \
                     if (f_ >= 0 && f_ % RS_ == 0 && f_ / RS_ < MB16 + NB16)                       \
@@ -867,7 +882,7 @@ hipError_t grouped_gemm_init()
     return hipSuccess;
 }
 
-bool grouped_gemm_variant_shape(int variant, int K, bool ragged, int G, int shape[7])
+bool grouped_gemm_variant_shape(int variant, int K, bool ragged, int G, int shape[8])
 {
     switch (variant) {
 #define X(id, BM, BN, BK, ST, WGM, WGN, FB, PK, MI)                                                  \
@@ -878,12 +893,17 @@ bool grouped_gemm_variant_shape(int variant, int K, bool ragged, int G, int shap
                 return grouped_gemm_variant_shape(FB, K, ragged, G, shape);                         \
             }                                                                                       \
             shape[0] = BM; shape[1] = BN; shape[2] = BK; shape[3] = ST; shape[4] = WGM; shape[5] = WGN; \
-            shape[6] = PK;                                                                          \
+            shape[6] = PK; shape[7] = MI;                                                           \
             return true;
         MOE_EP_VARIANTS(X)
 #undef X
         default: return false;
     }
+}
+
+int grouped_gemm_variant_mfma16(int variant)
+{
+    return variant == 1 ? 21 : variant == 2 ? 22 : variant == 11 ? 31 : variant;
 }
 
 hipError_t launch_grouped_gemm(const GemmArgs& a, bool swiglu, int variant, int n_cu,

@@ -83,9 +83,12 @@ hipError_t launch_grouped_gemm(const GemmArgs& a, bool swiglu, int variant, int 
                                long long max_rows, hipStream_t s);
 hipError_t grouped_gemm_init();   // raises the dynamic-LDS limit of every instantiation once
 // the shape a launch of `variant` really runs (after the fall-backs for a short K or many groups):
-// shape[] = tallest tile rows, weight rows per tile, K step, ring slots, wavefronts in m, in n, and
-// whether it reads weights in tile order when the launch has them (GemmArgs::Wp); false for an
+// shape[] = tallest tile rows, weight rows per tile, K step, ring slots, wavefronts in m, in n,
+// whether it reads weights in tile order when the launch has them (GemmArgs::Wp), and the rows of the
+// matrix instruction's block (32: v_mfma_f32_32x32x16_bf16, 16: v_mfma_f32_16x16x32_bf16); false for an
 // unknown variant
-bool grouped_gemm_variant_shape(int variant, int K, bool ragged, int G, int shape[7]);
+bool grouped_gemm_variant_shape(int variant, int K, bool ragged, int G, int shape[8]);
+// the variant of the same tile shape that multiplies with the 16 x 16 x 32 instruction, or `variant` itself
+int grouped_gemm_variant_mfma16(int variant);
 
 }  // namespace moe_ep

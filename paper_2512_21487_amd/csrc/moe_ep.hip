@@ -35,6 +35,10 @@ struct moe_ep_ctx {
     int up_variant = -1, down_variant = -1;  // the same for one projection only (tuning)
     int up_units = 0, down_units = 0;        // tallest row tile in units (0 = chosen / the variant's height)
     int shared_variant = 2;  // shared experts: dense rows, 256-row tiles
+    // the shapes the library picks by itself multiply with v_mfma_f32_16x16x32_bf16 (MOE_EP_MFMA=32: with
+    // v_mfma_f32_32x32x16_bf16); a shape named through a knob is taken as named
+    bool mfma16 = true;
+    bool shared_variant_named = false;
     bool fused_gather = true;  // the gate/up projection gathers the token rows itself (no grouped copy)
     int y_mode = 0;            // expert outputs: 0 bf16, 1 fp32, 2 bf16 scaled by the routing weight (expert_out_mode)
     // pinned-host mode, moe_ep_forward: the aggregation writes its rows straight into the caller's host
@@ -168,7 +172,9 @@ void read_knobs(moe_ep_ctx* ctx)
 {
     // tile-shape overrides for tuning (indices into the variant table of grouped_gemm.hip)
     if (const char* v = getenv("MOE_EP_GEMM_VARIANT")) ctx->gemm_variant = atoi(v);
-    if (const char* v = getenv("MOE_EP_SHARED_VARIANT")) ctx->shared_variant = atoi(v);
+    if (const char* v = getenv("MOE_EP_SHARED_VARIANT")) { ctx->shared_variant = atoi(v); ctx->shared_variant_named = true; }
+    if (const char* v = getenv("MOE_EP_MFMA")) ctx->mfma16 = atoi(v) != 32;
+    if (!ctx->shared_variant_named && ctx->mfma16) ctx->shared_variant = grouped_gemm_variant_mfma16(ctx->shared_variant);
     if (const char* v = getenv("MOE_EP_UP_VARIANT")) ctx->up_variant = atoi(v);
     if (const char* v = getenv("MOE_EP_DOWN_VARIANT")) ctx->down_variant = atoi(v);
     if (const char* v = getenv("MOE_EP_UP_UNITS")) ctx->up_units = atoi(v);
@@ -317,7 +323,7 @@ void prof_end(moe_ep_ctx* ctx, int span, hipStream_t s)
 
 extern "C" {
 
-const char* moe_ep_version(void) { return "0.2"; }
+const char* moe_ep_version(void) { return "0.3"; }
 
 int moe_ep_validate_config(const moe_ep_config* c, const char** why)
 {
@@ -772,8 +778,10 @@ int forward_impl(moe_ep_ctx* ctx, const void* tokens, const float* gate_logits, 
         else if (dep && cidx % r_2 == 0) HIP_TRY(ctx, hipStreamWaitEvent(s_comp, ctx->ev_attn[cidx / r_2], 0));
         // tile shapes of the two routed projections: N = H in tiles of 128 activation columns, N = M in
         // tiles of 256 columns
-        int v_up = ctx->gemm_variant >= 0 ? ctx->gemm_variant : routed_variant(Tn, k, E, El, (H + 127) / 128, M, n_cu);
-        int v_down = ctx->gemm_variant >= 0 ? ctx->gemm_variant : routed_variant(Tn, k, E, El, (M + 255) / 256, H, n_cu);
+        // a shape the library picks itself is taken in its 16 x 16 x 32 form, one named through a knob as named
+        const auto picked = [&](int v) { return ctx->mfma16 ? grouped_gemm_variant_mfma16(v) : v; };
+        int v_up = ctx->gemm_variant >= 0 ? ctx->gemm_variant : picked(routed_variant(Tn, k, E, El, (H + 127) / 128, M, n_cu));
+        int v_down = ctx->gemm_variant >= 0 ? ctx->gemm_variant : picked(routed_variant(Tn, k, E, El, (M + 255) / 256, H, n_cu));
         if (ctx->up_variant >= 0) v_up = ctx->up_variant;
         if (ctx->down_variant >= 0) v_down = ctx->down_variant;
         if (cidx < (int)ctx->last_variants.size()) ctx->last_variants[cidx] = {v_up, v_down};
@@ -893,7 +901,7 @@ int32_t moe_ep_routed_tile_rows(const moe_ep_config* cfg, int32_t n_tokens, int3
 
 int moe_ep_last_tile_shape(const moe_ep_ctx* ctx, int32_t chunk, int32_t stage, int32_t* rows, int32_t* cols,
                            int32_t* k_step, int32_t* ring_slots, int32_t* waves_m, int32_t* waves_n,
-                           int32_t* tile_order)
+                           int32_t* tile_order, int32_t* mfma_rows)
 {
     if (!ctx || stage < ST_GEMM1 || stage > ST_SGEMM2) return MOE_EP_EINVAL;
     if (ctx->last_T < 0) return MOE_EP_ESTATE;
@@ -903,8 +911,9 @@ int moe_ep_last_tile_shape(const moe_ep_ctx* ctx, int32_t chunk, int32_t stage, 
     const moe_ep_config& c = ctx->cfg;
     const int variant = shared ? ctx->shared_variant : (up ? ctx->last_variants[chunk].up : ctx->last_variants[chunk].down);
     const int K = shared ? (up ? c.hidden : c.n_shared * c.shared_inter) : (up ? c.hidden : c.inter);
-    int v[7];
+    int v[8];
     if (!grouped_gemm_variant_shape(variant, K, !shared, shared ? 1 : c.n_local, v)) return MOE_EP_ESTATE;
+    if (mfma_rows) *mfma_rows = v[7];
     if (tile_order) *tile_order = v[6] && (shared ? ctx->last_prepared_shared : ctx->last_prepared_routed);
     if (rows) *rows = v[0];
     if (cols) *cols = v[1];
