@@ -241,6 +241,9 @@ def main() -> int:
     ap.add_argument("--dep", default=None, metavar="R1,R2,ATTN_US",
                     help="also run the layer as the disaggregated schedule (moe_ep_forward_dep): r_1 micro-batches of "
                          "r_2 chunks, attention stand-ins of ATTN_US microseconds, both orders, against the replay model")
+    ap.add_argument("--vendor-gemm", action="store_true",
+                    help="after the timed forwards, time the vendor library's plain GEMM (torch.matmul) on the two "
+                         "shared-expert projection shapes with the same operands, in turn (context, not the product)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one 1 GiB device-to-device copy kernel: the known-size reference "
                          "that rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled by")
@@ -590,6 +593,32 @@ def main() -> int:
             line["roofline"]["frac_of_measured_ceiling"] = roof["achieved"] / probe["copy_gbs"]
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(wl, inp)
+    if args.vendor_gemm and wl.n_shared > 0 and not pinned:
+        # Context: the vendor library's GEMM on the shapes of the two shared-expert launches, same token rows and
+        # weights, the two in turn as a forward runs them (no SwiGLU: its gate/up result is twice as wide).
+        Hs, Ns = wl.shared_inter, wl.n_shared
+        sw = shared.view(torch.bfloat16).reshape(Ns, 3 * Hs * M)
+        w_gu = torch.cat([sw[i, :2 * Hs * M].reshape(2 * Hs, M) for i in range(Ns)], 0).contiguous()
+        w_d = torch.cat([sw[i, 2 * Hs * M:].reshape(M, Hs) for i in range(Ns)], 1).contiguous()
+        x = tokens.view(torch.bfloat16)
+        act = (0.5 * torch.randn(T, Ns * Hs, device="cuda")).to(torch.bfloat16)
+        n_pairs = 40
+        evs = [torch.cuda.Event(enable_timing=True) for _ in range(3 * n_pairs)]
+        for i in range(n_pairs):
+            evs[3 * i].record()
+            _ = x @ w_gu.t()
+            evs[3 * i + 1].record()
+            _ = act @ w_d.t()
+            evs[3 * i + 2].record()
+        torch.cuda.synchronize()
+        tail = range(n_pairs // 4, n_pairs)
+        g_ms = sum(evs[3 * i].elapsed_time(evs[3 * i + 1]) for i in tail) / len(tail)
+        d_ms = sum(evs[3 * i + 1].elapsed_time(evs[3 * i + 2]) for i in tail) / len(tail)
+        line["vendor_gemm"] = {"what": "torch.matmul (hipBLASLt) on the shared-expert shapes, same operands, in turn",
+                               "gate_up_ms": g_ms, "gate_up_tflops": 4.0 * T * M * Ns * Hs / (g_ms * 1e-3) / 1e12,
+                               "down_ms": d_ms, "down_tflops": 2.0 * T * M * Ns * Hs / (d_ms * 1e-3) / 1e12,
+                               "library_gate_up_ms": stages["shared_gate_up_gemm"],
+                               "library_down_ms": stages["shared_down_gemm"]}
     if args.copy_probe:
         src = torch.ones(1 << 29, dtype=torch.int16, device="cuda")
         dst = torch.empty_like(src)

@@ -3,9 +3,13 @@
 // Eq. shared_detail).
 //
 // Both operands are K-contiguous in memory (activations [rows, K], weights [N, K]), which is
-// exactly what v_mfma_f32_32x32x16_bf16 wants per lane: 8 consecutive K values of one row.
+// exactly what the bf16 matrix instructions want per lane: 8 consecutive K values of one row.
 // The weight rows feed the instruction's first operand and the token rows the second, so a
-// lane ends up with 4 consecutive output columns of one token row -> 8-byte bf16 stores.
+// lane ends up with 4 consecutive output columns of one token row.  Two instruction shapes are
+// built (template argument MI): v_mfma_f32_16x16x32_bf16 for the shapes the library picks by
+// itself -- at the package power limit, where these launches run, it does the same work in the
+// same number of cycles at a higher clock, because a 16 x 16 block moves fewer accumulator
+// registers per multiply-add -- and v_mfma_f32_32x32x16_bf16.  The two give the same bits.
 //
 // One launch covers all experts.  Workgroups are persistent and walk a tile list that is
 // defined by device-side prefix sums (the host never learns the routing): tile id ->
@@ -73,24 +77,21 @@ struct GemmCfg {
         return (l < RPW && (l * WINDOW) / RPW == p) ? l : -1;
     }
     // The same K step out of v_mfma_f32_16x16x32_bf16 (MI == 16 below): a wavefront's tile is MB16 x NB16
-    // blocks of 16 x 16, a K step is KK32 steps of 32, the hand-over sits three quarters through the
-    // K step's SLOTS16 MFMAs and the loads are spread over the three quarters that follow it.
+    // blocks of 16 x 16, a K step is KK32 steps of 32, the hand-over sits TAIL16 MFMAs before the end of the
+    // K step's SLOTS16 MFMAs and the loads are spread over the WINDOW16 MFMAs that follow it.
     static constexpr int MB16 = WTM / 16, NB16 = WTN / 16, KK32 = BK / 32;
-#ifndef MOE_EP_TAIL16_DEN   /* tuning: the part of a K step's MFMAs behind the hand-over, the part the loads are spread over */
-#define MOE_EP_TAIL16_NUM 1
-#define MOE_EP_TAIL16_DEN 4
-#endif
-#ifndef MOE_EP_WIN16_DEN
-#define MOE_EP_WIN16_NUM 3
-#define MOE_EP_WIN16_DEN 4
-#endif
+    // Measured (DeepSeek-V2-shaped share): one row of four wavefronts (the routed experts' 160-row tiles) runs
+    // 1-2 % faster with the hand-over an eighth before the K step's end and the loads spread over seven eighths,
+    // two rows of two wavefronts (256-row tiles) 1-2 % faster with a quarter and three quarters.
+    static constexpr int SLOTS16 = KK32 * MB16 * NB16;
+    static constexpr int TAIL16_ = WGM == 1 ? SLOTS16 / 8 : SLOTS16 / 4;
+    static constexpr int TAIL16 = TAIL16_ > MB16 + NB16 ? TAIL16_ : MB16 + NB16;
+    static constexpr int HO16 = SLOTS16 - TAIL16;
+    static constexpr int WINDOW16_ = WGM == 1 ? SLOTS16 * 7 / 8 : SLOTS16 * 3 / 4;
+    static constexpr int WINDOW16 = WINDOW16_ > RPW ? WINDOW16_ : RPW;
 #ifndef MOE_EP_RD16_STRIDE
 #define MOE_EP_RD16_STRIDE 2
 #endif
-    static constexpr int SLOTS16 = KK32 * MB16 * NB16;
-    static constexpr int TAIL16 = SLOTS16 * MOE_EP_TAIL16_NUM / MOE_EP_TAIL16_DEN > MB16 + NB16 ? SLOTS16 * MOE_EP_TAIL16_NUM / MOE_EP_TAIL16_DEN : MB16 + NB16;
-    static constexpr int HO16 = SLOTS16 - TAIL16;
-    static constexpr int WINDOW16 = SLOTS16 * MOE_EP_WIN16_NUM / MOE_EP_WIN16_DEN > RPW ? SLOTS16 * MOE_EP_WIN16_NUM / MOE_EP_WIN16_DEN : RPW;
     static constexpr int RD16 = MOE_EP_RD16_STRIDE * (MB16 + NB16) <= MB16 * NB16 ? MOE_EP_RD16_STRIDE : MB16 * NB16 / (MB16 + NB16);
     static constexpr int load_at16(int p)
     {
@@ -490,9 +491,8 @@ __device__ __forceinline__ void gemm_tiles(const GemmArgs& a, uint4* lds, const 
 
     // The same K step out of 16 x 16 x 32 MFMAs: KK32 steps of 32, step j out of fragment set j & 1 while the
     // reads of step j + 1 are slipped behind every second of its first MFMAs.  The hand-over sits in front of
-    // MFMA HO16 (three quarters through the K step); the next K step's first fragments are read behind the
-    // MFMAs that follow it, the loads of the K step STAGES ahead start there and carry on over the first three
-    // quarters of the following K step (GemmCfg::load_at16).
+    // MFMA HO16; the next K step's first fragments are read behind the MFMAs that follow it, the loads of
+    // the K step STAGES ahead start there and carry on into the following K step (GemmCfg::load_at16).
 #define MOE_EP_FRAG_ORDER16(f_) ((f_) == 0 ? MB16 : (f_) <= MB16 ? (f_) - 1 : (f_))
 #define MOE_EP_STEP16(prefetch_)                                                                  \
     {                                                                                             \
