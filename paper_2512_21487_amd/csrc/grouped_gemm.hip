@@ -848,14 +848,17 @@ static hipError_t launch_cfg(const GemmArgs& a, bool swiglu, int n_cu, long long
     return go(std::false_type{});
 }
 
-// tile variants: id, BM, BN, BK, ring slots, wavefronts in m, in n
+// tile variants: id, BM, BN, BK, ring slots, wavefronts in m, in n, fall-back, tile-order weights, block rows
 // (0: short row tiles; with exactly 16 rows per expert they stream the weights 13 % faster than
 // the 128-row tiles, with the ragged counts of real routing they do not, so nothing selects them by
 // default).  BM is the tallest tile of a variant: over ragged groups the tiles are cut to fit the group
 // (cut_group) in units of 32 rows per row of wavefronts.  A ring of S slots needs K >= S * BK; for a
 // shorter K the launcher takes the two-slot variant with 32-wide K steps (K is a multiple of 64)
-// listed in the column before the last.  Last column: the variant is also built for weights in tile
+// listed in the eighth column.  Ninth column: the variant is also built for weights in tile
 // order (kernels.h: the shapes the library picks by itself; the others read the caller's layout).
+// Last column: rows of the matrix instruction's block, 32 (v_mfma_f32_32x32x16_bf16) or 16
+// (v_mfma_f32_16x16x32_bf16; 64-wide K steps only, so their fall-backs for a short K are 32-row
+// variants).  21, 22 and 31 are 1, 2 and 11 with 16-row blocks: what the library picks by itself.
 #define MOE_EP_VARIANTS(X)         \
     X(0, 64, 128, 64, 2, 1, 2, 8, false, 32)  \
     X(1, 128, 256, 64, 3, 2, 2, 6, true, 32) \
