@@ -750,6 +750,14 @@ def _full_size_parity(name, variants, pinned=False, seed=0, tile_variants=()):
             out = g.run_forward(vctx, wl, d, r=1, order=0)
             vctx.destroy()
         assert np.array_equal(out, first), f"tile variant {tv} changed the output bits"
+    if tile_variants:                              # every projection out of the 32 x 32 x 16 instruction: the same bits
+        print(f"[case] {name} MOE_EP_MFMA=32", flush=True)
+        with _env(MOE_EP_MFMA=32):
+            vctx = g.make_ctx(wl, pinned=pinned)
+            out = g.run_forward(vctx, wl, d, r=1, order=0)
+            assert vctx.last_tile_shape("routed_gate_up_gemm")["mfma_rows"] == 32
+            vctx.destroy()
+        assert np.array_equal(out, first), "the 32 x 32 x 16 kernels changed the output bits"
 
 
 def _sweep(wl, orders=(0,)):
@@ -763,20 +771,20 @@ def _sweep(wl, orders=(0,)):
 
 
 def test_dsv2_lite_full_size():
-    _full_size_parity("dsv2_lite", _sweep(CONFIGS["dsv2_lite"]), tile_variants=(1, 11))
+    _full_size_parity("dsv2_lite", _sweep(CONFIGS["dsv2_lite"]), tile_variants=(1, 11, 21, 31))
 
 
 def test_qwen3_30b_full_size_skewed():
-    _full_size_parity("qwen3_30b", _sweep(CONFIGS["qwen3_30b"]), tile_variants=(1, 11))
+    _full_size_parity("qwen3_30b", _sweep(CONFIGS["qwen3_30b"]), tile_variants=(1, 11, 21, 31))
 
 
 def test_dsv2_expert_group_share_full_size():
-    _full_size_parity("dsv2_eg", _sweep(CONFIGS["dsv2_eg"]), tile_variants=(1, 11))
+    _full_size_parity("dsv2_eg", _sweep(CONFIGS["dsv2_eg"]), tile_variants=(1, 11, 21, 31))
 
 
 @pytest.mark.parametrize("name", ["qwen3_235b_eg_256", "qwen3_235b_eg_1024", "qwen3_235b_eg_4096"])
 def test_qwen3_235b_expert_group_share_decode_pinned(name):
-    _full_size_parity(name, _sweep(CONFIGS[name]), pinned=True, tile_variants=(1, 11))
+    _full_size_parity(name, _sweep(CONFIGS[name]), pinned=True, tile_variants=(1, 11, 21, 31))
 
 
 @pytest.mark.parametrize("seed", [1, 2, 3])
