@@ -329,7 +329,7 @@ def main() -> int:
     timed_stages = sorted({dominant, "routed_gate_up_gemm", "routed_down_gemm"})
     if not args.no_stage_timing:
         ctx.set_profiling_stages(timed_stages + ["forward"])   # + one event pair around every forward
-        ctx.set_profiling(args.steps)
+        ctx.set_profiling(min(args.steps, 256))   # the library keeps events of at most 256 forwards
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
@@ -346,7 +346,7 @@ def main() -> int:
         # Second pass, outside the timed region: the same forwards with events around every stage
         # (the per-stage breakdown; its "forward" is a little longer than ms_per_step for that reason).
         ctx.set_profiling_stages(None)
-        ctx.set_profiling(args.steps)
+        ctx.set_profiling(min(args.steps, 256))   # the library keeps events of at most 256 forwards
         for _ in range(args.steps):
             step()
         stages = ctx.get_stage_ms()
